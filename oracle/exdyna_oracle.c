@@ -1,0 +1,317 @@
+/*
+ * CPU oracle for ExDyna's per-iteration gradient-selection path.
+ * TEST INFRASTRUCTURE ONLY -- see exdyna_oracle.h.
+ *
+ * Written from the paper's definitions, one plain loop per statement, in
+ * the paper's order.  No blocking, fusion or threading.
+ * Build: gcc -O2 -std=c99 -ffp-contract=off -fno-fast-math -shared -fPIC
+ */
+#include "exdyna_oracle.h"
+
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* ------------------------------------------------------------------ */
+/* Alg. 2, lines 1-2                                                   */
+uint64_t exo_block_size(uint64_t n_g, uint64_t n_b)
+{
+    if (n_b == 0) return 0;
+    uint64_t temp = n_g / n_b;
+    return temp - temp % 32;
+}
+
+/* Alg. 2, lines 3-17                                                  */
+void exo_partition(uint64_t n_b, uint32_t n, int64_t *blk_part, int64_t *blk_pos)
+{
+    int64_t quotient  = (int64_t)(n_b / n);
+    int64_t remainder = (int64_t)(n_b % n);
+    for (uint32_t i = 0; i < n; ++i) {
+        blk_pos[i] = 0;
+        if ((int64_t)i < remainder)
+            blk_part[i] = quotient + 1;
+        else
+            blk_part[i] = quotient;
+    }
+    for (uint32_t i = 1; i < n; ++i)
+        blk_pos[i] = blk_part[i - 1] + blk_pos[i - 1];
+}
+
+/* Alg. 3, lines 8-28.  The re-indexing of k_t from rank order to partition
+ * order (lines 2-7) is done by the caller: here kvec is already indexed by
+ * partition.                                                           */
+int exo_allocate(double *kvec, int64_t *blk_part, int64_t *blk_pos, uint32_t n,
+                 uint64_t n_g, uint64_t sz_blk, int64_t blk_move, int64_t min_blk,
+                 double alpha)
+{
+    double sum = 0.0;
+    for (uint32_t i = 0; i < n; ++i) sum += kvec[i];
+    /* Nothing selected: det would be 0/0.  No adjustment is made. */
+    if (!(sum > 0.0)) return 0;
+
+    double pk_prev   = sum / (double)n;
+    double den_prev  = sum / (double)n_g;
+    double inv_alpha = 1.0 / alpha;
+    int moves = 0;
+
+    for (uint32_t i = 0; i + 1 < n; ++i) {
+        double det    = kvec[i] / pk_prev;
+        double det2   = kvec[i + 1] / pk_prev;
+        double k_move = (double)blk_move * (double)sz_blk * den_prev;
+        if (det > alpha && det2 < inv_alpha) {
+            if (blk_part[i] - blk_move < min_blk) continue;
+            blk_part[i]     -= blk_move;
+            blk_part[i + 1] += blk_move;
+            blk_pos[i + 1]  -= blk_move;
+            kvec[i]         -= k_move;
+            kvec[i + 1]     += k_move;
+            ++moves;
+        }
+        if (det < inv_alpha && det2 > alpha) {
+            if (blk_part[i + 1] - blk_move < min_blk) continue;
+            blk_part[i]     += blk_move;
+            blk_part[i + 1] -= blk_move;
+            blk_pos[i + 1]  += blk_move;
+            kvec[i]         += k_move;
+            kvec[i + 1]     -= k_move;
+            ++moves;
+        }
+    }
+    return moves;
+}
+
+/* Alg. 3, line 29                                                     */
+uint32_t exo_owner(uint64_t t, uint32_t rank, uint32_t n)
+{
+    return (uint32_t)((t % n + rank) % n);
+}
+
+/* Alg. 4: where(|g[st:end]| >= delta) + st                            */
+uint64_t exo_select(const float *acc, uint64_t st, uint64_t end, float delta,
+                    int cmp_mode, uint32_t *out_idx, uint64_t cap)
+{
+    uint64_t count = 0;
+    for (uint64_t i = st; i < end; ++i) {
+        float a = fabsf(acc[i]);
+        int sel = cmp_mode ? (a > delta) : (a >= delta);
+        if (sel) {
+            if (count < cap) out_idx[count] = (uint32_t)i;
+            ++count;
+        }
+    }
+    return count;
+}
+
+/* Alg. 5, lines 1-7                                                   */
+float exo_scale_factor(double k, double k_actual, double beta, double gamma)
+{
+    double exam = k_actual / k;
+    double sf;
+    if (exam > beta)
+        sf = 1.0 + gamma;
+    else if (exam > 1.0 / beta)
+        sf = 1.0 + 0.25 * gamma;
+    else
+        sf = 1.0 - gamma;
+    return (float)sf;
+}
+
+/* Alg. 5, line 8                                                      */
+float exo_estimate(double k, double k_actual, float delta, double beta, double gamma)
+{
+    float sf = exo_scale_factor(k, k_actual, beta, gamma);
+    return delta * sf;
+}
+
+/* ------------------------------------------------------------------ */
+struct exo_state {
+    uint64_t n_g, n_b, cap, t;
+    uint32_t b, n, blk_move, min_blk, cmp_mode;
+    double   k, alpha, beta, gamma;
+    float    delta, delta_used;
+    float   *e;                  /* residual; holds acc during a step */
+    double  *kvec;               /* partial-k vector, partition order */
+    int64_t *blk_part, *blk_pos; /* current topology */
+    int64_t *used_part, *used_pos; /* topology the last step selected with */
+    uint32_t *out_idx;
+    float    *out_val;
+    uint64_t *part_off, *part_cnt;
+    uint32_t *blk_cnt;
+    uint64_t k_actual, k_emitted;
+};
+
+exo_state *exo_create(uint64_t n_g, uint32_t block_size, uint32_t n_parts,
+                      double density, float threshold0, double alpha, double beta,
+                      double gamma, uint32_t blk_move, uint32_t min_blk,
+                      uint32_t cmp_mode, uint64_t cap)
+{
+    if (n_g == 0 || n_g > 0xFFFFFFFFull) return NULL;
+    if (block_size == 0 || block_size % 32 != 0) return NULL;
+    uint64_t n_b = (n_g + block_size - 1) / block_size;
+    if (n_parts == 0 || n_parts > n_b) return NULL;
+    if (!(density > 0.0 && density <= 1.0)) return NULL;
+    if (!(threshold0 > 0.0f) || isinf(threshold0)) return NULL;
+    if (!(alpha >= 1.0) || !(beta > 1.0) || !(gamma > 0.0 && gamma < 1.0)) return NULL;
+    if (min_blk == 0 || cmp_mode > 1) return NULL;
+
+    exo_state *s = (exo_state *)calloc(1, sizeof *s);
+    if (!s) return NULL;
+    s->n_g = n_g; s->b = block_size; s->n = n_parts; s->n_b = n_b;
+    s->k = density * (double)n_g;
+    s->alpha = alpha; s->beta = beta; s->gamma = gamma;
+    s->blk_move = blk_move; s->min_blk = min_blk; s->cmp_mode = cmp_mode;
+    if (cap == 0) {
+        double c = ceil(4.0 * s->k);
+        cap = c < 1024.0 ? 1024 : (uint64_t)c;
+    }
+    if (cap > n_g) cap = n_g;
+    s->cap = cap;
+    s->delta = threshold0;          /* Alg. 1 line 5 */
+    s->delta_used = threshold0;
+    s->t = 0;
+
+    s->e         = (float *)calloc(n_g, sizeof(float));        /* Alg. 1 line 3 */
+    s->kvec      = (double *)malloc(n_parts * sizeof(double));
+    s->blk_part  = (int64_t *)malloc(n_parts * sizeof(int64_t));
+    s->blk_pos   = (int64_t *)malloc(n_parts * sizeof(int64_t));
+    s->used_part = (int64_t *)malloc(n_parts * sizeof(int64_t));
+    s->used_pos  = (int64_t *)malloc(n_parts * sizeof(int64_t));
+    s->out_idx   = (uint32_t *)malloc(cap * sizeof(uint32_t));
+    s->out_val   = (float *)malloc(cap * sizeof(float));
+    s->part_off  = (uint64_t *)calloc(n_parts + 1, sizeof(uint64_t));
+    s->part_cnt  = (uint64_t *)calloc(n_parts, sizeof(uint64_t));
+    s->blk_cnt   = (uint32_t *)calloc(n_b, sizeof(uint32_t));
+    if (!s->e || !s->kvec || !s->blk_part || !s->blk_pos || !s->used_part ||
+        !s->used_pos || !s->out_idx || !s->out_val || !s->part_off ||
+        !s->part_cnt || !s->blk_cnt) {
+        exo_destroy(s);
+        return NULL;
+    }
+    for (uint32_t i = 0; i < n_parts; ++i)                      /* Alg. 1 line 4 */
+        s->kvec[i] = s->k / (double)n_parts;
+    exo_partition(n_b, n_parts, s->blk_part, s->blk_pos);       /* Alg. 1 line 6 */
+    memcpy(s->used_part, s->blk_part, n_parts * sizeof(int64_t));
+    memcpy(s->used_pos, s->blk_pos, n_parts * sizeof(int64_t));
+    return s;
+}
+
+void exo_destroy(exo_state *s)
+{
+    if (!s) return;
+    free(s->e); free(s->kvec); free(s->blk_part); free(s->blk_pos);
+    free(s->used_part); free(s->used_pos); free(s->out_idx); free(s->out_val);
+    free(s->part_off); free(s->part_cnt); free(s->blk_cnt);
+    free(s);
+}
+
+void exo_step(exo_state *s, const float *g)
+{
+    const uint64_t n_g = s->n_g;
+    const uint32_t n = s->n;
+    float *acc = s->e;
+
+    /* Alg. 1 line 7: acc = e + g (g carries the learning rate already). */
+    for (uint64_t i = 0; i < n_g; ++i) {
+        float a = acc[i] + g[i];
+        acc[i] = a;
+    }
+
+    /* Alg. 1 line 8: Allocate adjusts the topology from last iteration's
+     * per-partition counts; selection below uses the adjusted topology. */
+    exo_allocate(s->kvec, s->blk_part, s->blk_pos, n, n_g, s->b,
+                 (int64_t)s->blk_move, (int64_t)s->min_blk, s->alpha);
+    memcpy(s->used_part, s->blk_part, n * sizeof(int64_t));
+    memcpy(s->used_pos, s->blk_pos, n * sizeof(int64_t));
+
+    /* Alg. 1 lines 9-11: every partition is selected by exactly one worker
+     * (Alg. 3 line 29 is a bijection rank -> partition at fixed t), so on
+     * one device the gathered index list is the partitions' lists; they are
+     * laid out here in ascending partition order. */
+    const float delta = s->delta;
+    s->delta_used = delta;
+    memset(s->blk_cnt, 0, s->n_b * sizeof(uint32_t));
+    uint64_t emitted = 0, total = 0;
+    for (uint32_t p = 0; p < n; ++p) {
+        /* Alg. 3 lines 30-31, with the last block allowed to be short. */
+        uint64_t st  = (uint64_t)s->used_pos[p] * s->b;
+        uint64_t end = (uint64_t)(s->used_pos[p] + s->used_part[p]) * s->b;
+        if (end > n_g) end = n_g;
+        if (st > n_g) st = n_g;
+        s->part_off[p] = emitted;
+        uint64_t room = s->cap - emitted;
+        /* Alg. 4 */
+        uint64_t cnt = exo_select(acc, st, end, delta, (int)s->cmp_mode,
+                                  s->out_idx + emitted, room);
+        uint64_t take = cnt < room ? cnt : room;
+        /* per-block counts (scaffold for the device compaction; untruncated) */
+        for (uint64_t i = st; i < end; ++i) {
+            float a = fabsf(acc[i]);
+            int sel = s->cmp_mode ? (a > delta) : (a >= delta);
+            if (sel) s->blk_cnt[i / s->b] += 1;
+        }
+        /* Alg. 1 line 11: values at the selected indices. */
+        for (uint64_t j = 0; j < take; ++j)
+            s->out_val[emitted + j] = acc[s->out_idx[emitted + j]];
+        s->part_cnt[p] = cnt;
+        emitted += take;
+        total += cnt;
+    }
+    s->part_off[n] = emitted;
+    s->k_actual = total;        /* Alg. 1 line 13 */
+    s->k_emitted = emitted;
+
+    /* Alg. 1 line 14: Estimate. */
+    s->delta = exo_estimate(s->k, (double)total, delta, s->beta, s->gamma);
+
+    /* Alg. 1 lines 10/15: the partial-k vector for the next Allocate. */
+    for (uint32_t p = 0; p < n; ++p) s->kvec[p] = (double)s->part_cnt[p];
+
+    /* Alg. 1 line 17: zero what was sent (only what fitted the output). */
+    for (uint64_t j = 0; j < emitted; ++j) acc[s->out_idx[j]] = 0.0f;
+
+    /* Alg. 1 line 18: e_{t+1} = acc (same buffer). */
+    s->t += 1;
+}
+
+uint64_t        exo_n_blocks(const exo_state *s)       { return s->n_b; }
+uint64_t        exo_capacity(const exo_state *s)       { return s->cap; }
+uint64_t        exo_iteration(const exo_state *s)      { return s->t; }
+float           exo_threshold(const exo_state *s)      { return s->delta; }
+float           exo_threshold_used(const exo_state *s) { return s->delta_used; }
+float          *exo_residual(exo_state *s)             { return s->e; }
+const uint32_t *exo_out_idx(const exo_state *s)        { return s->out_idx; }
+const float    *exo_out_val(const exo_state *s)        { return s->out_val; }
+const uint64_t *exo_part_off(const exo_state *s)       { return s->part_off; }
+const uint64_t *exo_part_count(const exo_state *s)     { return s->part_cnt; }
+const uint32_t *exo_block_count(const exo_state *s)    { return s->blk_cnt; }
+uint64_t        exo_k_actual(const exo_state *s)       { return s->k_actual; }
+uint64_t        exo_k_emitted(const exo_state *s)      { return s->k_emitted; }
+const int64_t  *exo_blk_part(const exo_state *s, int which) { return which ? s->blk_part : s->used_part; }
+const int64_t  *exo_blk_pos(const exo_state *s, int which)  { return which ? s->blk_pos : s->used_pos; }
+
+/* Eq. 1 with one worker: the L2 norm of the residual, summed in fp64. */
+double exo_err_norm(const exo_state *s)
+{
+    double acc = 0.0;
+    for (uint64_t i = 0; i < s->n_g; ++i) {
+        double v = (double)s->e[i];
+        acc += v * v;
+    }
+    return sqrt(acc);
+}
+
+/* Eq. 6: |k - k'| / n_g */
+double exo_density_error(const exo_state *s)
+{
+    return fabs(s->k - (double)s->k_actual) / (double)s->n_g;
+}
+
+/* Eq. 5: n * max_i k_i / k' */
+double exo_traffic_ratio(const exo_state *s)
+{
+    if (s->k_actual == 0) return 0.0;
+    uint64_t m = 0;
+    for (uint32_t p = 0; p < s->n; ++p)
+        if (s->part_cnt[p] > m) m = s->part_cnt[p];
+    return (double)s->n * (double)m / (double)s->k_actual;
+}
