@@ -1,0 +1,163 @@
+/*
+ * exdyna.h -- C ABI of the MI355X (gfx950) ExDyna gradient-selection library.
+ *
+ * One `exdyna_step` is one iteration of the sparsifier of "Distributed SGD
+ * with ExDyna" (Alg. 1, lines 7-18) on ONE device that plays all P workers:
+ *   acc = residual + grad                         (Alg. 1 line 7, Sec. 2)
+ *   select |acc| >= delta inside every partition  (Alg. 4, Sec. 4.3)
+ *   emit (index, value) pairs, ascending          (Alg. 1 lines 9-11)
+ *   residual = acc with the emitted entries zeroed (Alg. 1 lines 17-18)
+ *   delta   <- online threshold scaling           (Alg. 5, Sec. 4.4)
+ *   topology <- adjacent-partition rebalancing    (Alg. 3 lines 8-28, Sec. 4.2)
+ * The collectives of Alg. 1 (lines 10, 12) and the model update (line 16) are
+ * not part of this library.
+ *
+ * Conventions
+ *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.
+ *  - The caller owns d_grad, d_residual, d_workspace and the HIP stream; the
+ *    library owns only the host-side context.  The library never allocates
+ *    device memory.
+ *  - Every call returns EXDYNA_OK (0) or a negative error; nothing throws or
+ *    aborts.  Arguments are validated on the host before anything is launched.
+ *  - exdyna_step only enqueues work on `hip_stream` and never synchronises.
+ *    The getters that fill host memory synchronise that stream.
+ *  - One context must not be used from two host threads at once, and steps of
+ *    one context must all be enqueued on streams that are ordered with respect
+ *    to each other.
+ */
+#ifndef EXDYNA_H
+#define EXDYNA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    EXDYNA_OK      = 0,
+    EXDYNA_EINVAL  = -1, /* a configuration value is out of range            */
+    EXDYNA_ENULL   = -2, /* a required pointer is NULL                       */
+    EXDYNA_EALIGN  = -3, /* a device pointer is not aligned as required      */
+    EXDYNA_ESTATE  = -4, /* context is not initialised / already destroyed / no step run yet */
+    EXDYNA_ENOMEM  = -5, /* workspace too small, or host allocation failed   */
+    EXDYNA_EHIP    = -6  /* a HIP runtime call failed (see exdyna_last_hip_error) */
+};
+
+typedef struct exdyna_ctx exdyna_ctx; /* opaque, host memory, library-owned */
+
+/* Problem statement of Alg. 1 / Alg. 3 / Alg. 5.  The paper names alpha, beta,
+ * gamma, blk_move and min_blk but gives them no values; exdyna_default_config
+ * fills this build's defaults. */
+typedef struct {
+    uint64_t n_g;          /* number of gradients, 1 <= n_g < 2^32 (indices are u32)        */
+    uint32_t block_size;   /* b: gradients per block, > 0 and a multiple of 256 (Sec. 4.1;
+                              the paper's granularity is 32, one wavefront x float4 is 256)  */
+    uint32_t n_parts;      /* P = number of workers n, 1 <= P <= min(n_b, 1024)             */
+    double   density;      /* d in (0, 1]; k = d * n_g is kept in fp64 (Sec. 1)             */
+    float    threshold0;   /* delta_0 > 0, finite (Alg. 1 line 5)                           */
+    uint32_t cmp_mode;     /* 0: |acc| >= delta (Alg. 4 line 2); 1: |acc| > delta           */
+    double   alpha;        /* >= 1, imbalance band of Alg. 3 lines 13/21                    */
+    double   beta;         /* > 1, density band of Alg. 5 lines 2/4                         */
+    double   gamma;        /* in (0, 1), threshold step of Alg. 5 lines 3-7                 */
+    uint32_t blk_move;     /* blocks moved per adjustment (Alg. 3 line 12); 0 = static      */
+    uint32_t min_blk;      /* >= 1, smallest partition in blocks (Alg. 3 lines 14/22)       */
+    uint64_t max_selected; /* output capacity in pairs; 0 = max(ceil(4k), 1024), <= n_g     */
+    uint32_t want_err_norm;/* != 0: also compute ||residual||_2 (Eq. 1, one worker)         */
+    uint32_t reserved;     /* must be 0                                                     */
+} exdyna_config;
+
+/* Per-step scalars, all produced on the device by the control kernel. */
+typedef struct {
+    uint64_t t;             /* iterations completed                                         */
+    uint64_t k_actual;      /* k' = number of gradients that passed the comparison          */
+    uint64_t k_emitted;     /* min(k', capacity): pairs actually written and zeroed         */
+    uint64_t k_max_part;    /* m_t = max_p k_{p,t} (Eq. 2)                                  */
+    double   density_error; /* eps_t = |k - k'| / n_g (Eq. 6)                               */
+    double   traffic_ratio; /* f(t) = P * m_t / k' (Eq. 5); 0 when k' = 0                   */
+    double   err_norm;      /* ||e_{t+1}||_2 (Eq. 1 with one worker); -1 when not requested */
+    float    delta_used;    /* delta_t the step compared with                               */
+    float    delta_next;    /* delta_{t+1} (Alg. 5 line 8)                                  */
+    uint32_t overflow;      /* 1 when k' > capacity                                         */
+    uint32_t moves;         /* boundary moves Alg. 3 made for the next iteration            */
+} exdyna_stats;
+
+/* Fill *cfg with defaults: alpha 1.0, beta 1.1, gamma 0.01, blk_move 1,
+ * min_blk 1, cmp_mode 0, max_selected 0, want_err_norm 0.  n_g, block_size,
+ * n_parts, density and threshold0 are left 0 for the caller to set. */
+int exdyna_default_config(exdyna_config *cfg);
+
+/* Alg. 2 lines 1-2, for callers that think in a block count n_b: floor(n_g /
+ * n_b) rounded down to the granularity `multiple` (the paper uses 32; this
+ * library's kernels need 256).  Writes 0 when fewer than `multiple` gradients
+ * would fall in a block.  Host only. */
+int exdyna_block_size_from_nb(uint64_t n_g, uint64_t n_b, uint32_t multiple, uint32_t *h_block_size);
+
+/* Bytes of device workspace exdyna_init needs for this configuration
+ * (state, per-block counters and offsets, the 1-bit-per-gradient selection
+ * mask, and the output pairs).  Host only, launches nothing. */
+int exdyna_workspace_bytes(const exdyna_config *cfg, size_t *h_bytes);
+
+/* Alg. 1 lines 3-6: residual <- 0, partial-k vector <- k/P, delta <- delta_0,
+ * topology <- Alg. 2.  d_residual: n_g floats, 16-byte aligned, zeroed here
+ * and updated in place by every step.  d_workspace: 256-byte aligned,
+ * ws_bytes >= exdyna_workspace_bytes().  Both must stay valid until
+ * exdyna_destroy.  Work is enqueued on hip_stream (a hipStream_t; NULL = the
+ * default stream).  *out receives the context. */
+int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
+                void *d_workspace, size_t ws_bytes, void *hip_stream);
+
+/* One iteration (see the top of this file).  d_grad: n_g floats, 16-byte
+ * aligned, read only, already scaled by the learning rate (the accumulate is a
+ * single fp32 add).  Asynchronous: returns after enqueueing three kernels. */
+int exdyna_step(exdyna_ctx *ctx, const float *d_grad, void *hip_stream);
+
+/* Results of the last step.  *d_idx / *d_val: device arrays of k_emitted
+ * ascending gradient indices and the accumulated values at them (Alg. 1 lines
+ * 9-11); *d_part_off: device array of P+1 offsets, partition p's pairs are
+ * [part_off[p], part_off[p+1]).  They point into the workspace and are
+ * overwritten by the next step.  Any of the three may be NULL.  If h_k_actual
+ * or h_k_emitted is non-NULL the stream is synchronised and the counts are
+ * copied to the host. */
+int exdyna_get_selected(exdyna_ctx *ctx, const uint32_t **d_idx, const float **d_val,
+                        const uint64_t **d_part_off, uint64_t *h_k_actual, uint64_t *h_k_emitted);
+
+/* Topology (Alg. 2 / Alg. 3): which = 0 is what the last step selected with,
+ * which = 1 what the next step will select with.  Host arrays of P entries
+ * each; any may be NULL.  h_elem_end is clamped to n_g (the last block may be
+ * short).  h_owner_rank[p] is the worker that owns partition p at that
+ * iteration under the cyclic rule of Alg. 3 line 29.  Synchronises. */
+int exdyna_get_partitions(exdyna_ctx *ctx, int which, uint32_t *h_blk_pos, uint32_t *h_blk_part,
+                          uint64_t *h_elem_start, uint64_t *h_elem_end, uint32_t *h_owner_rank);
+
+/* Untruncated per-block counts of the last step (n_b entries) and
+ * per-partition counts k_{p,t} (P entries).  Synchronise. */
+int exdyna_get_block_counts(exdyna_ctx *ctx, uint32_t *h_counts);
+int exdyna_get_part_counts(exdyna_ctx *ctx, uint64_t *h_counts);
+
+/* Scalars of the last step.  Synchronises. */
+int exdyna_get_stats(exdyna_ctx *ctx, exdyna_stats *h_out);
+
+/* Capacity and block count the context was created with.  Host only. */
+int exdyna_get_dims(const exdyna_ctx *ctx, uint64_t *h_n_blocks, uint64_t *h_capacity);
+
+/* Per-kernel timing for benchmarks: when enabled, exdyna_step records HIP
+ * events around its three kernels on the step's stream;
+ * exdyna_get_kernel_ms synchronises and returns the last step's durations in
+ * milliseconds: [0] streaming pass, [1] control, [2] compaction. */
+int exdyna_set_profiling(exdyna_ctx *ctx, int enable);
+int exdyna_get_kernel_ms(exdyna_ctx *ctx, float *h_ms3);
+
+const char *exdyna_strerror(int code);
+/* Text of the last HIP error seen by this context's calls ("" if none). */
+const char *exdyna_last_hip_error(const exdyna_ctx *ctx);
+
+/* Frees the host context.  Does not touch device memory; the caller must make
+ * sure the stream has drained before freeing d_residual / d_workspace. */
+int exdyna_destroy(exdyna_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

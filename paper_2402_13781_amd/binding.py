@@ -1,0 +1,244 @@
+"""Thin ctypes binding over libexdyna.so (the C ABI declared in include/exdyna.h).
+
+Argument marshalling only.  torch supplies device memory (gradient, residual,
+workspace) and the HIP stream; every step of the path runs in the library's
+kernels.  There is no CPU fallback: a missing library raises at first use.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libexdyna.so")
+
+EXDYNA_OK, EXDYNA_EINVAL, EXDYNA_ENULL, EXDYNA_EALIGN, EXDYNA_ESTATE, EXDYNA_ENOMEM, EXDYNA_EHIP = (
+    0, -1, -2, -3, -4, -5, -6)
+
+# every symbol include/exdyna.h declares
+SYMBOLS = (
+    "exdyna_default_config", "exdyna_block_size_from_nb", "exdyna_workspace_bytes", "exdyna_init",
+    "exdyna_step", "exdyna_get_selected", "exdyna_get_partitions", "exdyna_get_block_counts",
+    "exdyna_get_part_counts", "exdyna_get_stats", "exdyna_get_dims", "exdyna_set_profiling",
+    "exdyna_get_kernel_ms", "exdyna_strerror", "exdyna_last_hip_error", "exdyna_destroy",
+)
+
+
+class Config(C.Structure):
+    _fields_ = [
+        ("n_g", C.c_uint64), ("block_size", C.c_uint32), ("n_parts", C.c_uint32),
+        ("density", C.c_double), ("threshold0", C.c_float), ("cmp_mode", C.c_uint32),
+        ("alpha", C.c_double), ("beta", C.c_double), ("gamma", C.c_double),
+        ("blk_move", C.c_uint32), ("min_blk", C.c_uint32), ("max_selected", C.c_uint64),
+        ("want_err_norm", C.c_uint32), ("reserved", C.c_uint32),
+    ]
+
+
+class Stats(C.Structure):
+    _fields_ = [
+        ("t", C.c_uint64), ("k_actual", C.c_uint64), ("k_emitted", C.c_uint64),
+        ("k_max_part", C.c_uint64), ("density_error", C.c_double), ("traffic_ratio", C.c_double),
+        ("err_norm", C.c_double), ("delta_used", C.c_float), ("delta_next", C.c_float),
+        ("overflow", C.c_uint32), ("moves", C.c_uint32),
+    ]
+
+
+class ExDynaError(RuntimeError):
+    def __init__(self, code: int, what: str, detail: str = ""):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code}){' -- ' + detail if detail else ''}")
+
+
+_lib = None
+
+
+def load() -> C.CDLL:
+    """Load libexdyna.so; raises if it has not been built (no fallback)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2402_13781_amd.build` "
+            "(hipcc --offload-arch=gfx950).  There is no CPU fallback.")
+    L = C.CDLL(LIB_PATH)
+    vp, u64, u32, P = C.c_void_p, C.c_uint64, C.c_uint32, C.POINTER
+    L.exdyna_default_config.argtypes = [P(Config)]
+    L.exdyna_block_size_from_nb.argtypes = [u64, u64, u32, P(u32)]
+    L.exdyna_workspace_bytes.argtypes = [P(Config), P(C.c_size_t)]
+    L.exdyna_init.argtypes = [P(vp), P(Config), vp, vp, C.c_size_t, vp]
+    L.exdyna_step.argtypes = [vp, vp, vp]
+    L.exdyna_get_selected.argtypes = [vp, P(vp), P(vp), P(vp), P(u64), P(u64)]
+    L.exdyna_get_partitions.argtypes = [vp, C.c_int, P(u32), P(u32), P(u64), P(u64), P(u32)]
+    L.exdyna_get_block_counts.argtypes = [vp, P(u32)]
+    L.exdyna_get_part_counts.argtypes = [vp, P(u64)]
+    L.exdyna_get_stats.argtypes = [vp, P(Stats)]
+    L.exdyna_get_dims.argtypes = [vp, P(u64), P(u64)]
+    L.exdyna_set_profiling.argtypes = [vp, C.c_int]
+    L.exdyna_get_kernel_ms.argtypes = [vp, P(C.c_float)]
+    L.exdyna_strerror.argtypes = [C.c_int]
+    L.exdyna_strerror.restype = C.c_char_p
+    L.exdyna_last_hip_error.argtypes = [vp]
+    L.exdyna_last_hip_error.restype = C.c_char_p
+    L.exdyna_destroy.argtypes = [vp]
+    for name in SYMBOLS:
+        fn = getattr(L, name)
+        if name not in ("exdyna_strerror", "exdyna_last_hip_error"):
+            fn.restype = C.c_int
+    _lib = L
+    return L
+
+
+def strerror(code: int) -> str:
+    return load().exdyna_strerror(code).decode()
+
+
+def default_config(**kw) -> Config:
+    cfg = Config()
+    rc = load().exdyna_default_config(C.byref(cfg))
+    if rc:
+        raise ExDynaError(rc, "exdyna_default_config")
+    for k, v in kw.items():
+        if not hasattr(cfg, k):
+            raise AttributeError(k)
+        setattr(cfg, k, v)
+    return cfg
+
+
+def block_size_from_nb(n_g: int, n_b: int, multiple: int = 256) -> int:
+    out = C.c_uint32()
+    rc = load().exdyna_block_size_from_nb(n_g, n_b, multiple, C.byref(out))
+    if rc:
+        raise ExDynaError(rc, "exdyna_block_size_from_nb")
+    return out.value
+
+
+def workspace_bytes(cfg: Config) -> int:
+    out = C.c_size_t()
+    rc = load().exdyna_workspace_bytes(C.byref(cfg), C.byref(out))
+    if rc:
+        raise ExDynaError(rc, "exdyna_workspace_bytes")
+    return out.value
+
+
+class ExDyna:
+    """One sparsifier context on the current torch device.
+
+    Owns (through torch) the residual vector and the workspace the library lays
+    its state, counters, selection mask and output pairs in.
+    """
+
+    def __init__(self, cfg: Config, device="cuda:0", stream=None):
+        import torch
+
+        self._torch = torch
+        self._L = load()
+        self.cfg = cfg
+        self.device = torch.device(device)
+        self._h = C.c_void_p()
+        nbytes = workspace_bytes(cfg)            # validates the configuration on the host
+        with torch.cuda.device(self.device):
+            self.residual = torch.empty(cfg.n_g, dtype=torch.float32, device=self.device)
+            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+            rc = self._L.exdyna_init(C.byref(self._h), C.byref(cfg), self.residual.data_ptr(),
+                                     self.workspace.data_ptr(), nbytes, self._stream_ptr(stream))
+        if rc:
+            raise ExDynaError(rc, "exdyna_init")
+        nb, cap = C.c_uint64(), C.c_uint64()
+        self._L.exdyna_get_dims(self._h, C.byref(nb), C.byref(cap))
+        self.n_blocks, self.capacity = nb.value, cap.value
+        self.P = cfg.n_parts
+
+    # -- plumbing ---------------------------------------------------------
+    def _stream_ptr(self, stream):
+        if stream is None:
+            stream = self._torch.cuda.current_stream(self.device)
+        return C.c_void_p(stream.cuda_stream)
+
+    def _check(self, rc, what):
+        if rc:
+            detail = self._L.exdyna_last_hip_error(self._h).decode() if rc == EXDYNA_EHIP else ""
+            raise ExDynaError(rc, what, detail)
+
+    def _view(self, ptr: int, n: int, dtype):
+        """A torch view of `n` items of the workspace starting at device address `ptr`."""
+        torch = self._torch
+        off = ptr - self.workspace.data_ptr()
+        item = torch.empty((), dtype=dtype).element_size()
+        assert 0 <= off and off + n * item <= self.workspace.numel()
+        return self.workspace[off: off + n * item].view(dtype)
+
+    def close(self):
+        if self._h:
+            self._torch.cuda.synchronize(self.device)
+            self._L.exdyna_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- the C ABI, same names ---------------------------------------------
+    def step(self, grad, stream=None):
+        """exdyna_step: enqueue one iteration on `grad` (n_g fp32 on this device)."""
+        torch = self._torch
+        if grad.dtype != torch.float32 or grad.device != self.device or not grad.is_contiguous() \
+                or grad.numel() != self.cfg.n_g:
+            raise ValueError("grad must be a contiguous fp32 tensor of n_g elements on the context's device")
+        self._check(self._L.exdyna_step(self._h, C.c_void_p(grad.data_ptr()), self._stream_ptr(stream)),
+                    "exdyna_step")
+
+    def get_selected(self):
+        """exdyna_get_selected: (idx[int32 view of u32], val[fp32], part_off[int64], k_actual, k_emitted)."""
+        torch = self._torch
+        pi, pv, po = C.c_void_p(), C.c_void_p(), C.c_void_p()
+        ka, ke = C.c_uint64(), C.c_uint64()
+        self._check(self._L.exdyna_get_selected(self._h, C.byref(pi), C.byref(pv), C.byref(po),
+                                                C.byref(ka), C.byref(ke)), "exdyna_get_selected")
+        idx = self._view(pi.value, ke.value, torch.int32)
+        val = self._view(pv.value, ke.value, torch.float32)
+        off = self._view(po.value, self.P + 1, torch.int64)
+        return idx, val, off, ka.value, ke.value
+
+    def get_partitions(self, which: int = 0):
+        """exdyna_get_partitions: dict of numpy arrays (blk_pos, blk_part, elem_start, elem_end, owner_rank)."""
+        import numpy as np
+        P = self.P
+        pos, part, own = (np.empty(P, np.uint32) for _ in range(3))
+        st, en = (np.empty(P, np.uint64) for _ in range(2))
+        u32p, u64p = C.POINTER(C.c_uint32), C.POINTER(C.c_uint64)
+        self._check(self._L.exdyna_get_partitions(
+            self._h, which, pos.ctypes.data_as(u32p), part.ctypes.data_as(u32p),
+            st.ctypes.data_as(u64p), en.ctypes.data_as(u64p), own.ctypes.data_as(u32p)),
+            "exdyna_get_partitions")
+        return dict(blk_pos=pos, blk_part=part, elem_start=st, elem_end=en, owner_rank=own)
+
+    def get_block_counts(self):
+        import numpy as np
+        out = np.empty(self.n_blocks, np.uint32)
+        self._check(self._L.exdyna_get_block_counts(self._h, out.ctypes.data_as(C.POINTER(C.c_uint32))),
+                    "exdyna_get_block_counts")
+        return out
+
+    def get_part_counts(self):
+        import numpy as np
+        out = np.empty(self.P, np.uint64)
+        self._check(self._L.exdyna_get_part_counts(self._h, out.ctypes.data_as(C.POINTER(C.c_uint64))),
+                    "exdyna_get_part_counts")
+        return out
+
+    def get_stats(self) -> Stats:
+        st = Stats()
+        self._check(self._L.exdyna_get_stats(self._h, C.byref(st)), "exdyna_get_stats")
+        return st
+
+    def set_profiling(self, enable: bool):
+        self._check(self._L.exdyna_set_profiling(self._h, int(enable)), "exdyna_set_profiling")
+
+    def get_kernel_ms(self):
+        out = (C.c_float * 3)()
+        self._check(self._L.exdyna_get_kernel_ms(self._h, out), "exdyna_get_kernel_ms")
+        return [out[0], out[1], out[2]]

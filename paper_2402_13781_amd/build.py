@@ -1,0 +1,43 @@
+"""Builds libexdyna.so (HIP kernels + C ABI) for gfx950 with hipcc, in-tree."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+SRC = os.path.join(HERE, "csrc", "exdyna.hip")
+INC = os.path.join(ROOT, "include")
+LIB = os.path.join(HERE, "libexdyna.so")
+
+
+def hipcc() -> str:
+    for cand in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
+        if cand and (os.path.isabs(cand) and os.path.exists(cand) or not os.path.isabs(cand)):
+            return cand
+    return "hipcc"
+
+
+def build(extra_defines=(), out: str = LIB, verbose: bool = False) -> str:
+    cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+           "-fno-fast-math", "-Wall", "-Wno-unused-command-line-argument",
+           # keep the compiler from forming packed-fp32 instructions
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", INC, "-o", out, SRC]
+    cmd += [f"-D{d}" for d in extra_defines]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    r = subprocess.run(cmd, capture_output=True, text=True)
+    noise = "is not a recognized feature for this target"
+    err = "\n".join(l for l in r.stderr.splitlines() if noise not in l)
+    if r.returncode != 0:
+        sys.stderr.write(r.stderr)
+        raise RuntimeError("hipcc failed building libexdyna.so")
+    if verbose and err.strip():
+        print(err)
+    return out
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

@@ -1,0 +1,886 @@
+// ExDyna gradient-selection hot path for MI355X (gfx950, wave64).
+//
+// Three kernels per iteration, all enqueued by exdyna_step with no host
+// round trip (threshold, topology and counters live in device memory):
+//
+//   k_stream   acc = e + g (Alg. 1 line 7), |acc| cmp delta (Alg. 4 line 2),
+//              1 bit per gradient into a selection mask, per-block popcounts.
+//              Pure streaming: 8 B read + 4 B written per gradient.
+//   k_control  one workgroup: exclusive scan of the per-block counts,
+//              per-partition counts k_{p,t} and k' (Alg. 1 lines 10, 13),
+//              threshold scaling (Alg. 5), adjacent-partition rebalancing
+//              (Alg. 3 lines 8-28), Eq. 2/5/6 statistics.
+//   k_compact  one wavefront per block: wave-level scan of mask popcounts ->
+//              stable ascending (index, value) pairs at the block's offset
+//              (Alg. 1 lines 9-11), zero of the residual at emitted entries
+//              (Alg. 1 line 17).  Touches only the mask and the selected
+//              cache lines, never the whole vector again.
+//
+// Partitions are contiguous and ascending (Sec. 4.1), so the concatenation of
+// the per-partition index lists in partition order is the global ascending
+// list: output positions come from one scan over blocks and partition p's
+// segment starts at the scan value of its first block.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+
+#include "exdyna.h"
+
+namespace {
+
+constexpr uint32_t kGran        = 256;  // gradients per wave-iteration: 64 lanes x float4
+constexpr uint32_t kGranWords   = 8;    // mask words per granule
+constexpr uint32_t kStreamWG    = 256;  // threads per workgroup in k_stream
+constexpr uint32_t kWavesPerWG  = 4;
+constexpr uint32_t kMaxParts    = 1024;
+constexpr uint32_t kCtrlThreads = 1024;
+constexpr uint32_t kErrSlots    = 256;
+constexpr uint64_t kMagic       = 0x45784479'6e61'0001ull;
+
+#ifndef EXDYNA_UNROLL
+#define EXDYNA_UNROLL 4
+#endif
+
+// Device-resident scalar state.  One instance at the start of the workspace.
+struct DevState {
+    float    delta;       // threshold the NEXT k_stream compares with
+    float    delta_used;  // threshold the last k_stream compared with
+    uint32_t overflow;
+    uint32_t moves;
+    uint64_t t;
+    uint64_t k_actual;
+    uint64_t k_emitted;
+    uint64_t k_max_part;
+    double   density_error;
+    double   traffic_ratio;
+    double   err_norm;
+};
+
+struct CtrlParams {
+    uint64_t n_g;
+    uint64_t cap;
+    double   k;          // d * n_g
+    double   alpha, inv_alpha, beta, inv_beta;
+    float    sf_hi, sf_mid, sf_lo;
+    uint32_t n_b, n_parts, block_size, blk_move, min_blk;
+};
+
+struct Layout {
+    size_t state, kvec, parts, part_cnt, part_off, blk_cnt, blk_off, err_slots, mask, out_idx,
+        out_val, total;
+    size_t mask_words;
+};
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------------------
+// device helpers
+
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v, uint32_t lane)
+{
+#pragma unroll
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+        uint32_t t = __shfl_up(v, d, 64);
+        if (lane >= d) v += t;
+    }
+    return v;
+}
+
+template <int CMP>
+__device__ __forceinline__ uint32_t sel(float a, float delta)
+{
+    // |NaN| never compares true, +-Inf always does.
+    return CMP ? (__builtin_fabsf(a) > delta) : (__builtin_fabsf(a) >= delta);
+}
+
+// Mask words and the block counter for one granule.  nib holds this lane's
+// four flags (bit q <-> gradient 4*lane + q of the granule).
+__device__ __forceinline__ void publish_granule(uint32_t gran, uint32_t nib, uint32_t lane,
+                                                uint32_t *__restrict__ mask,
+                                                uint32_t *__restrict__ blk_cnt,
+                                                uint32_t gran_per_blk)
+{
+    const uint64_t any = __ballot(nib != 0);
+    uint32_t *mw = mask + (size_t)gran * kGranWords;
+    if (any == 0) {
+        if (lane < kGranWords) mw[lane] = 0u;
+    } else {
+        // word q of the granule = flags of lanes 8q .. 8q+7, element order
+        uint32_t v = nib << ((lane & 7u) * 4u);
+        v |= __shfl_xor(v, 1, 64);
+        v |= __shfl_xor(v, 2, 64);
+        v |= __shfl_xor(v, 4, 64);
+        if ((lane & 7u) == 0) mw[lane >> 3] = v;
+        const uint32_t cnt = __popcll(__ballot(nib & 1u)) + __popcll(__ballot(nib & 2u)) +
+                             __popcll(__ballot(nib & 4u)) + __popcll(__ballot(nib & 8u));
+        if (lane == 0) atomicAdd(&blk_cnt[gran / gran_per_blk], cnt);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// k_stream: error-feedback accumulate + compare + mask + per-block popcount.
+// Workgroup w handles granules [w*4U, (w+1)*4U); at unroll step u wave v takes
+// granule w*4U + 4u + v, so the four waves read 4 KiB contiguous per step.
+template <int CMP, bool NORM, int U>
+__global__ void __launch_bounds__(kStreamWG)
+k_stream(const float *__restrict__ g, float *__restrict__ e, const DevState *__restrict__ st,
+         uint32_t *__restrict__ mask, uint32_t *__restrict__ blk_cnt,
+         double *__restrict__ err_slots, uint32_t n_g, uint32_t n_gran, uint32_t gran_per_blk)
+{
+    const float    delta  = st->delta;
+    const uint32_t lane   = threadIdx.x & 63u;
+    const uint32_t wave   = threadIdx.x >> 6;
+    const uint32_t gran0  = blockIdx.x * (kWavesPerWG * U);
+    const uint32_t n_full = n_g >> 8;  // complete granules
+    float nrm = 0.f;
+
+    if (gran0 + kWavesPerWG * U <= n_full) {
+        f32x4 gv[U], ev[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const size_t off = ((size_t)(gran0 + u * kWavesPerWG + wave) << 8) + lane * 4u;
+            gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g + off));
+            ev[u] = *reinterpret_cast<const f32x4 *>(e + off);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t gran = gran0 + u * kWavesPerWG + wave;
+            const size_t   off  = ((size_t)gran << 8) + lane * 4u;
+            f32x4 a;
+            a.x = ev[u].x + gv[u].x;
+            a.y = ev[u].y + gv[u].y;
+            a.z = ev[u].z + gv[u].z;
+            a.w = ev[u].w + gv[u].w;
+            *reinterpret_cast<f32x4 *>(e + off) = a;
+            const uint32_t nib = sel<CMP>(a.x, delta) | (sel<CMP>(a.y, delta) << 1) |
+                                 (sel<CMP>(a.z, delta) << 2) | (sel<CMP>(a.w, delta) << 3);
+            if (NORM) {
+                nrm += (nib & 1u) ? 0.f : a.x * a.x;
+                nrm += (nib & 2u) ? 0.f : a.y * a.y;
+                nrm += (nib & 4u) ? 0.f : a.z * a.z;
+                nrm += (nib & 8u) ? 0.f : a.w * a.w;
+            }
+            publish_granule(gran, nib, lane, mask, blk_cnt, gran_per_blk);
+        }
+    } else {
+        // Ragged end of the vector: guarded scalar accesses.
+        for (int u = 0; u < U; ++u) {
+            const uint32_t gran = gran0 + u * kWavesPerWG + wave;
+            if (gran >= n_gran) break;  // wave-uniform
+            const uint64_t base = ((uint64_t)gran << 8) + lane * 4u;
+            uint32_t nib = 0;
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint64_t i = base + q;
+                if (i < n_g) {
+                    const float a = e[i] + g[i];
+                    e[i] = a;
+                    const uint32_t f = sel<CMP>(a, delta);
+                    nib |= f << q;
+                    if (NORM) nrm += f ? 0.f : a * a;
+                }
+            }
+            publish_granule(gran, nib, lane, mask, blk_cnt, gran_per_blk);
+        }
+    }
+
+    if (NORM) {
+        __shared__ double wsum[kWavesPerWG];
+        double s = (double)nrm;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+        if (lane == 0) wsum[wave] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+            atomicAdd(&err_slots[blockIdx.x % kErrSlots], tot);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// k_control: one workgroup of 1024 threads.
+//   cur  = topology slot the finished k_stream's iteration selects with
+//   next = slot receiving Alg. 3's adjusted topology for the next iteration
+__global__ void __launch_bounds__(kCtrlThreads)
+k_control(DevState *__restrict__ st, const uint32_t *__restrict__ blk_cnt,
+          uint32_t *__restrict__ blk_cnt_next, uint32_t *__restrict__ blk_off,
+          const int32_t *__restrict__ cur_part, const int32_t *__restrict__ cur_pos,
+          int32_t *__restrict__ nxt_part, int32_t *__restrict__ nxt_pos,
+          double *__restrict__ kvec, uint64_t *__restrict__ part_cnt,
+          uint64_t *__restrict__ part_off, double *__restrict__ err_slots_next, CtrlParams prm)
+{
+    __shared__ uint32_t wsum[kCtrlThreads / 64];
+    __shared__ uint32_t tile_total;
+    __shared__ double   kv[kMaxParts];
+    __shared__ int32_t  lpart[kMaxParts];
+    __shared__ int32_t  lpos[kMaxParts];
+
+    const uint32_t tid  = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = tid >> 6;
+    const uint32_t n_b  = prm.n_b;
+    const uint32_t P    = prm.n_parts;
+
+    // ---- exclusive scan of the per-block counts, 4096 blocks per tile ----
+    uint32_t carry = 0;
+    for (uint32_t base = 0; base < n_b; base += kCtrlThreads * 4u) {
+        const uint32_t i0 = base + tid * 4u;
+        uint32_t c[4];
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            c[q] = (i0 + q < n_b) ? blk_cnt[i0 + q] : 0u;
+            if (i0 + q < n_b) blk_cnt_next[i0 + q] = 0u;  // clean counters for the next iteration
+        }
+        const uint32_t s    = c[0] + c[1] + c[2] + c[3];
+        const uint32_t incl = wave_incl_scan(s, lane);
+        if (lane == 63) wsum[wave] = incl;
+        __syncthreads();
+        if (wave == 0) {
+            const uint32_t v  = lane < kCtrlThreads / 64 ? wsum[lane] : 0u;
+            const uint32_t vi = wave_incl_scan(v, lane);
+            if (lane < kCtrlThreads / 64) wsum[lane] = vi - v;
+            if (lane == kCtrlThreads / 64 - 1) tile_total = vi;
+        }
+        __syncthreads();
+        uint32_t excl = carry + wsum[wave] + (incl - s);
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            if (i0 + q < n_b) blk_off[i0 + q] = excl;
+            excl += c[q];
+        }
+        carry += tile_total;
+        __syncthreads();
+    }
+    if (tid == 0) blk_off[n_b] = carry;
+    if (tid < kErrSlots) err_slots_next[tid] = 0.0;
+    __syncthreads();
+    const uint64_t k_actual = carry;  // k' (Alg. 1 line 13)
+
+    // ---- per-partition counts and output segment starts ----
+    for (uint32_t p = tid; p < P; p += kCtrlThreads) {
+        const int32_t  pos  = cur_pos[p];
+        const int32_t  part = cur_part[p];
+        const uint32_t lo   = blk_off[pos];
+        const uint32_t hi   = blk_off[pos + part];
+        const uint64_t cnt  = (uint64_t)(hi - lo);
+        part_cnt[p] = cnt;
+        part_off[p] = lo < prm.cap ? (uint64_t)lo : prm.cap;
+        kv[p]    = (double)cnt;  // this iteration's k_{p,t} feeds the next Allocate (Alg. 1 line 15)
+        lpart[p] = part;
+        lpos[p]  = pos;
+    }
+    __syncthreads();
+
+    if (tid == 0) {
+        part_off[P] = k_actual < prm.cap ? k_actual : prm.cap;
+
+        // ---- Alg. 5: online threshold scaling ----
+        const float  delta = st->delta;
+        const double exam  = (double)k_actual / prm.k;
+        float sf;
+        if (exam > prm.beta)
+            sf = prm.sf_hi;
+        else if (exam > prm.inv_beta)
+            sf = prm.sf_mid;
+        else
+            sf = prm.sf_lo;
+        st->delta_used = delta;
+        st->delta      = delta * sf;
+
+        // ---- Eq. 2 / 5 / 6 ----
+        uint64_t m_t = 0;
+        for (uint32_t p = 0; p < P; ++p) {
+            const uint64_t c = (uint64_t)kv[p];
+            if (c > m_t) m_t = c;
+        }
+        st->k_actual      = k_actual;
+        st->k_emitted     = k_actual < prm.cap ? k_actual : prm.cap;
+        st->overflow      = k_actual > prm.cap ? 1u : 0u;
+        st->k_max_part    = m_t;
+        st->density_error = fabs(prm.k - (double)k_actual) / (double)prm.n_g;
+        st->traffic_ratio = k_actual ? (double)P * (double)m_t / (double)k_actual : 0.0;
+        st->t += 1;
+
+        // ---- Alg. 3 lines 8-28: sweep over adjacent pairs, sequential by
+        // construction (pair i sees pair i-1's updated estimate) ----
+        uint32_t moves = 0;
+        double   sum   = 0.0;
+        for (uint32_t p = 0; p < P; ++p) sum += kv[p];
+        if (sum > 0.0) {
+            const double  pk_prev  = sum / (double)P;
+            const double  den_prev = sum / (double)prm.n_g;
+            const int64_t blk_move = (int64_t)prm.blk_move;
+            const int64_t min_blk  = (int64_t)prm.min_blk;
+            for (uint32_t i = 0; i + 1 < P; ++i) {
+                const double det    = kv[i] / pk_prev;
+                const double det2   = kv[i + 1] / pk_prev;
+                const double k_move = (double)prm.blk_move * (double)prm.block_size * den_prev;
+                if (det > prm.alpha && det2 < prm.inv_alpha) {
+                    if ((int64_t)lpart[i] - blk_move < min_blk) continue;
+                    lpart[i]     -= (int32_t)blk_move;
+                    lpart[i + 1] += (int32_t)blk_move;
+                    lpos[i + 1]  -= (int32_t)blk_move;
+                    kv[i]        -= k_move;
+                    kv[i + 1]    += k_move;
+                    ++moves;
+                }
+                if (det < prm.inv_alpha && det2 > prm.alpha) {
+                    if ((int64_t)lpart[i + 1] - blk_move < min_blk) continue;
+                    lpart[i]     += (int32_t)blk_move;
+                    lpart[i + 1] -= (int32_t)blk_move;
+                    lpos[i + 1]  += (int32_t)blk_move;
+                    kv[i]        += k_move;
+                    kv[i + 1]    -= k_move;
+                    ++moves;
+                }
+            }
+        }
+        st->moves = moves;
+    }
+    __syncthreads();
+    for (uint32_t p = tid; p < P; p += kCtrlThreads) {
+        nxt_part[p] = lpart[p];
+        nxt_pos[p]  = lpos[p];
+        kvec[p]     = kv[p];
+    }
+}
+
+// ---------------------------------------------------------------------------
+// k_compact: one wavefront per block.  Each lane takes four consecutive mask
+// words (128 gradients); a wave scan of the popcounts gives every lane the
+// rank of its first set bit, so pairs come out in ascending index order.
+template <bool NORM>
+__global__ void __launch_bounds__(256)
+k_compact(float *__restrict__ e, const uint32_t *__restrict__ mask,
+          const uint32_t *__restrict__ blk_cnt, const uint32_t *__restrict__ blk_off,
+          uint32_t *__restrict__ out_idx, float *__restrict__ out_val,
+          double *__restrict__ err_slots, uint32_t n_b, uint32_t block_size, uint32_t n_g,
+          uint64_t cap)
+{
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t j    = blockIdx.x * 4u + (threadIdx.x >> 6);
+    if (j >= n_b) return;
+    if (blk_cnt[j] == 0) return;
+    const uint64_t base = blk_off[j];
+    if (!NORM && base >= cap) return;  // nothing of this block fits: it all stays in the residual
+
+    const uint64_t first = (uint64_t)j * block_size;
+    const uint32_t len   = (uint64_t)n_g - first < block_size ? (uint32_t)(n_g - first) : block_size;
+    const uint32_t words = (((len + 31u) >> 5) + 3u) & ~3u;
+    const uint4   *m4    = reinterpret_cast<const uint4 *>(mask + (size_t)j * (block_size >> 5));
+    uint64_t running = base;
+    float    spill   = 0.f;
+
+    for (uint32_t w0 = 0; w0 < words; w0 += 256u) {
+        const uint32_t wq = w0 + lane * 4u;
+        uint4 m = make_uint4(0, 0, 0, 0);
+        if (wq < words) m = m4[wq >> 2];
+        const uint32_t c    = __popc(m.x) + __popc(m.y) + __popc(m.z) + __popc(m.w);
+        const uint32_t incl = wave_incl_scan(c, lane);
+        const uint32_t tot  = __shfl(incl, 63, 64);
+        uint64_t r = running + (incl - c);
+        uint32_t wv[4] = {m.x, m.y, m.z, m.w};
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            uint32_t       bits  = wv[q];
+            const uint32_t ebase = (uint32_t)first + (wq + q) * 32u;
+            while (bits) {
+                const uint32_t i = ebase + (uint32_t)(__ffs(bits) - 1);
+                bits &= bits - 1u;
+                if (r < cap) {
+                    const float v = e[i];
+                    out_idx[r] = i;
+                    out_val[r] = v;
+                    e[i]       = 0.0f;  // +0 where sent (Alg. 1 line 17)
+                } else if (NORM) {
+                    const float v = e[i];  // selected but not emitted: stays in the residual
+                    spill += v * v;
+                }
+                ++r;
+            }
+        }
+        running += tot;
+    }
+    if (NORM) {
+        double s = (double)spill;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+        if (lane == 0 && s != 0.0) atomicAdd(&err_slots[j % kErrSlots], s);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// small set-up / read-out kernels
+
+__global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n)
+{
+    for (size_t i = blockIdx.x * (size_t)blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+// Alg. 1 lines 4-6: partial-k vector k/P, delta_0, Alg. 2 topology in closed
+// form (the first `remainder` partitions hold quotient+1 blocks; positions are
+// the exclusive prefix sum).
+__global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_t *part1,
+                             int32_t *pos1, double *kvec, uint64_t *part_cnt, uint64_t *part_off,
+                             double *err_slots, float delta0, double k, uint32_t n_b, uint32_t P)
+{
+    const uint32_t tid = blockIdx.x * blockDim.x + threadIdx.x;
+    const uint32_t q = n_b / P, r = n_b % P;
+    if (tid < P) {
+        const int32_t part = (int32_t)(q + (tid < r ? 1u : 0u));
+        const int32_t pos  = (int32_t)(tid * q + (tid < r ? tid : r));
+        part0[tid] = part; pos0[tid] = pos;
+        part1[tid] = part; pos1[tid] = pos;
+        kvec[tid]     = k / (double)P;
+        part_cnt[tid] = 0;
+        part_off[tid] = 0;
+    }
+    if (tid == P) part_off[P] = 0;
+    if (tid < 2 * kErrSlots) err_slots[tid] = 0.0;
+    if (tid == 0) {
+        st->delta = delta0;
+        st->delta_used = delta0;
+        st->overflow = 0; st->moves = 0; st->t = 0;
+        st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
+        st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
+    }
+}
+
+__global__ void k_norm_finalize(DevState *st, const double *err_slots)
+{
+    __shared__ double s[kErrSlots];
+    s[threadIdx.x] = err_slots[threadIdx.x];
+    __syncthreads();
+    for (uint32_t d = kErrSlots / 2; d >= 1; d >>= 1) {
+        if (threadIdx.x < d) s[threadIdx.x] += s[threadIdx.x + d];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) st->err_norm = sqrt(s[0]);
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// host side
+
+struct exdyna_ctx {
+    uint64_t      magic;
+    exdyna_config cfg;
+    CtrlParams    prm;
+    Layout        lay;
+    uint64_t      n_b, cap, n_gran;
+    uint64_t      t;  // iterations enqueued
+    float        *d_residual;
+    char         *ws;
+    hipStream_t   stream;  // stream of the most recent call
+    int           profiling;
+    hipEvent_t    ev[4];
+    char          hip_err[256];
+};
+
+namespace {
+
+int validate_config(const exdyna_config *c, uint64_t *n_b_out, uint64_t *cap_out)
+{
+    if (c->n_g == 0 || c->n_g > 0xFFFFFFFFull) return EXDYNA_EINVAL;
+    if (c->block_size == 0 || c->block_size % kGran != 0) return EXDYNA_EINVAL;
+    const uint64_t n_b = (c->n_g + c->block_size - 1) / c->block_size;
+    if (c->n_parts == 0 || c->n_parts > n_b || c->n_parts > kMaxParts) return EXDYNA_EINVAL;
+    if (!(c->density > 0.0 && c->density <= 1.0)) return EXDYNA_EINVAL;
+    if (!(c->threshold0 > 0.0f) || std::isinf(c->threshold0)) return EXDYNA_EINVAL;
+    if (c->cmp_mode > 1) return EXDYNA_EINVAL;
+    if (!(c->alpha >= 1.0) || std::isinf(c->alpha)) return EXDYNA_EINVAL;
+    if (!(c->beta > 1.0) || std::isinf(c->beta)) return EXDYNA_EINVAL;
+    if (!(c->gamma > 0.0 && c->gamma < 1.0)) return EXDYNA_EINVAL;
+    if (c->min_blk == 0) return EXDYNA_EINVAL;
+    if (c->reserved != 0) return EXDYNA_EINVAL;
+    if (c->max_selected > c->n_g) return EXDYNA_EINVAL;
+    uint64_t cap = c->max_selected;
+    if (cap == 0) {
+        const double want = std::ceil(4.0 * c->density * (double)c->n_g);
+        cap = want < 1024.0 ? 1024 : (uint64_t)want;
+        if (cap > c->n_g) cap = c->n_g;
+    }
+    *n_b_out = n_b;
+    *cap_out = cap;
+    return EXDYNA_OK;
+}
+
+Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
+{
+    Layout L{};
+    const size_t P = c->n_parts;
+    const size_t n_gran = (c->n_g + kGran - 1) / kGran;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    L.state     = take(sizeof(DevState));
+    L.kvec      = take(P * sizeof(double));
+    L.parts     = take(4 * P * sizeof(int32_t));        // slot0 part,pos ; slot1 part,pos
+    L.part_cnt  = take(P * sizeof(uint64_t));
+    L.part_off  = take((P + 1) * sizeof(uint64_t));
+    L.blk_cnt   = take(2 * n_b * sizeof(uint32_t));      // two alternating counter arrays
+    L.blk_off   = take((n_b + 1) * sizeof(uint32_t));
+    L.err_slots = take(2 * kErrSlots * sizeof(double));
+    L.mask_words = n_gran * kGranWords;
+    L.mask      = take(L.mask_words * sizeof(uint32_t));
+    L.out_idx   = take(cap * sizeof(uint32_t));
+    L.out_val   = take(cap * sizeof(float));
+    L.total     = off;
+    return L;
+}
+
+bool ctx_ok(const exdyna_ctx *c) { return c && c->magic == kMagic; }
+
+int hip_fail(exdyna_ctx *c, hipError_t e, const char *what)
+{
+    if (c) snprintf(c->hip_err, sizeof c->hip_err, "%s: %s", what, hipGetErrorString(e));
+    return EXDYNA_EHIP;
+}
+
+#define HIP_TRY(ctx, call)                                       \
+    do {                                                         \
+        hipError_t e__ = (call);                                 \
+        if (e__ != hipSuccess) return hip_fail(ctx, e__, #call); \
+    } while (0)
+
+template <typename T> T *at(exdyna_ctx *c, size_t off) { return reinterpret_cast<T *>(c->ws + off); }
+
+int32_t *slot_part(exdyna_ctx *c, uint64_t slot) { return at<int32_t>(c, c->lay.parts) + (slot & 1) * 2 * c->cfg.n_parts; }
+int32_t *slot_pos(exdyna_ctx *c, uint64_t slot) { return slot_part(c, slot) + c->cfg.n_parts; }
+uint32_t *blk_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.blk_cnt) + (t & 1) * c->n_b; }
+double *err_slots_of(exdyna_ctx *c, uint64_t t) { return at<double>(c, c->lay.err_slots) + (t & 1) * kErrSlots; }
+
+template <int CMP, bool NORM>
+void launch_stream(exdyna_ctx *c, const float *g, hipStream_t s)
+{
+    constexpr int U = EXDYNA_UNROLL;
+    const uint32_t per_wg = kWavesPerWG * U;
+    const uint32_t grid = (uint32_t)((c->n_gran + per_wg - 1) / per_wg);
+    hipLaunchKernelGGL((k_stream<CMP, NORM, U>), dim3(grid), dim3(kStreamWG), 0, s, g, c->d_residual,
+                       at<DevState>(c, c->lay.state), at<uint32_t>(c, c->lay.mask),
+                       blk_cnt_of(c, c->t), err_slots_of(c, c->t), (uint32_t)c->cfg.n_g,
+                       (uint32_t)c->n_gran, c->cfg.block_size / kGran);
+}
+
+}  // namespace
+
+extern "C" {
+
+int exdyna_default_config(exdyna_config *cfg)
+{
+    if (!cfg) return EXDYNA_ENULL;
+    memset(cfg, 0, sizeof *cfg);
+    cfg->alpha = 1.0;
+    cfg->beta = 1.1;
+    cfg->gamma = 0.01;
+    cfg->blk_move = 1;
+    cfg->min_blk = 1;
+    return EXDYNA_OK;
+}
+
+int exdyna_block_size_from_nb(uint64_t n_g, uint64_t n_b, uint32_t multiple, uint32_t *h_block_size)
+{
+    if (!h_block_size) return EXDYNA_ENULL;
+    if (n_b == 0 || multiple == 0) return EXDYNA_EINVAL;
+    const uint64_t temp = n_g / n_b;
+    const uint64_t sz = temp - temp % multiple;
+    if (sz > 0xFFFFFFFFull) return EXDYNA_EINVAL;
+    *h_block_size = (uint32_t)sz;
+    return EXDYNA_OK;
+}
+
+int exdyna_workspace_bytes(const exdyna_config *cfg, size_t *h_bytes)
+{
+    if (!cfg || !h_bytes) return EXDYNA_ENULL;
+    uint64_t n_b, cap;
+    int rc = validate_config(cfg, &n_b, &cap);
+    if (rc) return rc;
+    *h_bytes = make_layout(cfg, n_b, cap).total;
+    return EXDYNA_OK;
+}
+
+int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, void *d_workspace,
+                size_t ws_bytes, void *hip_stream)
+{
+    if (!out) return EXDYNA_ENULL;
+    *out = nullptr;
+    if (!cfg || !d_residual || !d_workspace) return EXDYNA_ENULL;
+    uint64_t n_b, cap;
+    int rc = validate_config(cfg, &n_b, &cap);
+    if (rc) return rc;
+    if ((uintptr_t)d_residual % 16 != 0 || (uintptr_t)d_workspace % 256 != 0) return EXDYNA_EALIGN;
+    const Layout L = make_layout(cfg, n_b, cap);
+    if (ws_bytes < L.total) return EXDYNA_ENOMEM;
+
+    exdyna_ctx *c = new (std::nothrow) exdyna_ctx();
+    if (!c) return EXDYNA_ENOMEM;
+    c->cfg = *cfg;
+    c->lay = L;
+    c->n_b = n_b;
+    c->cap = cap;
+    c->n_gran = (cfg->n_g + kGran - 1) / kGran;
+    c->t = 0;
+    c->d_residual = d_residual;
+    c->ws = static_cast<char *>(d_workspace);
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->profiling = 0;
+    c->hip_err[0] = 0;
+
+    CtrlParams &p = c->prm;
+    p.n_g = cfg->n_g;
+    p.cap = cap;
+    p.k = cfg->density * (double)cfg->n_g;
+    p.alpha = cfg->alpha;
+    p.inv_alpha = 1.0 / cfg->alpha;
+    p.beta = cfg->beta;
+    p.inv_beta = 1.0 / cfg->beta;
+    p.sf_hi = (float)(1.0 + cfg->gamma);           // Alg. 5 line 3
+    p.sf_mid = (float)(1.0 + 0.25 * cfg->gamma);   // Alg. 5 line 5
+    p.sf_lo = (float)(1.0 - cfg->gamma);           // Alg. 5 line 7
+    p.n_b = (uint32_t)n_b;
+    p.n_parts = cfg->n_parts;
+    p.block_size = cfg->block_size;
+    p.blk_move = cfg->blk_move;
+    p.min_blk = cfg->min_blk;
+
+    hipStream_t s = c->stream;
+    const uint32_t P = cfg->n_parts;
+    // residual <- 0 (Alg. 1 line 3); counters and mask start clean
+    hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, s,
+                       reinterpret_cast<uint32_t *>(d_residual), 0u, (size_t)cfg->n_g);
+    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
+                       (size_t)(2 * n_b));
+    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_off), 0u,
+                       (size_t)(n_b + 1));
+    hipLaunchKernelGGL(k_fill_u32, dim3(1024), dim3(256), 0, s, at<uint32_t>(c, L.mask), 0u,
+                       L.mask_words);
+    const uint32_t init_threads = (P + 1 > 2 * kErrSlots ? P + 1 : 2 * kErrSlots);
+    hipLaunchKernelGGL(k_init_state, dim3((init_threads + 255) / 256), dim3(256), 0, s,
+                       at<DevState>(c, L.state), slot_part(c, 0), slot_pos(c, 0), slot_part(c, 1),
+                       slot_pos(c, 1), at<double>(c, L.kvec), at<uint64_t>(c, L.part_cnt),
+                       at<uint64_t>(c, L.part_off), at<double>(c, L.err_slots), cfg->threshold0, p.k,
+                       (uint32_t)n_b, P);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) {
+        delete c;
+        return EXDYNA_EHIP;
+    }
+    c->magic = kMagic;
+    *out = c;
+    return EXDYNA_OK;
+}
+
+int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!d_grad) return EXDYNA_ENULL;
+    if ((uintptr_t)d_grad % 16 != 0) return EXDYNA_EALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    c->stream = s;
+    const bool norm = c->cfg.want_err_norm != 0;
+    const bool prof = c->profiling != 0;
+
+    if (prof) HIP_TRY(c, hipEventRecord(c->ev[0], s));
+    if (c->cfg.cmp_mode == 0) {
+        if (norm) launch_stream<0, true>(c, d_grad, s); else launch_stream<0, false>(c, d_grad, s);
+    } else {
+        if (norm) launch_stream<1, true>(c, d_grad, s); else launch_stream<1, false>(c, d_grad, s);
+    }
+    if (prof) HIP_TRY(c, hipEventRecord(c->ev[1], s));
+
+    const uint64_t t = c->t;
+    hipLaunchKernelGGL(k_control, dim3(1), dim3(kCtrlThreads), 0, s, at<DevState>(c, c->lay.state),
+                       blk_cnt_of(c, t), blk_cnt_of(c, t + 1), at<uint32_t>(c, c->lay.blk_off),
+                       slot_part(c, t), slot_pos(c, t), slot_part(c, t + 1), slot_pos(c, t + 1),
+                       at<double>(c, c->lay.kvec), at<uint64_t>(c, c->lay.part_cnt),
+                       at<uint64_t>(c, c->lay.part_off), err_slots_of(c, t + 1), c->prm);
+    if (prof) HIP_TRY(c, hipEventRecord(c->ev[2], s));
+
+    const uint32_t grid = (uint32_t)((c->n_b + 3) / 4);
+    if (norm)
+        hipLaunchKernelGGL(k_compact<true>, dim3(grid), dim3(256), 0, s, c->d_residual,
+                           at<uint32_t>(c, c->lay.mask), blk_cnt_of(c, t),
+                           at<uint32_t>(c, c->lay.blk_off), at<uint32_t>(c, c->lay.out_idx),
+                           at<float>(c, c->lay.out_val), err_slots_of(c, t), (uint32_t)c->n_b,
+                           c->cfg.block_size, (uint32_t)c->cfg.n_g, c->cap);
+    else
+        hipLaunchKernelGGL(k_compact<false>, dim3(grid), dim3(256), 0, s, c->d_residual,
+                           at<uint32_t>(c, c->lay.mask), blk_cnt_of(c, t),
+                           at<uint32_t>(c, c->lay.blk_off), at<uint32_t>(c, c->lay.out_idx),
+                           at<float>(c, c->lay.out_val), err_slots_of(c, t), (uint32_t)c->n_b,
+                           c->cfg.block_size, (uint32_t)c->cfg.n_g, c->cap);
+    if (prof) HIP_TRY(c, hipEventRecord(c->ev[3], s));
+    HIP_TRY(c, hipGetLastError());
+    c->t = t + 1;
+    return EXDYNA_OK;
+}
+
+int exdyna_get_selected(exdyna_ctx *c, const uint32_t **d_idx, const float **d_val,
+                        const uint64_t **d_part_off, uint64_t *h_k_actual, uint64_t *h_k_emitted)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (d_idx) *d_idx = at<uint32_t>(c, c->lay.out_idx);
+    if (d_val) *d_val = at<float>(c, c->lay.out_val);
+    if (d_part_off) *d_part_off = at<uint64_t>(c, c->lay.part_off);
+    if (h_k_actual || h_k_emitted) {
+        DevState st;
+        HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st,
+                                  hipMemcpyDeviceToHost, c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        if (h_k_actual) *h_k_actual = st.k_actual;
+        if (h_k_emitted) *h_k_emitted = st.k_emitted;
+    }
+    return EXDYNA_OK;
+}
+
+int exdyna_get_partitions(exdyna_ctx *c, int which, uint32_t *h_blk_pos, uint32_t *h_blk_part,
+                          uint64_t *h_elem_start, uint64_t *h_elem_end, uint32_t *h_owner_rank)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (which != 0 && which != 1) return EXDYNA_EINVAL;
+    if (which == 0 && c->t == 0) return EXDYNA_ESTATE;  // no step has selected yet
+    const uint32_t P = c->cfg.n_parts;
+    // iteration whose topology is asked for
+    const uint64_t it = which == 0 ? c->t - 1 : c->t;
+    int32_t *tmp = static_cast<int32_t *>(malloc(2 * (size_t)P * sizeof(int32_t)));
+    if (!tmp) return EXDYNA_ENOMEM;
+    hipError_t e = hipMemcpyAsync(tmp, slot_part(c, it), 2 * (size_t)P * sizeof(int32_t),
+                                  hipMemcpyDeviceToHost, c->stream);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->stream);
+    if (e != hipSuccess) {
+        free(tmp);
+        return hip_fail(c, e, "copy topology");
+    }
+    const int32_t *part = tmp, *pos = tmp + P;
+    for (uint32_t p = 0; p < P; ++p) {
+        if (h_blk_part) h_blk_part[p] = (uint32_t)part[p];
+        if (h_blk_pos) h_blk_pos[p] = (uint32_t)pos[p];
+        // Alg. 3 lines 30-31, the last block may be short
+        uint64_t st = (uint64_t)pos[p] * c->cfg.block_size;
+        uint64_t en = (uint64_t)(pos[p] + part[p]) * c->cfg.block_size;
+        if (st > c->cfg.n_g) st = c->cfg.n_g;
+        if (en > c->cfg.n_g) en = c->cfg.n_g;
+        if (h_elem_start) h_elem_start[p] = st;
+        if (h_elem_end) h_elem_end[p] = en;
+        // Alg. 3 line 29: alloc = (t mod P + rank) mod P  <=>  rank = (alloc - t) mod P
+        if (h_owner_rank) h_owner_rank[p] = (uint32_t)((p + P - (uint32_t)(it % P)) % P);
+    }
+    free(tmp);
+    return EXDYNA_OK;
+}
+
+int exdyna_get_block_counts(exdyna_ctx *c, uint32_t *h_counts)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!h_counts) return EXDYNA_ENULL;
+    if (c->t == 0) return EXDYNA_ESTATE;
+    HIP_TRY(c, hipMemcpyAsync(h_counts, blk_cnt_of(c, c->t - 1), c->n_b * sizeof(uint32_t),
+                              hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return EXDYNA_OK;
+}
+
+int exdyna_get_part_counts(exdyna_ctx *c, uint64_t *h_counts)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!h_counts) return EXDYNA_ENULL;
+    if (c->t == 0) return EXDYNA_ESTATE;
+    HIP_TRY(c, hipMemcpyAsync(h_counts, at<uint64_t>(c, c->lay.part_cnt),
+                              c->cfg.n_parts * sizeof(uint64_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    return EXDYNA_OK;
+}
+
+int exdyna_get_stats(exdyna_ctx *c, exdyna_stats *h_out)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!h_out) return EXDYNA_ENULL;
+    if (c->cfg.want_err_norm && c->t > 0)
+        hipLaunchKernelGGL(k_norm_finalize, dim3(1), dim3(kErrSlots), 0, c->stream,
+                           at<DevState>(c, c->lay.state), err_slots_of(c, c->t - 1));
+    DevState st;
+    HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st, hipMemcpyDeviceToHost,
+                              c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    h_out->t = st.t;
+    h_out->k_actual = st.k_actual;
+    h_out->k_emitted = st.k_emitted;
+    h_out->k_max_part = st.k_max_part;
+    h_out->density_error = st.density_error;
+    h_out->traffic_ratio = st.traffic_ratio;
+    h_out->err_norm = (c->cfg.want_err_norm && c->t > 0) ? st.err_norm : -1.0;
+    h_out->delta_used = st.delta_used;
+    h_out->delta_next = st.delta;
+    h_out->overflow = st.overflow;
+    h_out->moves = st.moves;
+    return EXDYNA_OK;
+}
+
+int exdyna_get_dims(const exdyna_ctx *c, uint64_t *h_n_blocks, uint64_t *h_capacity)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (h_n_blocks) *h_n_blocks = c->n_b;
+    if (h_capacity) *h_capacity = c->cap;
+    return EXDYNA_OK;
+}
+
+int exdyna_set_profiling(exdyna_ctx *c, int enable)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (enable && !c->profiling) {
+        for (int i = 0; i < 4; ++i) HIP_TRY(c, hipEventCreate(&c->ev[i]));
+        c->profiling = 1;
+    } else if (!enable && c->profiling) {
+        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
+        c->profiling = 0;
+    }
+    return EXDYNA_OK;
+}
+
+int exdyna_get_kernel_ms(exdyna_ctx *c, float *h_ms3)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!h_ms3) return EXDYNA_ENULL;
+    if (!c->profiling || c->t == 0) return EXDYNA_ESTATE;
+    HIP_TRY(c, hipEventSynchronize(c->ev[3]));
+    for (int i = 0; i < 3; ++i) HIP_TRY(c, hipEventElapsedTime(&h_ms3[i], c->ev[i], c->ev[i + 1]));
+    return EXDYNA_OK;
+}
+
+const char *exdyna_strerror(int code)
+{
+    switch (code) {
+    case EXDYNA_OK: return "ok";
+    case EXDYNA_EINVAL: return "configuration value out of range";
+    case EXDYNA_ENULL: return "required pointer is NULL";
+    case EXDYNA_EALIGN: return "device pointer not aligned as required";
+    case EXDYNA_ESTATE: return "context not initialised, destroyed, or no step run yet";
+    case EXDYNA_ENOMEM: return "workspace too small or host allocation failed";
+    case EXDYNA_EHIP: return "HIP runtime call failed";
+    default: return "unknown error code";
+    }
+}
+
+const char *exdyna_last_hip_error(const exdyna_ctx *c) { return ctx_ok(c) ? c->hip_err : ""; }
+
+int exdyna_destroy(exdyna_ctx *c)
+{
+    if (!c) return EXDYNA_ENULL;
+    if (c->magic != kMagic) return EXDYNA_ESTATE;
+    if (c->profiling)
+        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
+    c->magic = 0;
+    delete c;
+    return EXDYNA_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+"""Shared driver for the GPU parity tests: runs the HIP library and the CPU oracle on
+the same gradients and compares every output of every step."""
+import sys
+
+import numpy as np
+import torch
+
+from oracle import oracle
+from paper_2402_13781_amd import binding
+
+
+def log(msg):
+    print(msg, flush=True)
+    sys.stdout.flush()
+
+
+def make_pair(n_g, b, P, d, thr, **kw):
+    cfg = binding.default_config(n_g=n_g, block_size=b, n_parts=P, density=d, threshold0=thr, **kw)
+    x = binding.ExDyna(cfg, "cuda:0")
+    o = oracle.Oracle(n_g, b, P, d, thr, alpha=cfg.alpha, beta=cfg.beta, gamma=cfg.gamma,
+                      blk_move=cfg.blk_move, min_blk=cfg.min_blk, cmp_mode=cfg.cmp_mode,
+                      max_selected=cfg.max_selected)
+    assert x.capacity == o.cap and x.n_blocks == o.n_b
+    return x, o
+
+
+def bits(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def compare_step(x, o, t, check_norm=False, tag=""):
+    """Bit-exact on indices, values, residual, counts, topology; thresholds bit-equal
+    (the stated bar is 1e-6 relative); the norm statistic within 1e-5 relative."""
+    where = f"{tag} step {t}"
+    idx, val, off, ka, ke = x.get_selected()
+    assert ka == o.k_actual, (where, ka, o.k_actual)
+    assert ke == o.k_emitted, (where, ke, o.k_emitted)
+    g_idx = idx.cpu().numpy().view(np.uint32)
+    g_val = val.cpu().numpy()
+    o_idx, o_val = o.out_idx(), o.out_val()
+    assert np.array_equal(g_idx, o_idx), where
+    assert np.array_equal(bits(g_val), bits(o_val)), where
+    assert np.array_equal(off.cpu().numpy().view(np.uint64), o.part_off()), where
+    assert np.array_equal(x.get_block_counts(), o.block_count()), where
+    assert np.array_equal(x.get_part_counts(), o.part_count()), where
+    parts = x.get_partitions(0)
+    assert np.array_equal(parts["blk_part"].astype(np.int64), o.blk_part(0)), where
+    assert np.array_equal(parts["blk_pos"].astype(np.int64), o.blk_pos(0)), where
+    st = o.blk_pos(0) * o.b
+    en = np.minimum((o.blk_pos(0) + o.blk_part(0)) * o.b, o.n_g)
+    assert np.array_equal(parts["elem_start"].astype(np.int64), st), where
+    assert np.array_equal(parts["elem_end"].astype(np.int64), en), where
+    owners = [oracle.owner(t, int(r), o.P) for r in parts["owner_rank"]]
+    assert owners == list(range(o.P)), where                 # Alg. 3 line 29, inverted
+    res = x.residual.cpu().numpy()
+    assert np.array_equal(bits(res), bits(o.residual(copy=False))), where
+    s = x.get_stats()
+    assert s.t == t + 1 == o.t
+    assert np.float32(s.delta_used) == o.threshold_used, where
+    assert np.float32(s.delta_next) == o.threshold, where
+    assert abs(s.delta_next - float(o.threshold)) <= 1e-6 * float(o.threshold)
+    assert s.k_actual == ka and s.k_emitted == ke and s.overflow == int(ka > ke)
+    assert s.k_max_part == int(o.part_count().max())
+    assert s.density_error == o.density_error(), where
+    assert s.traffic_ratio == o.traffic_ratio(), where
+    if check_norm:
+        want = o.err_norm()
+        if np.isnan(want):
+            assert np.isnan(s.err_norm), where
+        else:
+            assert abs(s.err_norm - want) <= 1e-5 * max(want, 1e-30), (where, s.err_norm, want)
+    return ka, ke
+
+
+def run_trajectory(x, o, grads, tag="", check_norm=False, every=1):
+    """grads: iterable of device tensors.  Also checks that the topology the library
+    announces for the next step is the one the oracle's next Allocate produces."""
+    announced = None
+    for t, g in enumerate(grads):
+        x.step(g)
+        o.step(g.cpu().numpy())
+        if announced is not None:
+            assert np.array_equal(announced["blk_part"].astype(np.int64), o.blk_part(0)), (tag, t)
+            assert np.array_equal(announced["blk_pos"].astype(np.int64), o.blk_pos(0)), (tag, t)
+        if t % every == 0:
+            ka, ke = compare_step(x, o, t, check_norm=check_norm, tag=tag)
+            log(f"  [{tag}] t={t} k'={ka} emitted={ke} delta_next={float(o.threshold):.6g} ok")
+        announced = x.get_partitions(1)
+    torch.cuda.synchronize()
