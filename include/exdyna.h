@@ -142,12 +142,15 @@ int exdyna_get_stats(exdyna_ctx *ctx, exdyna_stats *h_out);
 /* Capacity and block count the context was created with.  Host only. */
 int exdyna_get_dims(const exdyna_ctx *ctx, uint64_t *h_n_blocks, uint64_t *h_capacity);
 
-/* Per-kernel timing for benchmarks: when enabled, exdyna_step records HIP
- * events around its three kernels on the step's stream;
- * exdyna_get_kernel_ms synchronises and returns the last step's durations in
- * milliseconds: [0] streaming pass, [1] control, [2] compaction. */
-int exdyna_set_profiling(exdyna_ctx *ctx, int enable);
-int exdyna_get_kernel_ms(exdyna_ctx *ctx, float *h_ms3);
+/* Per-kernel timing for benchmarks.  exdyna_set_profiling(ctx, n_slots) with
+ * n_slots > 0 makes every later exdyna_step record HIP events around its three
+ * kernels on the step's stream, into a ring of n_slots (<= 65536) event sets;
+ * 0 turns it off.  exdyna_get_kernel_ms waits for iteration `iteration`
+ * (0-based, one of the last n_slots enqueued since profiling was turned on)
+ * and returns its durations in milliseconds: [0] streaming pass, [1] control,
+ * [2] compaction. */
+int exdyna_set_profiling(exdyna_ctx *ctx, uint32_t n_slots);
+int exdyna_get_kernel_ms(exdyna_ctx *ctx, uint64_t iteration, float *h_ms3);
 
 const char *exdyna_strerror(int code);
 /* Text of the last HIP error seen by this context's calls ("" if none). */

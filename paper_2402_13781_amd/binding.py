@@ -75,8 +75,8 @@ def load() -> C.CDLL:
     L.exdyna_get_part_counts.argtypes = [vp, P(u64)]
     L.exdyna_get_stats.argtypes = [vp, P(Stats)]
     L.exdyna_get_dims.argtypes = [vp, P(u64), P(u64)]
-    L.exdyna_set_profiling.argtypes = [vp, C.c_int]
-    L.exdyna_get_kernel_ms.argtypes = [vp, P(C.c_float)]
+    L.exdyna_set_profiling.argtypes = [vp, u32]
+    L.exdyna_get_kernel_ms.argtypes = [vp, u64, P(C.c_float)]
     L.exdyna_strerror.argtypes = [C.c_int]
     L.exdyna_strerror.restype = C.c_char_p
     L.exdyna_last_hip_error.argtypes = [vp]
@@ -235,10 +235,11 @@ class ExDyna:
         self._check(self._L.exdyna_get_stats(self._h, C.byref(st)), "exdyna_get_stats")
         return st
 
-    def set_profiling(self, enable: bool):
-        self._check(self._L.exdyna_set_profiling(self._h, int(enable)), "exdyna_set_profiling")
+    def set_profiling(self, n_slots: int):
+        self._check(self._L.exdyna_set_profiling(self._h, int(n_slots)), "exdyna_set_profiling")
 
-    def get_kernel_ms(self):
+    def get_kernel_ms(self, iteration: int):
+        """[streaming pass, control, compaction] milliseconds of a profiled iteration."""
         out = (C.c_float * 3)()
-        self._check(self._L.exdyna_get_kernel_ms(self._h, out), "exdyna_get_kernel_ms")
+        self._check(self._L.exdyna_get_kernel_ms(self._h, iteration, out), "exdyna_get_kernel_ms")
         return [out[0], out[1], out[2]]

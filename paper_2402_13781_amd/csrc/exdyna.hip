@@ -482,8 +482,9 @@ struct exdyna_ctx {
     float        *d_residual;
     char         *ws;
     hipStream_t   stream;  // stream of the most recent call
-    int           profiling;
-    hipEvent_t    ev[4];
+    uint32_t      prof_slots;  // 0 = profiling off
+    uint64_t      prof_since;  // first iteration recorded with the current events
+    hipEvent_t   *ev;          // prof_slots x 4 events, slot = iteration % prof_slots
     char          hip_err[256];
 };
 
@@ -632,7 +633,8 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
     c->d_residual = d_residual;
     c->ws = static_cast<char *>(d_workspace);
     c->stream = static_cast<hipStream_t>(hip_stream);
-    c->profiling = 0;
+    c->prof_slots = 0;
+    c->ev = nullptr;
     c->hip_err[0] = 0;
 
     CtrlParams &p = c->prm;
@@ -687,15 +689,16 @@ int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     c->stream = s;
     const bool norm = c->cfg.want_err_norm != 0;
-    const bool prof = c->profiling != 0;
+    const bool prof = c->prof_slots != 0;
+    hipEvent_t *ev = prof ? c->ev + 4 * (c->t % c->prof_slots) : nullptr;
 
-    if (prof) HIP_TRY(c, hipEventRecord(c->ev[0], s));
+    if (prof) HIP_TRY(c, hipEventRecord(ev[0], s));
     if (c->cfg.cmp_mode == 0) {
         if (norm) launch_stream<0, true>(c, d_grad, s); else launch_stream<0, false>(c, d_grad, s);
     } else {
         if (norm) launch_stream<1, true>(c, d_grad, s); else launch_stream<1, false>(c, d_grad, s);
     }
-    if (prof) HIP_TRY(c, hipEventRecord(c->ev[1], s));
+    if (prof) HIP_TRY(c, hipEventRecord(ev[1], s));
 
     const uint64_t t = c->t;
     hipLaunchKernelGGL(k_control, dim3(1), dim3(kCtrlThreads), 0, s, at<DevState>(c, c->lay.state),
@@ -703,7 +706,7 @@ int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
                        slot_part(c, t), slot_pos(c, t), slot_part(c, t + 1), slot_pos(c, t + 1),
                        at<double>(c, c->lay.kvec), at<uint64_t>(c, c->lay.part_cnt),
                        at<uint64_t>(c, c->lay.part_off), err_slots_of(c, t + 1), c->prm);
-    if (prof) HIP_TRY(c, hipEventRecord(c->ev[2], s));
+    if (prof) HIP_TRY(c, hipEventRecord(ev[2], s));
 
     const uint32_t grid = (uint32_t)((c->n_b + 3) / 4);
     if (norm)
@@ -718,7 +721,7 @@ int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
                            at<uint32_t>(c, c->lay.blk_off), at<uint32_t>(c, c->lay.out_idx),
                            at<float>(c, c->lay.out_val), err_slots_of(c, t), (uint32_t)c->n_b,
                            c->cfg.block_size, (uint32_t)c->cfg.n_g, c->cap);
-    if (prof) HIP_TRY(c, hipEventRecord(c->ev[3], s));
+    if (prof) HIP_TRY(c, hipEventRecord(ev[3], s));
     HIP_TRY(c, hipGetLastError());
     c->t = t + 1;
     return EXDYNA_OK;
@@ -833,26 +836,54 @@ int exdyna_get_dims(const exdyna_ctx *c, uint64_t *h_n_blocks, uint64_t *h_capac
     return EXDYNA_OK;
 }
 
-int exdyna_set_profiling(exdyna_ctx *c, int enable)
+namespace {
+void drop_events(exdyna_ctx *c)
+{
+    if (c->ev) {
+        for (uint32_t i = 0; i < 4 * c->prof_slots; ++i) (void)hipEventDestroy(c->ev[i]);
+        free(c->ev);
+    }
+    c->ev = nullptr;
+    c->prof_slots = 0;
+}
+}  // namespace
+
+int exdyna_set_profiling(exdyna_ctx *c, uint32_t n_slots)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
-    if (enable && !c->profiling) {
-        for (int i = 0; i < 4; ++i) HIP_TRY(c, hipEventCreate(&c->ev[i]));
-        c->profiling = 1;
-    } else if (!enable && c->profiling) {
-        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
-        c->profiling = 0;
+    if (n_slots > 65536) return EXDYNA_EINVAL;
+    if (c->prof_slots) {
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        drop_events(c);
     }
+    if (n_slots == 0) return EXDYNA_OK;
+    c->ev = static_cast<hipEvent_t *>(calloc(4 * (size_t)n_slots, sizeof(hipEvent_t)));
+    if (!c->ev) return EXDYNA_ENOMEM;
+    for (uint32_t i = 0; i < 4 * n_slots; ++i) {
+        hipError_t e = hipEventCreate(&c->ev[i]);
+        if (e != hipSuccess) {
+            for (uint32_t j = 0; j < i; ++j) (void)hipEventDestroy(c->ev[j]);
+            free(c->ev);
+            c->ev = nullptr;
+            return hip_fail(c, e, "hipEventCreate");
+        }
+    }
+    c->prof_slots = n_slots;
+    c->prof_since = c->t;
     return EXDYNA_OK;
 }
 
-int exdyna_get_kernel_ms(exdyna_ctx *c, float *h_ms3)
+int exdyna_get_kernel_ms(exdyna_ctx *c, uint64_t iteration, float *h_ms3)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (!h_ms3) return EXDYNA_ENULL;
-    if (!c->profiling || c->t == 0) return EXDYNA_ESTATE;
-    HIP_TRY(c, hipEventSynchronize(c->ev[3]));
-    for (int i = 0; i < 3; ++i) HIP_TRY(c, hipEventElapsedTime(&h_ms3[i], c->ev[i], c->ev[i + 1]));
+    if (!c->prof_slots) return EXDYNA_ESTATE;
+    // only iterations enqueued while profiling was on and not yet overwritten
+    if (iteration >= c->t || iteration < c->prof_since || c->t - iteration > c->prof_slots)
+        return EXDYNA_EINVAL;
+    hipEvent_t *ev = c->ev + 4 * (iteration % c->prof_slots);
+    HIP_TRY(c, hipEventSynchronize(ev[3]));
+    for (int i = 0; i < 3; ++i) HIP_TRY(c, hipEventElapsedTime(&h_ms3[i], ev[i], ev[i + 1]));
     return EXDYNA_OK;
 }
 
@@ -876,8 +907,7 @@ int exdyna_destroy(exdyna_ctx *c)
 {
     if (!c) return EXDYNA_ENULL;
     if (c->magic != kMagic) return EXDYNA_ESTATE;
-    if (c->profiling)
-        for (int i = 0; i < 4; ++i) (void)hipEventDestroy(c->ev[i]);
+    drop_events(c);
     c->magic = 0;
     delete c;
     return EXDYNA_OK;
