@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the ExDyna gradient-selection hot path on one MI355X.
 
-A step is one exdyna_step (streaming accumulate+compare+mask pass, control
-kernel, compaction) over one synthetic gradient vector that is already resident
+A step is one exdyna_step (streaming accumulate+compare+mask pass, then the
+finishing kernel: control + compaction) over one synthetic gradient vector that is already resident
 in HBM.  Prints ONE JSON line: whole-step throughput in G elements/s, the HBM
 roofline of the dominant kernel measured with HIP events over the timed steps,
 and the CPU oracle timed on a bounded sample of the same trajectory.
@@ -130,8 +130,7 @@ def main() -> int:
     if prof:
         ms = np.array([x.get_kernel_ms(t) for t in range(W, W + K)], dtype=np.float64)
         kern = {"k_stream_ms": round(float(ms[:, 0].mean()), 5),
-                "k_control_ms": round(float(ms[:, 1].mean()), 5),
-                "k_compact_ms": round(float(ms[:, 2].mean()), 5)}
+                "k_finish_ms": round(float(ms[:, 1].mean()), 5)}
         achieved = ALG_BYTES_PER_ELEM * w.n_g / (ms[:, 0].mean() * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),

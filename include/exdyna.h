@@ -53,7 +53,8 @@ typedef struct exdyna_ctx exdyna_ctx; /* opaque, host memory, library-owned */
 typedef struct {
     uint64_t n_g;          /* number of gradients, 1 <= n_g < 2^32 (indices are u32)        */
     uint32_t block_size;   /* b: gradients per block, > 0 and a multiple of 256 (Sec. 4.1;
-                              the paper's granularity is 32, one wavefront x float4 is 256)  */
+                              the paper's granularity is 32, one wavefront x float4 is 256);
+                              n_b = ceil(n_g / b) must not exceed 2^20                       */
     uint32_t n_parts;      /* P = number of workers n, 1 <= P <= min(n_b, 1024)             */
     double   density;      /* d in (0, 1]; k = d * n_g is kept in fp64 (Sec. 1)             */
     float    threshold0;   /* delta_0 > 0, finite (Alg. 1 line 5)                           */
@@ -68,7 +69,7 @@ typedef struct {
     uint32_t reserved;     /* must be 0                                                     */
 } exdyna_config;
 
-/* Per-step scalars, all produced on the device by the control kernel. */
+/* Per-step scalars, all produced on the device by the finishing kernel. */
 typedef struct {
     uint64_t t;             /* iterations completed                                         */
     uint64_t k_actual;      /* k' = number of gradients that passed the comparison          */
@@ -95,8 +96,8 @@ int exdyna_default_config(exdyna_config *cfg);
 int exdyna_block_size_from_nb(uint64_t n_g, uint64_t n_b, uint32_t multiple, uint32_t *h_block_size);
 
 /* Bytes of device workspace exdyna_init needs for this configuration
- * (state, per-block counters and offsets, the 1-bit-per-gradient selection
- * mask, and the output pairs).  Host only, launches nothing. */
+ * (state, per-block counters, the 1-bit-per-gradient selection mask, and the
+ * output pairs).  Host only, launches nothing. */
 int exdyna_workspace_bytes(const exdyna_config *cfg, size_t *h_bytes);
 
 /* Alg. 1 lines 3-6: residual <- 0, partial-k vector <- k/P, delta <- delta_0,
@@ -110,7 +111,7 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
 
 /* One iteration (see the top of this file).  d_grad: n_g floats, 16-byte
  * aligned, read only, already scaled by the learning rate (the accumulate is a
- * single fp32 add).  Asynchronous: returns after enqueueing three kernels. */
+ * single fp32 add).  Asynchronous: returns after enqueueing two kernels. */
 int exdyna_step(exdyna_ctx *ctx, const float *d_grad, void *hip_stream);
 
 /* Results of the last step.  *d_idx / *d_val: device arrays of k_emitted
@@ -143,14 +144,14 @@ int exdyna_get_stats(exdyna_ctx *ctx, exdyna_stats *h_out);
 int exdyna_get_dims(const exdyna_ctx *ctx, uint64_t *h_n_blocks, uint64_t *h_capacity);
 
 /* Per-kernel timing for benchmarks.  exdyna_set_profiling(ctx, n_slots) with
- * n_slots > 0 makes every later exdyna_step record HIP events around its three
+ * n_slots > 0 makes every later exdyna_step record HIP events around its two
  * kernels on the step's stream, into a ring of n_slots (<= 65536) event sets;
  * 0 turns it off.  exdyna_get_kernel_ms waits for iteration `iteration`
  * (0-based, one of the last n_slots enqueued since profiling was turned on)
- * and returns its durations in milliseconds: [0] streaming pass, [1] control,
- * [2] compaction. */
+ * and returns its durations in milliseconds: [0] the streaming pass, [1] the
+ * finishing kernel (control + compaction). */
 int exdyna_set_profiling(exdyna_ctx *ctx, uint32_t n_slots);
-int exdyna_get_kernel_ms(exdyna_ctx *ctx, uint64_t iteration, float *h_ms3);
+int exdyna_get_kernel_ms(exdyna_ctx *ctx, uint64_t iteration, float *h_ms2);
 
 const char *exdyna_strerror(int code);
 /* Text of the last HIP error seen by this context's calls ("" if none). */

@@ -239,7 +239,7 @@ class ExDyna:
         self._check(self._L.exdyna_set_profiling(self._h, int(n_slots)), "exdyna_set_profiling")
 
     def get_kernel_ms(self, iteration: int):
-        """[streaming pass, control, compaction] milliseconds of a profiled iteration."""
-        out = (C.c_float * 3)()
+        """[streaming pass, finishing kernel] milliseconds of a profiled iteration."""
+        out = (C.c_float * 2)()
         self._check(self._L.exdyna_get_kernel_ms(self._h, iteration, out), "exdyna_get_kernel_ms")
-        return [out[0], out[1], out[2]]
+        return [out[0], out[1]]

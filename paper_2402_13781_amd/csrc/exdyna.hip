@@ -1,25 +1,34 @@
 // ExDyna gradient-selection hot path for MI355X (gfx950, wave64).
 //
-// Three kernels per iteration, all enqueued by exdyna_step with no host
-// round trip (threshold, topology and counters live in device memory):
+// Two kernels per iteration, both enqueued by exdyna_step with no host round
+// trip (threshold, topology and counters live in device memory):
 //
 //   k_stream   acc = e + g (Alg. 1 line 7), |acc| cmp delta (Alg. 4 line 2),
-//              1 bit per gradient into a selection mask, per-block popcounts.
+//              1 bit per gradient into a selection mask, popcounts added to a
+//              per-block counter and to a counter per 64 blocks.
 //              Pure streaming: 8 B read + 4 B written per gradient.
-//   k_control  one workgroup: exclusive scan of the per-block counts,
-//              per-partition counts k_{p,t} and k' (Alg. 1 lines 10, 13),
-//              threshold scaling (Alg. 5), adjacent-partition rebalancing
-//              (Alg. 3 lines 8-28), Eq. 2/5/6 statistics.
-//   k_compact  one wavefront per block: wave-level scan of mask popcounts ->
-//              stable ascending (index, value) pairs at the block's offset
-//              (Alg. 1 lines 9-11), zero of the residual at emitted entries
-//              (Alg. 1 line 17).  Touches only the mask and the selected
-//              cache lines, never the whole vector again.
+//   k_finish   workgroup 0 = control: per-partition counts k_{p,t} and k'
+//              (Alg. 1 lines 10, 13), output segment offsets, threshold
+//              scaling (Alg. 5), adjacent-partition rebalancing (Alg. 3 lines
+//              8-28), Eq. 2/5/6 statistics.
+//              other workgroups = compaction, one wavefront per block: the
+//              wave sums the counters in front of its block (two levels, at
+//              most a few loads per lane), then a wave scan of mask popcounts
+//              gives stable ascending (index, value) pairs (Alg. 1 lines 9-11)
+//              and the residual is zeroed at emitted entries (Alg. 1 line 17).
+//              Touches only the mask and the selected cache lines.
+//              Control and compaction read the same finished counters and do
+//              not depend on each other, so they overlap inside one launch.
 //
 // Partitions are contiguous and ascending (Sec. 4.1), so the concatenation of
 // the per-partition index lists in partition order is the global ascending
-// list: output positions come from one scan over blocks and partition p's
-// segment starts at the scan value of its first block.
+// list: a pair's output position is the number of selected gradients in front
+// of it, and partition p's segment starts at the sum of the counts of the
+// partitions before it.
+//
+// No device-scope fence or "last workgroup done" ticket is used anywhere: on
+// this multi-die part such a fence per workgroup costs far more than a second
+// launch.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -37,7 +46,10 @@ constexpr uint32_t kGranWords   = 8;    // mask words per granule
 constexpr uint32_t kStreamWG    = 256;  // threads per workgroup in k_stream
 constexpr uint32_t kWavesPerWG  = 4;
 constexpr uint32_t kMaxParts    = 1024;
-constexpr uint32_t kCtrlThreads = 1024;
+constexpr uint32_t kFinishWG    = 1024; // k_finish: 16 waves = control, or 16 blocks
+constexpr uint32_t kSupShift    = 6;    // one coarse counter per 64 blocks ...
+constexpr uint32_t kSupThreshold = 32768; // ... built only above this many blocks
+constexpr uint64_t kMaxBlocks   = 1u << 20;
 constexpr uint32_t kErrSlots    = 256;
 constexpr uint64_t kMagic       = 0x45784479'6e61'0001ull;
 
@@ -70,9 +82,9 @@ struct CtrlParams {
 };
 
 struct Layout {
-    size_t state, kvec, parts, part_cnt, part_off, blk_cnt, blk_off, err_slots, mask, out_idx,
+    size_t state, kvec, parts, part_cnt, part_off, blk_cnt, sup_cnt, err_slots, mask, out_idx,
         out_val, total;
-    size_t mask_words;
+    size_t mask_words, n_sup;
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -119,6 +131,8 @@ __device__ __forceinline__ void publish_granule(uint32_t gran, uint32_t nib, uin
         if ((lane & 7u) == 0) mw[lane >> 3] = v;
         const uint32_t cnt = __popcll(__ballot(nib & 1u)) + __popcll(__ballot(nib & 2u)) +
                              __popcll(__ballot(nib & 4u)) + __popcll(__ballot(nib & 8u));
+        // one counter per block keeps same-address atomics rare (they serialise
+        // at roughly 150 ns each across the dies)
         if (lane == 0) atomicAdd(&blk_cnt[gran / gran_per_blk], cnt);
     }
 }
@@ -146,7 +160,7 @@ k_stream(const float *__restrict__ g, float *__restrict__ e, const DevState *__r
         for (int u = 0; u < U; ++u) {
             const size_t off = ((size_t)(gran0 + u * kWavesPerWG + wave) << 8) + lane * 4u;
             gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g + off));
-            ev[u] = *reinterpret_cast<const f32x4 *>(e + off);
+            ev[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(e + off));
         }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
@@ -157,7 +171,7 @@ k_stream(const float *__restrict__ g, float *__restrict__ e, const DevState *__r
             a.y = ev[u].y + gv[u].y;
             a.z = ev[u].z + gv[u].z;
             a.w = ev[u].w + gv[u].w;
-            *reinterpret_cast<f32x4 *>(e + off) = a;
+            __builtin_nontemporal_store(a, reinterpret_cast<f32x4 *>(e + off));
             const uint32_t nib = sel<CMP>(a.x, delta) | (sel<CMP>(a.y, delta) << 1) |
                                  (sel<CMP>(a.z, delta) << 2) | (sel<CMP>(a.w, delta) << 3);
             if (NORM) {
@@ -205,19 +219,48 @@ k_stream(const float *__restrict__ g, float *__restrict__ e, const DevState *__r
 }
 
 // ---------------------------------------------------------------------------
-// k_control: one workgroup of 1024 threads.
-//   cur  = topology slot the finished k_stream's iteration selects with
-//   next = slot receiving Alg. 3's adjusted topology for the next iteration
-__global__ void __launch_bounds__(kCtrlThreads)
-k_control(DevState *__restrict__ st, const uint32_t *__restrict__ blk_cnt,
-          uint32_t *__restrict__ blk_cnt_next, uint32_t *__restrict__ blk_off,
-          const int32_t *__restrict__ cur_part, const int32_t *__restrict__ cur_pos,
-          int32_t *__restrict__ nxt_part, int32_t *__restrict__ nxt_pos,
-          double *__restrict__ kvec, uint64_t *__restrict__ part_cnt,
-          uint64_t *__restrict__ part_off, double *__restrict__ err_slots_next, CtrlParams prm)
+struct FinishArgs {
+    DevState       *st;
+    float          *e;
+    const uint32_t *mask;
+    const uint32_t *blk_cnt;       // this iteration's per-block counters (complete)
+    const uint32_t *sup_cnt;       // sums of 64 counters each; only valid when use_sup
+    uint32_t       *blk_cnt_next;  // the other parity's counters, cleared here
+    const int32_t  *cur_part;      // topology this iteration selected with
+    const int32_t  *cur_pos;
+    int32_t        *nxt_part;      // receives Alg. 3's adjusted topology
+    int32_t        *nxt_pos;
+    double         *kvec;
+    uint64_t       *part_cnt;
+    uint64_t       *part_off;
+    uint32_t       *out_idx;
+    float          *out_val;
+    double         *err_slots;       // this iteration's norm partials
+    double         *err_slots_next;  // cleared here
+    uint32_t        use_sup;
+};
+
+// Only for very many blocks (n_b > kSupThreshold): sup_cnt[i] = sum of the 64
+// block counters of group i, one wavefront per group.
+__global__ void __launch_bounds__(kFinishWG)
+k_sup(const uint32_t *__restrict__ blk_cnt, uint32_t *__restrict__ sup_cnt, uint32_t n_b,
+      uint32_t n_sup)
 {
-    __shared__ uint32_t wsum[kCtrlThreads / 64];
-    __shared__ uint32_t tile_total;
+    const uint32_t i = blockIdx.x * (kFinishWG / 64) + (threadIdx.x >> 6);
+    if (i >= n_sup) return;
+    const uint32_t idx = (i << kSupShift) + (threadIdx.x & 63u);
+    uint32_t s = idx < n_b ? blk_cnt[idx] : 0u;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+    if ((threadIdx.x & 63u) == 0) sup_cnt[i] = s;
+}
+
+// ---- control: workgroup 0 of k_finish (1024 threads) ----
+__device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
+{
+    __shared__ uint32_t cnt_s[kMaxParts];
+    __shared__ uint32_t wsum[kFinishWG / 64];
+    __shared__ uint64_t k_total;
     __shared__ double   kv[kMaxParts];
     __shared__ int32_t  lpart[kMaxParts];
     __shared__ int32_t  lpos[kMaxParts];
@@ -225,65 +268,61 @@ k_control(DevState *__restrict__ st, const uint32_t *__restrict__ blk_cnt,
     const uint32_t tid  = threadIdx.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wave = tid >> 6;
-    const uint32_t n_b  = prm.n_b;
     const uint32_t P    = prm.n_parts;
+    const uint32_t n_b  = prm.n_b;
 
-    // ---- exclusive scan of the per-block counts, 4096 blocks per tile ----
-    uint32_t carry = 0;
-    for (uint32_t base = 0; base < n_b; base += kCtrlThreads * 4u) {
-        const uint32_t i0 = base + tid * 4u;
-        uint32_t c[4];
-#pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            c[q] = (i0 + q < n_b) ? blk_cnt[i0 + q] : 0u;
-            if (i0 + q < n_b) blk_cnt_next[i0 + q] = 0u;  // clean counters for the next iteration
-        }
-        const uint32_t s    = c[0] + c[1] + c[2] + c[3];
-        const uint32_t incl = wave_incl_scan(s, lane);
-        if (lane == 63) wsum[wave] = incl;
-        __syncthreads();
-        if (wave == 0) {
-            const uint32_t v  = lane < kCtrlThreads / 64 ? wsum[lane] : 0u;
-            const uint32_t vi = wave_incl_scan(v, lane);
-            if (lane < kCtrlThreads / 64) wsum[lane] = vi - v;
-            if (lane == kCtrlThreads / 64 - 1) tile_total = vi;
-        }
-        __syncthreads();
-        uint32_t excl = carry + wsum[wave] + (incl - s);
-#pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            if (i0 + q < n_b) blk_off[i0 + q] = excl;
-            excl += c[q];
-        }
-        carry += tile_total;
-        __syncthreads();
+    if (tid < P) {
+        cnt_s[tid] = 0u;
+        lpart[tid] = A.cur_part[tid];
+        lpos[tid]  = A.cur_pos[tid];
     }
-    if (tid == 0) blk_off[n_b] = carry;
-    if (tid < kErrSlots) err_slots_next[tid] = 0.0;
+    if (tid < kErrSlots) A.err_slots_next[tid] = 0.0;
     __syncthreads();
-    const uint64_t k_actual = carry;  // k' (Alg. 1 line 13)
 
-    // ---- per-partition counts and output segment starts ----
-    for (uint32_t p = tid; p < P; p += kCtrlThreads) {
-        const int32_t  pos  = cur_pos[p];
-        const int32_t  part = cur_part[p];
-        const uint32_t lo   = blk_off[pos];
-        const uint32_t hi   = blk_off[pos + part];
-        const uint64_t cnt  = (uint64_t)(hi - lo);
-        part_cnt[p] = cnt;
-        part_off[p] = lo < prm.cap ? (uint64_t)lo : prm.cap;
-        kv[p]    = (double)cnt;  // this iteration's k_{p,t} feeds the next Allocate (Alg. 1 line 15)
-        lpart[p] = part;
-        lpos[p]  = pos;
+    // k_{p,t} (Sec. 4.2: the workload of a partition): every thread walks a
+    // strided share of the block counters and adds each non-zero one to the
+    // partition that holds the block (largest p with blk_pos[p] <= block).
+    for (uint32_t i = tid; i < n_b; i += kFinishWG) {
+        const uint32_t c = A.blk_cnt[i];
+        if (c) {
+            uint32_t lo = 0, hi = P - 1;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi + 1) >> 1;
+                if ((uint32_t)lpos[mid] <= i) lo = mid; else hi = mid - 1;
+            }
+            atomicAdd(&cnt_s[lo], c);
+        }
     }
+    __syncthreads();
+
+    // exclusive scan of the P counts (P <= 1024 = one value per thread)
+    const uint32_t c    = tid < P ? cnt_s[tid] : 0u;
+    const uint32_t incl = wave_incl_scan(c, lane);
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t v  = lane < kFinishWG / 64 ? wsum[lane] : 0u;
+        const uint32_t vi = wave_incl_scan(v, lane);
+        if (lane < kFinishWG / 64) wsum[lane] = vi - v;
+    }
+    __syncthreads();
+    const uint64_t excl = (uint64_t)wsum[wave] + (incl - c);
+    if (tid < P) {
+        A.part_cnt[tid] = c;
+        A.part_off[tid] = excl < prm.cap ? excl : prm.cap;
+        kv[tid] = (double)c;  // this iteration's k_{p,t} feeds the next Allocate (Alg. 1 line 15)
+    }
+    if (tid == P - 1) k_total = excl + c;
     __syncthreads();
 
     if (tid == 0) {
-        part_off[P] = k_actual < prm.cap ? k_actual : prm.cap;
+        const uint64_t k_actual = k_total;  // k' (Alg. 1 line 13)
+        A.part_off[P] = k_actual < prm.cap ? k_actual : prm.cap;
 
         // ---- Alg. 5: online threshold scaling ----
-        const float  delta = st->delta;
-        const double exam  = (double)k_actual / prm.k;
+        DevState   *st    = A.st;
+        const float delta = st->delta;
+        const double exam = (double)k_actual / prm.k;
         float sf;
         if (exam > prm.beta)
             sf = prm.sf_hi;
@@ -297,8 +336,8 @@ k_control(DevState *__restrict__ st, const uint32_t *__restrict__ blk_cnt,
         // ---- Eq. 2 / 5 / 6 ----
         uint64_t m_t = 0;
         for (uint32_t p = 0; p < P; ++p) {
-            const uint64_t c = (uint64_t)kv[p];
-            if (c > m_t) m_t = c;
+            const uint64_t cp = (uint64_t)kv[p];
+            if (cp > m_t) m_t = cp;
         }
         st->k_actual      = k_actual;
         st->k_emitted     = k_actual < prm.cap ? k_actual : prm.cap;
@@ -345,36 +384,61 @@ k_control(DevState *__restrict__ st, const uint32_t *__restrict__ blk_cnt,
         st->moves = moves;
     }
     __syncthreads();
-    for (uint32_t p = tid; p < P; p += kCtrlThreads) {
-        nxt_part[p] = lpart[p];
-        nxt_pos[p]  = lpos[p];
-        kvec[p]     = kv[p];
+    if (tid < P) {
+        A.nxt_part[tid] = lpart[tid];
+        A.nxt_pos[tid]  = lpos[tid];
+        A.kvec[tid]     = kv[tid];
     }
 }
 
-// ---------------------------------------------------------------------------
-// k_compact: one wavefront per block.  Each lane takes four consecutive mask
-// words (128 gradients); a wave scan of the popcounts gives every lane the
-// rank of its first set bit, so pairs come out in ascending index order.
+// ---- compaction: a workgroup takes 16 consecutive blocks, one wavefront per
+// block.  The workgroup first sums the counters in front of its first block
+// (all 1024 threads, counters sit in L2), which is the output position of its
+// first pair.  Then each lane takes four consecutive mask words (128
+// gradients); a wave scan of the popcounts gives every lane the rank of its
+// first set bit, so pairs come out in ascending index order. ----
 template <bool NORM>
-__global__ void __launch_bounds__(256)
-k_compact(float *__restrict__ e, const uint32_t *__restrict__ mask,
-          const uint32_t *__restrict__ blk_cnt, const uint32_t *__restrict__ blk_off,
-          uint32_t *__restrict__ out_idx, float *__restrict__ out_val,
-          double *__restrict__ err_slots, uint32_t n_b, uint32_t block_size, uint32_t n_g,
-          uint64_t cap)
+__device__ void finish_compact(const FinishArgs &A, uint32_t n_b, uint32_t block_size, uint32_t n_g,
+                               uint64_t cap)
 {
-    const uint32_t lane = threadIdx.x & 63u;
-    const uint32_t j    = blockIdx.x * 4u + (threadIdx.x >> 6);
+    __shared__ uint32_t red[kFinishWG / 64];
+    __shared__ uint32_t wcnt[kFinishWG / 64];
+    const uint32_t tid  = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = tid >> 6;
+    const uint32_t j0   = (blockIdx.x - 1u) * (kFinishWG / 64);
+    const uint32_t j    = j0 + wave;
+
+    uint32_t s = 0;
+    if (A.use_sup) {
+        const uint32_t sb = j0 >> kSupShift;
+        for (uint32_t i = tid; i < sb; i += kFinishWG) s += A.sup_cnt[i];
+        for (uint32_t i = (sb << kSupShift) + tid; i < j0; i += kFinishWG) s += A.blk_cnt[i];
+    } else {
+        for (uint32_t i = tid; i < j0; i += kFinishWG) s += A.blk_cnt[i];
+    }
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+    const uint32_t cnt_j = j < n_b ? A.blk_cnt[j] : 0u;
+    if (lane == 0) {
+        red[wave]  = s;
+        wcnt[wave] = cnt_j;
+    }
+    __syncthreads();
     if (j >= n_b) return;
-    if (blk_cnt[j] == 0) return;
-    const uint64_t base = blk_off[j];
+    uint64_t base = 0;  // selected gradients in front of block j = its output position
+#pragma unroll
+    for (uint32_t w = 0; w < kFinishWG / 64; ++w) base += red[w] + (w < wave ? wcnt[w] : 0u);
+
+    if (lane == 0) A.blk_cnt_next[j] = 0u;  // clean counter for the next iteration
+    if (cnt_j == 0) return;
     if (!NORM && base >= cap) return;  // nothing of this block fits: it all stays in the residual
 
+    float *__restrict__ e = A.e;
     const uint64_t first = (uint64_t)j * block_size;
     const uint32_t len   = (uint64_t)n_g - first < block_size ? (uint32_t)(n_g - first) : block_size;
     const uint32_t words = (((len + 31u) >> 5) + 3u) & ~3u;
-    const uint4   *m4    = reinterpret_cast<const uint4 *>(mask + (size_t)j * (block_size >> 5));
+    const uint4   *m4    = reinterpret_cast<const uint4 *>(A.mask + (size_t)j * (block_size >> 5));
     uint64_t running = base;
     float    spill   = 0.f;
 
@@ -396,9 +460,9 @@ k_compact(float *__restrict__ e, const uint32_t *__restrict__ mask,
                 bits &= bits - 1u;
                 if (r < cap) {
                     const float v = e[i];
-                    out_idx[r] = i;
-                    out_val[r] = v;
-                    e[i]       = 0.0f;  // +0 where sent (Alg. 1 line 17)
+                    A.out_idx[r] = i;
+                    A.out_val[r] = v;
+                    e[i]         = 0.0f;  // +0 where sent (Alg. 1 line 17)
                 } else if (NORM) {
                     const float v = e[i];  // selected but not emitted: stays in the residual
                     spill += v * v;
@@ -409,11 +473,21 @@ k_compact(float *__restrict__ e, const uint32_t *__restrict__ mask,
         running += tot;
     }
     if (NORM) {
-        double s = (double)spill;
+        double sq = (double)spill;
 #pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
-        if (lane == 0 && s != 0.0) atomicAdd(&err_slots[j % kErrSlots], s);
+        for (int d = 32; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, 64);
+        if (lane == 0 && sq != 0.0) atomicAdd(&A.err_slots[j % kErrSlots], sq);
     }
+}
+
+template <bool NORM>
+__global__ void __launch_bounds__(kFinishWG)
+k_finish(FinishArgs A, CtrlParams prm)
+{
+    if (blockIdx.x == 0)
+        finish_control(A, prm);
+    else
+        finish_compact<NORM>(A, prm.n_b, prm.block_size, (uint32_t)prm.n_g, prm.cap);
 }
 
 // ---------------------------------------------------------------------------
@@ -484,7 +558,7 @@ struct exdyna_ctx {
     hipStream_t   stream;  // stream of the most recent call
     uint32_t      prof_slots;  // 0 = profiling off
     uint64_t      prof_since;  // first iteration recorded with the current events
-    hipEvent_t   *ev;          // prof_slots x 4 events, slot = iteration % prof_slots
+    hipEvent_t   *ev;          // prof_slots x 3 events, slot = iteration % prof_slots
     char          hip_err[256];
 };
 
@@ -495,6 +569,7 @@ int validate_config(const exdyna_config *c, uint64_t *n_b_out, uint64_t *cap_out
     if (c->n_g == 0 || c->n_g > 0xFFFFFFFFull) return EXDYNA_EINVAL;
     if (c->block_size == 0 || c->block_size % kGran != 0) return EXDYNA_EINVAL;
     const uint64_t n_b = (c->n_g + c->block_size - 1) / c->block_size;
+    if (n_b > kMaxBlocks) return EXDYNA_EINVAL;
     if (c->n_parts == 0 || c->n_parts > n_b || c->n_parts > kMaxParts) return EXDYNA_EINVAL;
     if (!(c->density > 0.0 && c->density <= 1.0)) return EXDYNA_EINVAL;
     if (!(c->threshold0 > 0.0f) || std::isinf(c->threshold0)) return EXDYNA_EINVAL;
@@ -529,7 +604,8 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
     L.part_cnt  = take(P * sizeof(uint64_t));
     L.part_off  = take((P + 1) * sizeof(uint64_t));
     L.blk_cnt   = take(2 * n_b * sizeof(uint32_t));      // two alternating counter arrays
-    L.blk_off   = take((n_b + 1) * sizeof(uint32_t));
+    L.n_sup     = (n_b >> kSupShift) + 1;
+    L.sup_cnt   = take(L.n_sup * sizeof(uint32_t));      // coarse counters (many-block case)
     L.err_slots = take(2 * kErrSlots * sizeof(double));
     L.mask_words = n_gran * kGranWords;
     L.mask      = take(L.mask_words * sizeof(uint32_t));
@@ -661,8 +737,8 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
                        reinterpret_cast<uint32_t *>(d_residual), 0u, (size_t)cfg->n_g);
     hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
                        (size_t)(2 * n_b));
-    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_off), 0u,
-                       (size_t)(n_b + 1));
+    hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.sup_cnt), 0u,
+                       (size_t)L.n_sup);
     hipLaunchKernelGGL(k_fill_u32, dim3(1024), dim3(256), 0, s, at<uint32_t>(c, L.mask), 0u,
                        L.mask_words);
     const uint32_t init_threads = (P + 1 > 2 * kErrSlots ? P + 1 : 2 * kErrSlots);
@@ -690,7 +766,7 @@ int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
     c->stream = s;
     const bool norm = c->cfg.want_err_norm != 0;
     const bool prof = c->prof_slots != 0;
-    hipEvent_t *ev = prof ? c->ev + 4 * (c->t % c->prof_slots) : nullptr;
+    hipEvent_t *ev = prof ? c->ev + 3 * (c->t % c->prof_slots) : nullptr;
 
     if (prof) HIP_TRY(c, hipEventRecord(ev[0], s));
     if (c->cfg.cmp_mode == 0) {
@@ -701,27 +777,38 @@ int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
     if (prof) HIP_TRY(c, hipEventRecord(ev[1], s));
 
     const uint64_t t = c->t;
-    hipLaunchKernelGGL(k_control, dim3(1), dim3(kCtrlThreads), 0, s, at<DevState>(c, c->lay.state),
-                       blk_cnt_of(c, t), blk_cnt_of(c, t + 1), at<uint32_t>(c, c->lay.blk_off),
-                       slot_part(c, t), slot_pos(c, t), slot_part(c, t + 1), slot_pos(c, t + 1),
-                       at<double>(c, c->lay.kvec), at<uint64_t>(c, c->lay.part_cnt),
-                       at<uint64_t>(c, c->lay.part_off), err_slots_of(c, t + 1), c->prm);
-    if (prof) HIP_TRY(c, hipEventRecord(ev[2], s));
-
-    const uint32_t grid = (uint32_t)((c->n_b + 3) / 4);
+    FinishArgs A;
+    A.st = at<DevState>(c, c->lay.state);
+    A.e = c->d_residual;
+    A.mask = at<uint32_t>(c, c->lay.mask);
+    A.blk_cnt = blk_cnt_of(c, t);
+    A.sup_cnt = at<uint32_t>(c, c->lay.sup_cnt);
+    A.blk_cnt_next = blk_cnt_of(c, t + 1);
+    A.use_sup = c->n_b > kSupThreshold ? 1u : 0u;
+    if (A.use_sup) {
+        const uint32_t n_sup = (uint32_t)c->lay.n_sup;
+        hipLaunchKernelGGL(k_sup, dim3((n_sup + kFinishWG / 64 - 1) / (kFinishWG / 64)),
+                           dim3(kFinishWG), 0, s, A.blk_cnt, at<uint32_t>(c, c->lay.sup_cnt),
+                           (uint32_t)c->n_b, n_sup);
+    }
+    A.cur_part = slot_part(c, t);
+    A.cur_pos = slot_pos(c, t);
+    A.nxt_part = slot_part(c, t + 1);
+    A.nxt_pos = slot_pos(c, t + 1);
+    A.kvec = at<double>(c, c->lay.kvec);
+    A.part_cnt = at<uint64_t>(c, c->lay.part_cnt);
+    A.part_off = at<uint64_t>(c, c->lay.part_off);
+    A.out_idx = at<uint32_t>(c, c->lay.out_idx);
+    A.out_val = at<float>(c, c->lay.out_val);
+    A.err_slots = err_slots_of(c, t);
+    A.err_slots_next = err_slots_of(c, t + 1);
+    const uint32_t per_wg = kFinishWG / 64;
+    const uint32_t grid = 1u + (uint32_t)((c->n_b + per_wg - 1) / per_wg);
     if (norm)
-        hipLaunchKernelGGL(k_compact<true>, dim3(grid), dim3(256), 0, s, c->d_residual,
-                           at<uint32_t>(c, c->lay.mask), blk_cnt_of(c, t),
-                           at<uint32_t>(c, c->lay.blk_off), at<uint32_t>(c, c->lay.out_idx),
-                           at<float>(c, c->lay.out_val), err_slots_of(c, t), (uint32_t)c->n_b,
-                           c->cfg.block_size, (uint32_t)c->cfg.n_g, c->cap);
+        hipLaunchKernelGGL(k_finish<true>, dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
     else
-        hipLaunchKernelGGL(k_compact<false>, dim3(grid), dim3(256), 0, s, c->d_residual,
-                           at<uint32_t>(c, c->lay.mask), blk_cnt_of(c, t),
-                           at<uint32_t>(c, c->lay.blk_off), at<uint32_t>(c, c->lay.out_idx),
-                           at<float>(c, c->lay.out_val), err_slots_of(c, t), (uint32_t)c->n_b,
-                           c->cfg.block_size, (uint32_t)c->cfg.n_g, c->cap);
-    if (prof) HIP_TRY(c, hipEventRecord(ev[3], s));
+        hipLaunchKernelGGL(k_finish<false>, dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
+    if (prof) HIP_TRY(c, hipEventRecord(ev[2], s));
     HIP_TRY(c, hipGetLastError());
     c->t = t + 1;
     return EXDYNA_OK;
@@ -840,7 +927,7 @@ namespace {
 void drop_events(exdyna_ctx *c)
 {
     if (c->ev) {
-        for (uint32_t i = 0; i < 4 * c->prof_slots; ++i) (void)hipEventDestroy(c->ev[i]);
+        for (uint32_t i = 0; i < 3 * c->prof_slots; ++i) (void)hipEventDestroy(c->ev[i]);
         free(c->ev);
     }
     c->ev = nullptr;
@@ -857,9 +944,9 @@ int exdyna_set_profiling(exdyna_ctx *c, uint32_t n_slots)
         drop_events(c);
     }
     if (n_slots == 0) return EXDYNA_OK;
-    c->ev = static_cast<hipEvent_t *>(calloc(4 * (size_t)n_slots, sizeof(hipEvent_t)));
+    c->ev = static_cast<hipEvent_t *>(calloc(3 * (size_t)n_slots, sizeof(hipEvent_t)));
     if (!c->ev) return EXDYNA_ENOMEM;
-    for (uint32_t i = 0; i < 4 * n_slots; ++i) {
+    for (uint32_t i = 0; i < 3 * n_slots; ++i) {
         hipError_t e = hipEventCreate(&c->ev[i]);
         if (e != hipSuccess) {
             for (uint32_t j = 0; j < i; ++j) (void)hipEventDestroy(c->ev[j]);
@@ -873,17 +960,17 @@ int exdyna_set_profiling(exdyna_ctx *c, uint32_t n_slots)
     return EXDYNA_OK;
 }
 
-int exdyna_get_kernel_ms(exdyna_ctx *c, uint64_t iteration, float *h_ms3)
+int exdyna_get_kernel_ms(exdyna_ctx *c, uint64_t iteration, float *h_ms2)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
-    if (!h_ms3) return EXDYNA_ENULL;
+    if (!h_ms2) return EXDYNA_ENULL;
     if (!c->prof_slots) return EXDYNA_ESTATE;
     // only iterations enqueued while profiling was on and not yet overwritten
     if (iteration >= c->t || iteration < c->prof_since || c->t - iteration > c->prof_slots)
         return EXDYNA_EINVAL;
-    hipEvent_t *ev = c->ev + 4 * (iteration % c->prof_slots);
-    HIP_TRY(c, hipEventSynchronize(ev[3]));
-    for (int i = 0; i < 3; ++i) HIP_TRY(c, hipEventElapsedTime(&h_ms3[i], ev[i], ev[i + 1]));
+    hipEvent_t *ev = c->ev + 3 * (iteration % c->prof_slots);
+    HIP_TRY(c, hipEventSynchronize(ev[2]));
+    for (int i = 0; i < 2; ++i) HIP_TRY(c, hipEventElapsedTime(&h_ms2[i], ev[i], ev[i + 1]));
     return EXDYNA_OK;
 }
 

@@ -60,6 +60,7 @@ def test_workspace_bytes_accepts_the_five_configurations():
     dict(threshold0=float("inf")), dict(threshold0=float("nan")), dict(cmp_mode=2),
     dict(alpha=0.99), dict(alpha=float("nan")), dict(beta=1.0), dict(gamma=0.0), dict(gamma=1.0),
     dict(min_blk=0), dict(reserved=1), dict(max_selected=(1 << 20) + 1),
+    dict(n_g=1 << 29, block_size=256),        # more than 2^20 blocks
 ])
 def test_bad_configurations_are_rejected(bad):
     with pytest.raises(binding.ExDynaError) as ei:

@@ -138,6 +138,16 @@ def test_partition_count_extremes():
     x.close()
 
 
+def test_many_small_blocks_use_the_coarse_counter_path():
+    """More than 32768 blocks: the finishing kernel reads per-64-block sums built by a pre-pass."""
+    n = 256 * 40_000 + 100
+    w = synthetic.WORKLOADS[5].scaled(n, 256, 1024)
+    log("case n_b = 40001")
+    x, o = make_pair(n, 256, 1024, 0.002, _thr(w))
+    run_trajectory(x, o, _grads(w, 4), tag="nb40001")
+    x.close()
+
+
 def test_rebalancing_reduces_traffic_ratio():
     """Sec. 5.3: with the skewed-head workload f(t) (Eq. 5) falls as blocks migrate."""
     n = 1_000_000
