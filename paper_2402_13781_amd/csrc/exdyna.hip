@@ -238,6 +238,7 @@ struct FinishArgs {
     double         *err_slots;       // this iteration's norm partials
     double         *err_slots_next;  // cleared here
     uint32_t        use_sup;
+    uint64_t        t_next;          // iterations completed once this kernel is done
 };
 
 // Only for very many blocks (n_b > kSupThreshold): sup_cnt[i] = sum of the 64
@@ -256,14 +257,18 @@ k_sup(const uint32_t *__restrict__ blk_cnt, uint32_t *__restrict__ sup_cnt, uint
 }
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
+// Everything that can be done side by side is (counts, scan, the fp64
+// quotients of Alg. 3); only the decision chain of the sweep runs on one lane.
 __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 {
     __shared__ uint32_t cnt_s[kMaxParts];
     __shared__ uint32_t wsum[kFinishWG / 64];
+    __shared__ uint32_t wmax[kFinishWG / 64];
     __shared__ uint64_t k_total;
-    __shared__ double   kv[kMaxParts];
     __shared__ int32_t  lpart[kMaxParts];
     __shared__ int32_t  lpos[kMaxParts];
+    __shared__ uint8_t  flags[kMaxParts];
+    __shared__ double   kv_out[kMaxParts];
 
     const uint32_t tid  = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -271,6 +276,8 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     const uint32_t P    = prm.n_parts;
     const uint32_t n_b  = prm.n_b;
 
+    float delta = 0.f;
+    if (tid == 0) delta = A.st->delta;  // in flight while the counts are gathered
     if (tid < P) {
         cnt_s[tid] = 0u;
         lpart[tid] = A.cur_part[tid];
@@ -282,46 +289,85 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     // k_{p,t} (Sec. 4.2: the workload of a partition): every thread walks a
     // strided share of the block counters and adds each non-zero one to the
     // partition that holds the block (largest p with blk_pos[p] <= block).
-    for (uint32_t i = tid; i < n_b; i += kFinishWG) {
-        const uint32_t c = A.blk_cnt[i];
-        if (c) {
-            uint32_t lo = 0, hi = P - 1;
-            while (lo < hi) {
-                const uint32_t mid = (lo + hi + 1) >> 1;
-                if ((uint32_t)lpos[mid] <= i) lo = mid; else hi = mid - 1;
+    for (uint32_t i0 = tid; i0 < n_b; i0 += 4u * kFinishWG) {
+        uint32_t c[4];
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            const uint32_t i = i0 + q * kFinishWG;
+            c[q] = i < n_b ? A.blk_cnt[i] : 0u;
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            if (c[q]) {
+                const uint32_t i = i0 + q * kFinishWG;
+                uint32_t lo = 0, hi = P - 1;
+                while (lo < hi) {
+                    const uint32_t mid = (lo + hi + 1) >> 1;
+                    if ((uint32_t)lpos[mid] <= i) lo = mid; else hi = mid - 1;
+                }
+                atomicAdd(&cnt_s[lo], c[q]);
             }
-            atomicAdd(&cnt_s[lo], c);
         }
     }
     __syncthreads();
 
-    // exclusive scan of the P counts (P <= 1024 = one value per thread)
+    // exclusive scan and maximum of the P counts (P <= 1024 = one value per thread)
     const uint32_t c    = tid < P ? cnt_s[tid] : 0u;
     const uint32_t incl = wave_incl_scan(c, lane);
+    uint32_t mx = c;
+#pragma unroll
+    for (int d = 32; d >= 1; d >>= 1) {
+        const uint32_t o = __shfl_xor(mx, d, 64);
+        mx = o > mx ? o : mx;
+    }
     if (lane == 63) wsum[wave] = incl;
+    if (lane == 0) wmax[wave] = mx;
     __syncthreads();
     if (wave == 0) {
         const uint32_t v  = lane < kFinishWG / 64 ? wsum[lane] : 0u;
         const uint32_t vi = wave_incl_scan(v, lane);
         if (lane < kFinishWG / 64) wsum[lane] = vi - v;
+        if (lane == kFinishWG / 64 - 1) k_total = vi;  // k' (Alg. 1 line 13)
     }
     __syncthreads();
-    const uint64_t excl = (uint64_t)wsum[wave] + (incl - c);
+    const uint64_t excl     = (uint64_t)wsum[wave] + (incl - c);
+    const uint64_t k_actual = k_total;
     if (tid < P) {
         A.part_cnt[tid] = c;
         A.part_off[tid] = excl < prm.cap ? excl : prm.cap;
-        kv[tid] = (double)c;  // this iteration's k_{p,t} feeds the next Allocate (Alg. 1 line 15)
     }
-    if (tid == P - 1) k_total = excl + c;
+
+    // Alg. 3 lines 8-10 and the comparisons of lines 13 / 21, for every pair at
+    // once.  This iteration's counts are the next Allocate's partial-k vector
+    // (Alg. 1 line 15); they are integers, so their fp64 sum is k' exactly.
+    // When pair i is inspected, k[i] is its count c, or c +/- k_move if pair
+    // i-1 moved blocks, and k[i+1] is still its count: quotients for the three
+    // cases, compared against alpha and 1/alpha, go into six flag bits.
+    const double sum      = (double)k_actual;
+    const double pk_prev  = sum / (double)P;
+    const double den_prev = sum / (double)prm.n_g;
+    const double k_move   = (double)prm.blk_move * (double)prm.block_size * den_prev;
+    if (tid < P) {
+        uint32_t f = 0;
+        if (k_actual) {
+            const double kc = (double)c;
+            const double d0 = kc / pk_prev;
+            const double dp = (kc + k_move) / pk_prev;
+            const double dm = (kc - k_move) / pk_prev;
+            f = (d0 > prm.alpha ? 1u : 0u) | (d0 < prm.inv_alpha ? 2u : 0u) |
+                (dp > prm.alpha ? 4u : 0u) | (dp < prm.inv_alpha ? 8u : 0u) |
+                (dm > prm.alpha ? 16u : 0u) | (dm < prm.inv_alpha ? 32u : 0u);
+        }
+        flags[tid]  = (uint8_t)f;
+        kv_out[tid] = (double)c;
+    }
     __syncthreads();
 
     if (tid == 0) {
-        const uint64_t k_actual = k_total;  // k' (Alg. 1 line 13)
         A.part_off[P] = k_actual < prm.cap ? k_actual : prm.cap;
 
         // ---- Alg. 5: online threshold scaling ----
-        DevState   *st    = A.st;
-        const float delta = st->delta;
+        DevState   *st   = A.st;
         const double exam = (double)k_actual / prm.k;
         float sf;
         if (exam > prm.beta)
@@ -335,50 +381,58 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 
         // ---- Eq. 2 / 5 / 6 ----
         uint64_t m_t = 0;
-        for (uint32_t p = 0; p < P; ++p) {
-            const uint64_t cp = (uint64_t)kv[p];
-            if (cp > m_t) m_t = cp;
-        }
+        for (uint32_t w = 0; w < kFinishWG / 64; ++w) m_t = wmax[w] > m_t ? wmax[w] : m_t;
         st->k_actual      = k_actual;
         st->k_emitted     = k_actual < prm.cap ? k_actual : prm.cap;
         st->overflow      = k_actual > prm.cap ? 1u : 0u;
         st->k_max_part    = m_t;
         st->density_error = fabs(prm.k - (double)k_actual) / (double)prm.n_g;
         st->traffic_ratio = k_actual ? (double)P * (double)m_t / (double)k_actual : 0.0;
-        st->t += 1;
+        st->t = A.t_next;
 
-        // ---- Alg. 3 lines 8-28: sweep over adjacent pairs, sequential by
-        // construction (pair i sees pair i-1's updated estimate) ----
+        // ---- Alg. 3 lines 11-28: the decision chain, pair by pair.  `adj` says
+        // what pair i-1 did to k[i]: 0 nothing, 1 added k_move, 2 subtracted it.
         uint32_t moves = 0;
-        double   sum   = 0.0;
-        for (uint32_t p = 0; p < P; ++p) sum += kv[p];
-        if (sum > 0.0) {
-            const double  pk_prev  = sum / (double)P;
-            const double  den_prev = sum / (double)prm.n_g;
-            const int64_t blk_move = (int64_t)prm.blk_move;
-            const int64_t min_blk  = (int64_t)prm.min_blk;
+        if (k_actual) {
+            const int32_t bm      = (int32_t)prm.blk_move;
+            const int64_t min_blk = (int64_t)prm.min_blk;
+            uint32_t adj = 0;
+            int32_t  part_i = lpart[0];
+            uint32_t f_i = flags[0];
             for (uint32_t i = 0; i + 1 < P; ++i) {
-                const double det    = kv[i] / pk_prev;
-                const double det2   = kv[i + 1] / pk_prev;
-                const double k_move = (double)prm.blk_move * (double)prm.block_size * den_prev;
-                if (det > prm.alpha && det2 < prm.inv_alpha) {
-                    if ((int64_t)lpart[i] - blk_move < min_blk) continue;
-                    lpart[i]     -= (int32_t)blk_move;
-                    lpart[i + 1] += (int32_t)blk_move;
-                    lpos[i + 1]  -= (int32_t)blk_move;
-                    kv[i]        -= k_move;
-                    kv[i + 1]    += k_move;
-                    ++moves;
-                }
-                if (det < prm.inv_alpha && det2 > prm.alpha) {
-                    if ((int64_t)lpart[i + 1] - blk_move < min_blk) continue;
-                    lpart[i]     += (int32_t)blk_move;
-                    lpart[i + 1] -= (int32_t)blk_move;
-                    lpos[i + 1]  += (int32_t)blk_move;
-                    kv[i]        += k_move;
-                    kv[i + 1]    -= k_move;
-                    ++moves;
-                }
+                const uint32_t f_n    = flags[i + 1];
+                const int32_t  part_n = lpart[i + 1];
+                const uint32_t fi     = f_i >> (2u * adj);
+                const bool det_hi = fi & 1u, det_lo = fi & 2u;      // det > alpha, det < 1/alpha
+                const bool det2_hi = f_n & 1u, det2_lo = f_n & 2u;  // same for det2
+                uint32_t adj_n  = 0;
+                int32_t  part_o = part_n;  // blk_part[i+1] after this pair
+                do {
+                    if (det_hi && det2_lo) {
+                        if ((int64_t)part_i - bm < min_blk) break;  // "continue" of line 15
+                        lpart[i]    = part_i - bm;
+                        part_o      = part_n + bm;
+                        lpos[i + 1] -= bm;
+                        kv_out[i]     -= k_move;
+                        kv_out[i + 1] += k_move;
+                        adj_n = 1;
+                        ++moves;
+                    }
+                    if (det_lo && det2_hi) {
+                        if ((int64_t)part_n - bm < min_blk) break;  // "continue" of line 23
+                        lpart[i]    = part_i + bm;
+                        part_o      = part_n - bm;
+                        lpos[i + 1] += bm;
+                        kv_out[i]     += k_move;
+                        kv_out[i + 1] -= k_move;
+                        adj_n = 2;
+                        ++moves;
+                    }
+                } while (false);
+                lpart[i + 1] = part_o;
+                part_i = part_o;
+                f_i    = f_n;
+                adj    = adj_n;
             }
         }
         st->moves = moves;
@@ -387,7 +441,7 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     if (tid < P) {
         A.nxt_part[tid] = lpart[tid];
         A.nxt_pos[tid]  = lpos[tid];
-        A.kvec[tid]     = kv[tid];
+        A.kvec[tid]     = kv_out[tid];
     }
 }
 
@@ -409,17 +463,36 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_b, uint32_t block
     const uint32_t j0   = (blockIdx.x - 1u) * (kFinishWG / 64);
     const uint32_t j    = j0 + wave;
 
-    uint32_t s = 0;
+    // this block's first mask words are requested up front, with the counter loads
+    const uint64_t first = (uint64_t)j * block_size;
+    uint32_t len = 0;
+    if (j < n_b) len = (uint64_t)n_g - first < block_size ? (uint32_t)(n_g - first) : block_size;
+    const uint32_t words = (((len + 31u) >> 5) + 3u) & ~3u;
+    const uint4   *m4    = reinterpret_cast<const uint4 *>(A.mask + (size_t)j * (block_size >> 5));
+    uint4 m_first = make_uint4(0, 0, 0, 0);
+    if (lane * 4u < words) m_first = m4[lane];
+    const uint32_t cnt_j = j < n_b ? A.blk_cnt[j] : 0u;
+
+    uint32_t s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+    uint32_t lo = 0;
     if (A.use_sup) {
         const uint32_t sb = j0 >> kSupShift;
-        for (uint32_t i = tid; i < sb; i += kFinishWG) s += A.sup_cnt[i];
-        for (uint32_t i = (sb << kSupShift) + tid; i < j0; i += kFinishWG) s += A.blk_cnt[i];
-    } else {
-        for (uint32_t i = tid; i < j0; i += kFinishWG) s += A.blk_cnt[i];
+        for (uint32_t i = tid; i < sb; i += kFinishWG) s0 += A.sup_cnt[i];
+        lo = sb << kSupShift;
     }
+    {
+        uint32_t i = lo + tid;
+        for (; i + 3u * kFinishWG < j0; i += 4u * kFinishWG) {
+            s0 += A.blk_cnt[i];
+            s1 += A.blk_cnt[i + kFinishWG];
+            s2 += A.blk_cnt[i + 2u * kFinishWG];
+            s3 += A.blk_cnt[i + 3u * kFinishWG];
+        }
+        for (; i < j0; i += kFinishWG) s0 += A.blk_cnt[i];
+    }
+    uint32_t s = (s0 + s1) + (s2 + s3);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
-    const uint32_t cnt_j = j < n_b ? A.blk_cnt[j] : 0u;
     if (lane == 0) {
         red[wave]  = s;
         wcnt[wave] = cnt_j;
@@ -435,17 +508,16 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_b, uint32_t block
     if (!NORM && base >= cap) return;  // nothing of this block fits: it all stays in the residual
 
     float *__restrict__ e = A.e;
-    const uint64_t first = (uint64_t)j * block_size;
-    const uint32_t len   = (uint64_t)n_g - first < block_size ? (uint32_t)(n_g - first) : block_size;
-    const uint32_t words = (((len + 31u) >> 5) + 3u) & ~3u;
-    const uint4   *m4    = reinterpret_cast<const uint4 *>(A.mask + (size_t)j * (block_size >> 5));
     uint64_t running = base;
     float    spill   = 0.f;
 
     for (uint32_t w0 = 0; w0 < words; w0 += 256u) {
         const uint32_t wq = w0 + lane * 4u;
-        uint4 m = make_uint4(0, 0, 0, 0);
-        if (wq < words) m = m4[wq >> 2];
+        uint4 m = m_first;
+        if (w0 != 0) {
+            m = make_uint4(0, 0, 0, 0);
+            if (wq < words) m = m4[wq >> 2];
+        }
         const uint32_t c    = __popc(m.x) + __popc(m.y) + __popc(m.z) + __popc(m.w);
         const uint32_t incl = wave_incl_scan(c, lane);
         const uint32_t tot  = __shfl(incl, 63, 64);
@@ -785,6 +857,7 @@ int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
     A.sup_cnt = at<uint32_t>(c, c->lay.sup_cnt);
     A.blk_cnt_next = blk_cnt_of(c, t + 1);
     A.use_sup = c->n_b > kSupThreshold ? 1u : 0u;
+    A.t_next = t + 1;
     if (A.use_sup) {
         const uint32_t n_sup = (uint32_t)c->lay.n_sup;
         hipLaunchKernelGGL(k_sup, dim3((n_sup + kFinishWG / 64 - 1) / (kFinishWG / 64)),
