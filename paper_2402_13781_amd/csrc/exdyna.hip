@@ -82,7 +82,7 @@ struct CtrlParams {
 };
 
 struct Layout {
-    size_t state, kvec, parts, part_cnt, part_off, blk_cnt, sup_cnt, err_slots, mask, out_idx,
+    size_t state, parts, part_cnt, part_off, blk_cnt, sup_cnt, err_slots, mask, out_idx,
         out_val, total;
     size_t mask_words, n_sup;
 };
@@ -230,7 +230,6 @@ struct FinishArgs {
     const int32_t  *cur_pos;
     int32_t        *nxt_part;      // receives Alg. 3's adjusted topology
     int32_t        *nxt_pos;
-    double         *kvec;
     uint64_t       *part_cnt;
     uint64_t       *part_off;
     uint32_t       *out_idx;
@@ -257,18 +256,36 @@ k_sup(const uint32_t *__restrict__ blk_cnt, uint32_t *__restrict__ sup_cnt, uint
 }
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
-// Everything that can be done side by side is (counts, scan, the fp64
-// quotients of Alg. 3); only the decision chain of the sweep runs on one lane.
+//
+// Alg. 3's sweep looks sequential (pair i sees what pair i-1 did), but pair
+// i-1 can leave pair i in only three states: untouched, or k[i] and
+// blk_part[i] raised, or lowered, by one move.  So every pair's decision is
+// tabulated for the three states side by side, and the chain of tables is
+// resolved with a prefix scan of table compositions.  A table is three 2-bit
+// actions (0 none, 1 blocks go right: lines 16-20, 2 blocks go left: lines
+// 24-28), and the action a pair takes is the state it hands to the next pair.
+__device__ __forceinline__ uint32_t compose(uint32_t later, uint32_t earlier)
+{
+    // (later o earlier)[s] = later[earlier[s]]
+    return ((later >> (2u * (earlier & 3u))) & 3u) |
+           (((later >> (2u * ((earlier >> 2) & 3u))) & 3u) << 2) |
+           (((later >> (2u * ((earlier >> 4) & 3u))) & 3u) << 4);
+}
+
 __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 {
+    constexpr uint32_t kWaves = kFinishWG / 64;
+    constexpr uint32_t kIdent = 0u | (1u << 2) | (2u << 4);  // s -> s
     __shared__ uint32_t cnt_s[kMaxParts];
-    __shared__ uint32_t wsum[kFinishWG / 64];
-    __shared__ uint32_t wmax[kFinishWG / 64];
-    __shared__ uint64_t k_total;
-    __shared__ int32_t  lpart[kMaxParts];
     __shared__ int32_t  lpos[kMaxParts];
+    __shared__ int32_t  lpart[kMaxParts];
     __shared__ uint8_t  flags[kMaxParts];
-    __shared__ double   kv_out[kMaxParts];
+    __shared__ uint32_t wsum[kWaves];
+    __shared__ uint32_t wmax[kWaves];
+    __shared__ uint32_t wfun[kWaves];
+    __shared__ uint32_t wcarry[kWaves];
+    __shared__ uint32_t n_moves;
+    __shared__ uint64_t k_total;
 
     const uint32_t tid  = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -276,36 +293,58 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     const uint32_t P    = prm.n_parts;
     const uint32_t n_b  = prm.n_b;
 
+    // all first loads are requested before anything waits on them
+    uint32_t c4[4];
+#pragma unroll
+    for (uint32_t q = 0; q < 4; ++q) {
+        const uint32_t i = tid + q * kFinishWG;
+        c4[q] = i < n_b ? A.blk_cnt[i] : 0u;
+    }
     float delta = 0.f;
-    if (tid == 0) delta = A.st->delta;  // in flight while the counts are gathered
+    if (tid == 0) delta = A.st->delta;
+    const int32_t part = tid < P ? A.cur_part[tid] : 0;
+    const int32_t pos  = tid < P ? A.cur_pos[tid] : 0;
     if (tid < P) {
         cnt_s[tid] = 0u;
-        lpart[tid] = A.cur_part[tid];
-        lpos[tid]  = A.cur_pos[tid];
+        lpos[tid]  = pos;
+        lpart[tid] = part;
     }
+    if (tid == 0) n_moves = 0u;
     if (tid < kErrSlots) A.err_slots_next[tid] = 0.0;
     __syncthreads();
 
     // k_{p,t} (Sec. 4.2: the workload of a partition): every thread walks a
     // strided share of the block counters and adds each non-zero one to the
     // partition that holds the block (largest p with blk_pos[p] <= block).
-    for (uint32_t i0 = tid; i0 < n_b; i0 += 4u * kFinishWG) {
-        uint32_t c[4];
+    // the loop condition is the same for all lanes of a wave (it tests the
+    // wave's first block), so the cross-lane steps below see every lane
+    for (uint32_t i0 = tid; i0 - lane < n_b; i0 += 4u * kFinishWG) {
+        if (i0 != tid) {
 #pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            const uint32_t i = i0 + q * kFinishWG;
-            c[q] = i < n_b ? A.blk_cnt[i] : 0u;
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint32_t i = i0 + q * kFinishWG;
+                c4[q] = i < n_b ? A.blk_cnt[i] : 0u;
+            }
         }
 #pragma unroll
         for (uint32_t q = 0; q < 4; ++q) {
-            if (c[q]) {
-                const uint32_t i = i0 + q * kFinishWG;
-                uint32_t lo = 0, hi = P - 1;
-                while (lo < hi) {
-                    const uint32_t mid = (lo + hi + 1) >> 1;
-                    if ((uint32_t)lpos[mid] <= i) lo = mid; else hi = mid - 1;
-                }
-                atomicAdd(&cnt_s[lo], c[q]);
+            // a wave's 64 blocks are consecutive, so they usually share a partition:
+            // then one lane adds the wave's sum instead of 64 lanes colliding
+            const uint32_t i  = i0 + q * kFinishWG;
+            const uint32_t ib = i < n_b ? i : n_b - 1;
+            uint32_t lo = 0, hi = P - 1;
+            while (lo < hi) {
+                const uint32_t mid = (lo + hi + 1) >> 1;
+                if ((uint32_t)lpos[mid] <= ib) lo = mid; else hi = mid - 1;
+            }
+            const uint32_t p0 = __shfl(lo, 0, 64);
+            if (__ballot(lo != p0) == 0) {
+                uint32_t v = c4[q];
+#pragma unroll
+                for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
+                if (lane == 0 && v) atomicAdd(&cnt_s[p0], v);
+            } else if (c4[q]) {
+                atomicAdd(&cnt_s[lo], c4[q]);
             }
         }
     }
@@ -324,10 +363,10 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     if (lane == 0) wmax[wave] = mx;
     __syncthreads();
     if (wave == 0) {
-        const uint32_t v  = lane < kFinishWG / 64 ? wsum[lane] : 0u;
+        const uint32_t v  = lane < kWaves ? wsum[lane] : 0u;
         const uint32_t vi = wave_incl_scan(v, lane);
-        if (lane < kFinishWG / 64) wsum[lane] = vi - v;
-        if (lane == kFinishWG / 64 - 1) k_total = vi;  // k' (Alg. 1 line 13)
+        if (lane < kWaves) wsum[lane] = vi - v;
+        if (lane == kWaves - 1) k_total = vi;  // k' (Alg. 1 line 13)
     }
     __syncthreads();
     const uint64_t excl     = (uint64_t)wsum[wave] + (incl - c);
@@ -337,19 +376,19 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
         A.part_off[tid] = excl < prm.cap ? excl : prm.cap;
     }
 
-    // Alg. 3 lines 8-10 and the comparisons of lines 13 / 21, for every pair at
-    // once.  This iteration's counts are the next Allocate's partial-k vector
-    // (Alg. 1 line 15); they are integers, so their fp64 sum is k' exactly.
-    // When pair i is inspected, k[i] is its count c, or c +/- k_move if pair
-    // i-1 moved blocks, and k[i+1] is still its count: quotients for the three
-    // cases, compared against alpha and 1/alpha, go into six flag bits.
+    // Alg. 3 lines 8-10 and the comparisons of lines 13 / 21.  This iteration's
+    // counts are the next Allocate's partial-k vector (Alg. 1 line 15); they
+    // are integers, so their fp64 sum is k' exactly.  When pair i is inspected,
+    // k[i] is its count, or its count +/- k_move if pair i-1 moved blocks, and
+    // k[i+1] is still its count: quotients for the three cases, compared
+    // against alpha and 1/alpha, go into six flag bits.
     const double sum      = (double)k_actual;
     const double pk_prev  = sum / (double)P;
     const double den_prev = sum / (double)prm.n_g;
     const double k_move   = (double)prm.blk_move * (double)prm.block_size * den_prev;
     if (tid < P) {
         uint32_t f = 0;
-        if (k_actual) {
+        if (k_actual) {  // nothing selected: det is 0/0 and no pair moves
             const double kc = (double)c;
             const double d0 = kc / pk_prev;
             const double dp = (kc + k_move) / pk_prev;
@@ -358,8 +397,65 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
                 (dp > prm.alpha ? 4u : 0u) | (dp < prm.inv_alpha ? 8u : 0u) |
                 (dm > prm.alpha ? 16u : 0u) | (dm < prm.inv_alpha ? 32u : 0u);
         }
-        flags[tid]  = (uint8_t)f;
-        kv_out[tid] = (double)c;
+        flags[tid] = (uint8_t)f;
+    }
+    __syncthreads();
+
+    // decision table of pair (tid, tid+1) for the three incoming states
+    const int64_t bm      = (int64_t)prm.blk_move;
+    const int64_t min_blk = (int64_t)prm.min_blk;
+    uint32_t table = 0;  // beyond the last pair: every state maps to "none"
+    if (tid + 1 < P) {
+        const uint32_t f_i     = flags[tid];
+        const uint32_t f_n     = flags[tid + 1];
+        const bool     det2_hi = f_n & 1u, det2_lo = f_n & 2u;
+        const int64_t  part_n  = lpart[tid + 1];
+#pragma unroll
+        for (uint32_t st = 0; st < 3; ++st) {
+            const uint32_t fi     = f_i >> (2u * st);
+            const bool     det_hi = fi & 1u, det_lo = fi & 2u;
+            const int64_t  part_i = (int64_t)part + (st == 1 ? bm : st == 2 ? -bm : 0);
+            uint32_t act = 0;
+            if (det_hi && det2_lo) {
+                if (!(part_i - bm < min_blk)) act = 1;   // else "continue" (line 15)
+            } else if (det_lo && det2_hi) {
+                if (!(part_n - bm < min_blk)) act = 2;   // else "continue" (line 23)
+            }
+            table |= act << (2u * st);
+        }
+    }
+    // inclusive scan of compositions: after it, `fun` maps the state entering
+    // this wave's first pair to the state leaving pair tid
+    uint32_t fun = table;
+#pragma unroll
+    for (uint32_t d = 1; d < 64; d <<= 1) {
+        const uint32_t prev = __shfl_up(fun, d, 64);
+        if (lane >= d) fun = compose(fun, prev);
+    }
+    if (lane == 63) wfun[wave] = fun;
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t stt = 0;  // pair 0 starts untouched
+        for (uint32_t w = 0; w < kWaves; ++w) {
+            wcarry[w] = stt;
+            stt = (wfun[w] >> (2u * stt)) & 3u;
+        }
+    }
+    __syncthreads();
+    uint32_t before = __shfl_up(fun, 1, 64);
+    if (lane == 0) before = kIdent;
+    const uint32_t st_in = (before >> (2u * wcarry[wave])) & 3u;  // what pair tid-1 did
+    const uint32_t act   = (table >> (2u * st_in)) & 3u;          // what pair tid does
+    const uint64_t moved = __ballot(act != 0);
+    if (lane == 0 && moved) atomicAdd(&n_moves, (uint32_t)__popcll(moved));
+    if (tid < P) {
+        const int32_t bmi = (int32_t)prm.blk_move;
+        // lines 16-18 / 24-26 as seen from partition tid: it is the right side
+        // of pair tid-1 and the left side of pair tid
+        const int32_t d_in  = st_in == 1 ? bmi : st_in == 2 ? -bmi : 0;
+        const int32_t d_out = act == 1 ? -bmi : act == 2 ? bmi : 0;
+        A.nxt_part[tid] = part + d_in + d_out;
+        A.nxt_pos[tid]  = pos - d_in;
     }
     __syncthreads();
 
@@ -381,76 +477,29 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 
         // ---- Eq. 2 / 5 / 6 ----
         uint64_t m_t = 0;
-        for (uint32_t w = 0; w < kFinishWG / 64; ++w) m_t = wmax[w] > m_t ? wmax[w] : m_t;
+        for (uint32_t w = 0; w < kWaves; ++w) m_t = wmax[w] > m_t ? wmax[w] : m_t;
         st->k_actual      = k_actual;
         st->k_emitted     = k_actual < prm.cap ? k_actual : prm.cap;
         st->overflow      = k_actual > prm.cap ? 1u : 0u;
         st->k_max_part    = m_t;
         st->density_error = fabs(prm.k - (double)k_actual) / (double)prm.n_g;
         st->traffic_ratio = k_actual ? (double)P * (double)m_t / (double)k_actual : 0.0;
-        st->t = A.t_next;
-
-        // ---- Alg. 3 lines 11-28: the decision chain, pair by pair.  `adj` says
-        // what pair i-1 did to k[i]: 0 nothing, 1 added k_move, 2 subtracted it.
-        uint32_t moves = 0;
-        if (k_actual) {
-            const int32_t bm      = (int32_t)prm.blk_move;
-            const int64_t min_blk = (int64_t)prm.min_blk;
-            uint32_t adj = 0;
-            int32_t  part_i = lpart[0];
-            uint32_t f_i = flags[0];
-            for (uint32_t i = 0; i + 1 < P; ++i) {
-                const uint32_t f_n    = flags[i + 1];
-                const int32_t  part_n = lpart[i + 1];
-                const uint32_t fi     = f_i >> (2u * adj);
-                const bool det_hi = fi & 1u, det_lo = fi & 2u;      // det > alpha, det < 1/alpha
-                const bool det2_hi = f_n & 1u, det2_lo = f_n & 2u;  // same for det2
-                uint32_t adj_n  = 0;
-                int32_t  part_o = part_n;  // blk_part[i+1] after this pair
-                do {
-                    if (det_hi && det2_lo) {
-                        if ((int64_t)part_i - bm < min_blk) break;  // "continue" of line 15
-                        lpart[i]    = part_i - bm;
-                        part_o      = part_n + bm;
-                        lpos[i + 1] -= bm;
-                        kv_out[i]     -= k_move;
-                        kv_out[i + 1] += k_move;
-                        adj_n = 1;
-                        ++moves;
-                    }
-                    if (det_lo && det2_hi) {
-                        if ((int64_t)part_n - bm < min_blk) break;  // "continue" of line 23
-                        lpart[i]    = part_i + bm;
-                        part_o      = part_n - bm;
-                        lpos[i + 1] += bm;
-                        kv_out[i]     += k_move;
-                        kv_out[i + 1] -= k_move;
-                        adj_n = 2;
-                        ++moves;
-                    }
-                } while (false);
-                lpart[i + 1] = part_o;
-                part_i = part_o;
-                f_i    = f_n;
-                adj    = adj_n;
-            }
-        }
-        st->moves = moves;
-    }
-    __syncthreads();
-    if (tid < P) {
-        A.nxt_part[tid] = lpart[tid];
-        A.nxt_pos[tid]  = lpos[tid];
-        A.kvec[tid]     = kv_out[tid];
+        st->t     = A.t_next;
+        st->moves = n_moves;
     }
 }
 
 // ---- compaction: a workgroup takes 16 consecutive blocks, one wavefront per
 // block.  The workgroup first sums the counters in front of its first block
 // (all 1024 threads, counters sit in L2), which is the output position of its
-// first pair.  Then each lane takes four consecutive mask words (128
-// gradients); a wave scan of the popcounts gives every lane the rank of its
-// first set bit, so pairs come out in ascending index order. ----
+// first pair.  The block's mask is read 256 words (8192 gradients) per load
+// instruction, lane l taking words 4l..4l+3 of each such slice, and up to four
+// slices are requested before anything waits on memory; a wave scan of the
+// popcounts per slice gives every lane the rank of its first set bit, so pairs
+// come out in ascending index order. ----
+constexpr uint32_t kLaneVec   = 4;                    // uint4 loads per lane and pass
+constexpr uint32_t kPassWords = 64 * kLaneVec * 4;    // 1024 words = 32768 gradients per pass
+
 template <bool NORM>
 __device__ void finish_compact(const FinishArgs &A, uint32_t n_b, uint32_t block_size, uint32_t n_g,
                                uint64_t cap)
@@ -463,14 +512,19 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_b, uint32_t block
     const uint32_t j0   = (blockIdx.x - 1u) * (kFinishWG / 64);
     const uint32_t j    = j0 + wave;
 
-    // this block's first mask words are requested up front, with the counter loads
+    // this block's mask words (first pass) are requested up front, with the counter loads
     const uint64_t first = (uint64_t)j * block_size;
     uint32_t len = 0;
     if (j < n_b) len = (uint64_t)n_g - first < block_size ? (uint32_t)(n_g - first) : block_size;
     const uint32_t words = (((len + 31u) >> 5) + 3u) & ~3u;
-    const uint4   *m4    = reinterpret_cast<const uint4 *>(A.mask + (size_t)j * (block_size >> 5));
-    uint4 m_first = make_uint4(0, 0, 0, 0);
-    if (lane * 4u < words) m_first = m4[lane];
+    const uint32_t *mw   = A.mask + (size_t)j * (block_size >> 5);
+    uint4 mv[kLaneVec];
+#pragma unroll
+    for (uint32_t q = 0; q < kLaneVec; ++q) {
+        const uint32_t w = q * 256u + lane * 4u;
+        mv[q] = make_uint4(0, 0, 0, 0);
+        if (w < words) mv[q] = *reinterpret_cast<const uint4 *>(mw + w);
+    }
     const uint32_t cnt_j = j < n_b ? A.blk_cnt[j] : 0u;
 
     uint32_t s0 = 0, s1 = 0, s2 = 0, s3 = 0;
@@ -511,38 +565,46 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_b, uint32_t block
     uint64_t running = base;
     float    spill   = 0.f;
 
-    for (uint32_t w0 = 0; w0 < words; w0 += 256u) {
-        const uint32_t wq = w0 + lane * 4u;
-        uint4 m = m_first;
-        if (w0 != 0) {
-            m = make_uint4(0, 0, 0, 0);
-            if (wq < words) m = m4[wq >> 2];
-        }
-        const uint32_t c    = __popc(m.x) + __popc(m.y) + __popc(m.z) + __popc(m.w);
-        const uint32_t incl = wave_incl_scan(c, lane);
-        const uint32_t tot  = __shfl(incl, 63, 64);
-        uint64_t r = running + (incl - c);
-        uint32_t wv[4] = {m.x, m.y, m.z, m.w};
+    for (uint32_t w0 = 0; w0 < words; w0 += kPassWords) {
+        if (w0 != 0) {  // blocks above 32768 gradients take further passes
 #pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            uint32_t       bits  = wv[q];
-            const uint32_t ebase = (uint32_t)first + (wq + q) * 32u;
-            while (bits) {
-                const uint32_t i = ebase + (uint32_t)(__ffs(bits) - 1);
-                bits &= bits - 1u;
-                if (r < cap) {
-                    const float v = e[i];
-                    A.out_idx[r] = i;
-                    A.out_val[r] = v;
-                    e[i]         = 0.0f;  // +0 where sent (Alg. 1 line 17)
-                } else if (NORM) {
-                    const float v = e[i];  // selected but not emitted: stays in the residual
-                    spill += v * v;
-                }
-                ++r;
+            for (uint32_t q = 0; q < kLaneVec; ++q) {
+                const uint32_t w = w0 + q * 256u + lane * 4u;
+                mv[q] = make_uint4(0, 0, 0, 0);
+                if (w < words) mv[q] = *reinterpret_cast<const uint4 *>(mw + w);
             }
         }
-        running += tot;
+#pragma unroll
+        for (uint32_t q = 0; q < kLaneVec; ++q) {
+            if (w0 + q * 256u >= words) break;  // uniform
+            const uint32_t c =
+                __popc(mv[q].x) + __popc(mv[q].y) + __popc(mv[q].z) + __popc(mv[q].w);
+            if (__ballot(c != 0) == 0) continue;  // uniform: nothing selected in this slice
+            const uint32_t incl = wave_incl_scan(c, lane);
+            const uint32_t tot  = __shfl(incl, 63, 64);
+            uint64_t r = running + (incl - c);
+            const uint32_t wv[4] = {mv[q].x, mv[q].y, mv[q].z, mv[q].w};
+#pragma unroll
+            for (uint32_t h = 0; h < 4; ++h) {
+                uint32_t       bits  = wv[h];
+                const uint32_t ebase = (uint32_t)first + (w0 + q * 256u + lane * 4u + h) * 32u;
+                while (bits) {
+                    const uint32_t i = ebase + (uint32_t)(__ffs(bits) - 1);
+                    bits &= bits - 1u;
+                    if (r < cap) {
+                        const float v = e[i];
+                        A.out_idx[r] = i;
+                        A.out_val[r] = v;
+                        e[i]         = 0.0f;  // +0 where sent (Alg. 1 line 17)
+                    } else if (NORM) {
+                        const float v = e[i];  // selected but not emitted: stays in the residual
+                        spill += v * v;
+                    }
+                    ++r;
+                }
+            }
+            running += tot;
+        }
     }
     if (NORM) {
         double sq = (double)spill;
@@ -552,8 +614,9 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_b, uint32_t block
     }
 }
 
+// 8 waves per SIMD (64 VGPRs) so that two of these 16-wave workgroups fit a CU
 template <bool NORM>
-__global__ void __launch_bounds__(kFinishWG)
+__global__ void __launch_bounds__(kFinishWG, 8)
 k_finish(FinishArgs A, CtrlParams prm)
 {
     if (blockIdx.x == 0)
@@ -572,12 +635,14 @@ __global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n)
         p[i] = v;
 }
 
-// Alg. 1 lines 4-6: partial-k vector k/P, delta_0, Alg. 2 topology in closed
-// form (the first `remainder` partitions hold quotient+1 blocks; positions are
-// the exclusive prefix sum).
+// Alg. 1 lines 5-6: delta_0 and Alg. 2's topology in closed form (the first
+// `remainder` partitions hold quotient+1 blocks; positions are the exclusive
+// prefix sum).  The uniform initial partial-k vector of line 4 is not stored:
+// with equal entries det = det2 for every pair, so the first Allocate moves
+// nothing, and every later Allocate uses the counts of the step before it.
 __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_t *part1,
-                             int32_t *pos1, double *kvec, uint64_t *part_cnt, uint64_t *part_off,
-                             double *err_slots, float delta0, double k, uint32_t n_b, uint32_t P)
+                             int32_t *pos1, uint64_t *part_cnt, uint64_t *part_off,
+                             double *err_slots, float delta0, uint32_t n_b, uint32_t P)
 {
     const uint32_t tid = blockIdx.x * blockDim.x + threadIdx.x;
     const uint32_t q = n_b / P, r = n_b % P;
@@ -586,7 +651,6 @@ __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_
         const int32_t pos  = (int32_t)(tid * q + (tid < r ? tid : r));
         part0[tid] = part; pos0[tid] = pos;
         part1[tid] = part; pos1[tid] = pos;
-        kvec[tid]     = k / (double)P;
         part_cnt[tid] = 0;
         part_off[tid] = 0;
     }
@@ -671,7 +735,6 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L.state     = take(sizeof(DevState));
-    L.kvec      = take(P * sizeof(double));
     L.parts     = take(4 * P * sizeof(int32_t));        // slot0 part,pos ; slot1 part,pos
     L.part_cnt  = take(P * sizeof(uint64_t));
     L.part_off  = take((P + 1) * sizeof(uint64_t));
@@ -816,9 +879,8 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
     const uint32_t init_threads = (P + 1 > 2 * kErrSlots ? P + 1 : 2 * kErrSlots);
     hipLaunchKernelGGL(k_init_state, dim3((init_threads + 255) / 256), dim3(256), 0, s,
                        at<DevState>(c, L.state), slot_part(c, 0), slot_pos(c, 0), slot_part(c, 1),
-                       slot_pos(c, 1), at<double>(c, L.kvec), at<uint64_t>(c, L.part_cnt),
-                       at<uint64_t>(c, L.part_off), at<double>(c, L.err_slots), cfg->threshold0, p.k,
-                       (uint32_t)n_b, P);
+                       slot_pos(c, 1), at<uint64_t>(c, L.part_cnt), at<uint64_t>(c, L.part_off),
+                       at<double>(c, L.err_slots), cfg->threshold0, (uint32_t)n_b, P);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) {
         delete c;
@@ -868,7 +930,6 @@ int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
     A.cur_pos = slot_pos(c, t);
     A.nxt_part = slot_part(c, t + 1);
     A.nxt_pos = slot_pos(c, t + 1);
-    A.kvec = at<double>(c, c->lay.kvec);
     A.part_cnt = at<uint64_t>(c, c->lay.part_cnt);
     A.part_off = at<uint64_t>(c, c->lay.part_off);
     A.out_idx = at<uint32_t>(c, c->lay.out_idx);

@@ -30,6 +30,8 @@ def _thr(w):
     (100_003, 768, 7, 0.005),
     (65_536 * 3 + 1, 65_536, 2, 0.001),
     (1_000_001, 4096, 16, 0.01),
+    (196_608 * 3 + 5, 196_608, 2, 0.002),      # blocks above 65536 gradients: several mask passes
+    (300_000, 512, 40, 0.01),
 ])
 def test_small_trajectories_bit_exact(n_g, b, P, d):
     w = synthetic.WORKLOADS[1].scaled(n_g, b, P)
