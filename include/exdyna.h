@@ -53,8 +53,7 @@ typedef struct exdyna_ctx exdyna_ctx; /* opaque, host memory, library-owned */
 typedef struct {
     uint64_t n_g;          /* number of gradients, 1 <= n_g < 2^32 (indices are u32)        */
     uint32_t block_size;   /* b: gradients per block, > 0 and a multiple of 256 (Sec. 4.1;
-                              the paper's granularity is 32, one wavefront x float4 is 256);
-                              n_b = ceil(n_g / b) must not exceed 2^20                       */
+                              the paper's granularity is 32, one wavefront x float4 is 256)  */
     uint32_t n_parts;      /* P = number of workers n, 1 <= P <= min(n_b, 1024)             */
     double   density;      /* d in (0, 1]; k = d * n_g is kept in fp64 (Sec. 1)             */
     float    threshold0;   /* delta_0 > 0, finite (Alg. 1 line 5)                           */
@@ -96,8 +95,8 @@ int exdyna_default_config(exdyna_config *cfg);
 int exdyna_block_size_from_nb(uint64_t n_g, uint64_t n_b, uint32_t multiple, uint32_t *h_block_size);
 
 /* Bytes of device workspace exdyna_init needs for this configuration
- * (state, per-block counters, the 1-bit-per-gradient selection mask, and the
- * output pairs).  Host only, launches nothing. */
+ * (state, per-block / per-chunk / per-tile counters, the staging slots the
+ * streaming pass writes selected pairs into, and the output pairs).  Host only, launches nothing. */
 int exdyna_workspace_bytes(const exdyna_config *cfg, size_t *h_bytes);
 
 /* Alg. 1 lines 3-6: residual <- 0, partial-k vector <- k/P, delta <- delta_0,

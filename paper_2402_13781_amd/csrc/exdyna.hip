@@ -3,20 +3,28 @@
 // Two kernels per iteration, both enqueued by exdyna_step with no host round
 // trip (threshold, topology and counters live in device memory):
 //
-//   k_stream   acc = e + g (Alg. 1 line 7), |acc| cmp delta (Alg. 4 line 2),
-//              1 bit per gradient into a selection mask, popcounts added to a
-//              per-block counter and to a counter per 64 blocks.
-//              Pure streaming: 8 B read + 4 B written per gradient.
+//   k_stream   acc = e + g (Alg. 1 line 7), |acc| cmp delta (Alg. 4 line 2).
+//              Each wavefront owns 1024 contiguous gradients (a "wave tile").
+//              It ranks its selected gradients with ballots, writes their
+//              (index, value) pairs in index order into the tile's slots of a
+//              staging buffer, writes the residual with those entries already
+//              zeroed (Alg. 1 lines 17-18), stores the tile's count, and adds
+//              the count to a per-block and a per-segment counter.  A tile with
+//              more selected gradients than slots is only counted and flagged;
+//              its residual is written unzeroed.
+//              Pure streaming: 8 B read + 4 B written per gradient, no
+//              workgroup barrier, no fence.
 //   k_finish   workgroup 0 = control: per-partition counts k_{p,t} and k'
 //              (Alg. 1 lines 10, 13), output segment offsets, threshold
 //              scaling (Alg. 5), adjacent-partition rebalancing (Alg. 3 lines
 //              8-28), Eq. 2/5/6 statistics.
-//              other workgroups = compaction, one wavefront per block: the
-//              wave sums the counters in front of its block (two levels, at
-//              most a few loads per lane), then a wave scan of mask popcounts
-//              gives stable ascending (index, value) pairs (Alg. 1 lines 9-11)
-//              and the residual is zeroed at emitted entries (Alg. 1 line 17).
-//              Touches only the mask and the selected cache lines.
+//              other workgroups = compaction, one wavefront per chunk of 64
+//              wave tiles: prefix of the segment counters in front (summed by
+//              the whole workgroup), a wave scan of the 64 tile counts, then each
+//              lane copies its tile's staged pairs to their final positions
+//              (Alg. 1 lines 9-11).  Flagged tiles are re-read from the
+//              residual and compacted by the whole wave.  Pairs beyond the
+//              output capacity are put back into the residual.
 //              Control and compaction read the same finished counters and do
 //              not depend on each other, so they overlap inside one launch.
 //
@@ -26,9 +34,12 @@
 // of it, and partition p's segment starts at the sum of the counts of the
 // partitions before it.
 //
-// No device-scope fence or "last workgroup done" ticket is used anywhere: on
-// this multi-die part such a fence per workgroup costs far more than a second
-// launch.
+// What the measurements on this part ruled out: a device-scope fence or a
+// "last workgroup done" ticket per workgroup (about 150 ns each, serialised),
+// hot counters shared by many workgroups (same cost per same-address atomic),
+// a workgroup barrier in the streaming pass (6 % slower), and gathering the
+// selected values from the residual afterwards (random 4-byte reads over
+// gigabytes cost more than the whole compaction does now).
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -41,26 +52,23 @@
 
 namespace {
 
-constexpr uint32_t kGran        = 256;  // gradients per wave-iteration: 64 lanes x float4
-constexpr uint32_t kGranWords   = 8;    // mask words per granule
-constexpr uint32_t kStreamWG    = 256;  // threads per workgroup in k_stream
-constexpr uint32_t kWavesPerWG  = 4;
+constexpr uint32_t kGran        = 256;   // gradients per wave load: 64 lanes x float4
+constexpr uint32_t kTileGran    = 4;     // granules per wave tile
+constexpr uint32_t kTile        = kGran * kTileGran;  // 1024 gradients per wavefront
+constexpr uint32_t kStreamWG    = 256;   // k_stream: 4 wavefronts = 4096 contiguous gradients
+constexpr uint32_t kWavesPerWG  = kStreamWG / 64;
+constexpr uint32_t kChunkShift  = 6;     // 64 wave tiles (65536 gradients) per compaction wavefront
 constexpr uint32_t kMaxParts    = 1024;
-constexpr uint32_t kFinishWG    = 1024; // k_finish: 16 waves = control, or 16 blocks
-constexpr uint32_t kSupShift    = 6;    // one coarse counter per 64 blocks ...
-constexpr uint32_t kSupThreshold = 32768; // ... built only above this many blocks
-constexpr uint64_t kMaxBlocks   = 1u << 20;
+constexpr uint32_t kFinishWG    = 1024;  // k_finish: 16 waves = control, or 16 chunks
 constexpr uint32_t kErrSlots    = 256;
-constexpr uint64_t kMagic       = 0x45784479'6e61'0001ull;
-
-#ifndef EXDYNA_UNROLL
-#define EXDYNA_UNROLL 4
-#endif
+constexpr uint32_t kFlag        = 0x80000000u;  // tile count flag: pairs not staged
+constexpr uint64_t kMagic       = 0x45784479'6e61'0002ull;
 
 // Device-resident scalar state.  One instance at the start of the workspace.
 struct DevState {
-    float    delta;       // threshold the NEXT k_stream compares with
-    float    delta_used;  // threshold the last k_stream compared with
+    float    delta[2];    // delta[t & 1] is what iteration t compares with
+    float    delta_used;  // threshold the last iteration compared with
+    float    delta_next;  // threshold the next iteration will compare with
     uint32_t overflow;
     uint32_t moves;
     uint64_t t;
@@ -82,9 +90,11 @@ struct CtrlParams {
 };
 
 struct Layout {
-    size_t state, parts, part_cnt, part_off, blk_cnt, sup_cnt, err_slots, mask, out_idx,
-        out_val, total;
-    size_t mask_words, n_sup;
+    size_t state, parts, part_cnt, part_off, blk_cnt, seg_cnt, tile_cnt, err_slots, stage,
+        out_idx, out_val, total;
+    size_t n_tiles, n_chunks, n_segs;
+    uint32_t slots;      // staging slots per wave tile
+    uint32_t seg_shift;  // log2(wave tiles per segment counter)
 };
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -111,96 +121,171 @@ __device__ __forceinline__ uint32_t sel(float a, float delta)
     return CMP ? (__builtin_fabsf(a) > delta) : (__builtin_fabsf(a) >= delta);
 }
 
-// Mask words and the block counter for one granule.  nib holds this lane's
-// four flags (bit q <-> gradient 4*lane + q of the granule).
-__device__ __forceinline__ void publish_granule(uint32_t gran, uint32_t nib, uint32_t lane,
-                                                uint32_t *__restrict__ mask,
-                                                uint32_t *__restrict__ blk_cnt,
-                                                uint32_t gran_per_blk)
+// number of set bits of `m` in lanes below this one
+__device__ __forceinline__ uint32_t lanes_below(uint64_t m)
 {
-    const uint64_t any = __ballot(nib != 0);
-    uint32_t *mw = mask + (size_t)gran * kGranWords;
-    if (any == 0) {
-        if (lane < kGranWords) mw[lane] = 0u;
-    } else {
-        // word q of the granule = flags of lanes 8q .. 8q+7, element order
-        uint32_t v = nib << ((lane & 7u) * 4u);
-        v |= __shfl_xor(v, 1, 64);
-        v |= __shfl_xor(v, 2, 64);
-        v |= __shfl_xor(v, 4, 64);
-        if ((lane & 7u) == 0) mw[lane >> 3] = v;
-        const uint32_t cnt = __popcll(__ballot(nib & 1u)) + __popcll(__ballot(nib & 2u)) +
-                             __popcll(__ballot(nib & 4u)) + __popcll(__ballot(nib & 8u));
-        // one counter per block keeps same-address atomics rare (they serialise
-        // at roughly 150 ns each across the dies)
-        if (lane == 0) atomicAdd(&blk_cnt[gran / gran_per_blk], cnt);
-    }
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+}
+
+// Flags of one granule (nib: bit q <-> gradient 4*lane + q) -> how many are
+// set in the whole granule, and how many precede this lane's, in index order.
+__device__ __forceinline__ void granule_ranks(uint32_t nib, uint32_t &count, uint32_t &below)
+{
+    const uint64_t b0 = __ballot(nib & 1u), b1 = __ballot(nib & 2u), b2 = __ballot(nib & 4u),
+                   b3 = __ballot(nib & 8u);
+    count = (uint32_t)(__popcll(b0) + __popcll(b1) + __popcll(b2) + __popcll(b3));
+    below = lanes_below(b0) + lanes_below(b1) + lanes_below(b2) + lanes_below(b3);
 }
 
 // ---------------------------------------------------------------------------
-// k_stream: error-feedback accumulate + compare + mask + per-block popcount.
-// Workgroup w handles granules [w*4U, (w+1)*4U); at unroll step u wave v takes
-// granule w*4U + 4u + v, so the four waves read 4 KiB contiguous per step.
-template <int CMP, bool NORM, int U>
+// k_stream: error-feedback accumulate + compare + rank + stage + zeroed
+// write-back.  Workgroup w streams gradients [4096 w, 4096 (w+1)); its wave v
+// owns wave tile 4w + v = four consecutive granules.
+struct StreamArgs {
+    const float    *g;
+    float          *e;
+    const DevState *st;
+    uint2          *stage;      // n_tiles x slots pairs (index, value bits)
+    uint32_t       *tile_cnt;   // n_tiles: selected in the tile, kFlag if not staged
+    uint32_t       *blk_cnt;    // this iteration's per-block counters (zero on entry)
+    uint32_t       *seg_cnt;    // this iteration's per-segment counters (zero on entry)
+    double         *err_slots;
+    uint32_t        n_g, n_tiles, gran_per_blk, slots, parity;
+    uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
+    uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
+};
+
+template <int CMP, bool NORM>
 __global__ void __launch_bounds__(kStreamWG)
-k_stream(const float *__restrict__ g, float *__restrict__ e, const DevState *__restrict__ st,
-         uint32_t *__restrict__ mask, uint32_t *__restrict__ blk_cnt,
-         double *__restrict__ err_slots, uint32_t n_g, uint32_t n_gran, uint32_t gran_per_blk)
+k_stream(StreamArgs A)
 {
-    const float    delta  = st->delta;
+    const float    delta  = A.st->delta[A.parity];
     const uint32_t lane   = threadIdx.x & 63u;
     const uint32_t wave   = threadIdx.x >> 6;
-    const uint32_t gran0  = blockIdx.x * (kWavesPerWG * U);
-    const uint32_t n_full = n_g >> 8;  // complete granules
+    const uint32_t tile   = blockIdx.x * kWavesPerWG + wave;
+    const uint32_t gran0  = tile * kTileGran;
+    const uint32_t n_full = A.n_g >> 8;  // complete granules
+    const bool     live   = tile < A.n_tiles;            // wave-uniform
+    const bool     fast   = gran0 + kTileGran <= n_full;  // wave-uniform: no ragged end inside
     float nrm = 0.f;
 
-    if (gran0 + kWavesPerWG * U <= n_full) {
-        f32x4 gv[U], ev[U];
+    if (live && fast) {
+        f32x4    a[kTileGran];
+        uint32_t nib[kTileGran];
+        {
+            f32x4 gv[kTileGran], ev[kTileGran];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const size_t off = ((size_t)(gran0 + u * kWavesPerWG + wave) << 8) + lane * 4u;
-            gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(g + off));
-            ev[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(e + off));
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t gran = gran0 + u * kWavesPerWG + wave;
-            const size_t   off  = ((size_t)gran << 8) + lane * 4u;
-            f32x4 a;
-            a.x = ev[u].x + gv[u].x;
-            a.y = ev[u].y + gv[u].y;
-            a.z = ev[u].z + gv[u].z;
-            a.w = ev[u].w + gv[u].w;
-            __builtin_nontemporal_store(a, reinterpret_cast<f32x4 *>(e + off));
-            const uint32_t nib = sel<CMP>(a.x, delta) | (sel<CMP>(a.y, delta) << 1) |
-                                 (sel<CMP>(a.z, delta) << 2) | (sel<CMP>(a.w, delta) << 3);
-            if (NORM) {
-                nrm += (nib & 1u) ? 0.f : a.x * a.x;
-                nrm += (nib & 2u) ? 0.f : a.y * a.y;
-                nrm += (nib & 4u) ? 0.f : a.z * a.z;
-                nrm += (nib & 8u) ? 0.f : a.w * a.w;
+            for (uint32_t u = 0; u < kTileGran; ++u) {
+                const size_t off = ((size_t)(gran0 + u) << 8) + lane * 4u;
+                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(A.g + off));
+                ev[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(A.e + off));
             }
-            publish_granule(gran, nib, lane, mask, blk_cnt, gran_per_blk);
+#pragma unroll
+            for (uint32_t u = 0; u < kTileGran; ++u) {
+                a[u].x = ev[u].x + gv[u].x;
+                a[u].y = ev[u].y + gv[u].y;
+                a[u].z = ev[u].z + gv[u].z;
+                a[u].w = ev[u].w + gv[u].w;
+                nib[u] = sel<CMP>(a[u].x, delta) | (sel<CMP>(a[u].y, delta) << 1) |
+                         (sel<CMP>(a[u].z, delta) << 2) | (sel<CMP>(a[u].w, delta) << 3);
+            }
         }
-    } else {
-        // Ragged end of the vector: guarded scalar accesses.
-        for (int u = 0; u < U; ++u) {
-            const uint32_t gran = gran0 + u * kWavesPerWG + wave;
-            if (gran >= n_gran) break;  // wave-uniform
-            const uint64_t base = ((uint64_t)gran << 8) + lane * 4u;
-            uint32_t nib = 0;
+
+        if (NORM) {
+#pragma unroll
+            for (uint32_t u = 0; u < kTileGran; ++u) {
+                nrm += (nib[u] & 1u) ? 0.f : a[u].x * a[u].x;
+                nrm += (nib[u] & 2u) ? 0.f : a[u].y * a[u].y;
+                nrm += (nib[u] & 4u) ? 0.f : a[u].z * a[u].z;
+                nrm += (nib[u] & 8u) ? 0.f : a[u].w * a[u].w;
+            }
+        }
+
+        uint32_t total = 0, word = 0;
+        if (__ballot((nib[0] | nib[1] | nib[2] | nib[3]) != 0)) {  // wave-uniform
+            uint32_t cu[kTileGran], below[kTileGran];
+#pragma unroll
+            for (uint32_t u = 0; u < kTileGran; ++u) {
+                cu[u] = 0;
+                below[u] = 0;
+                if (__ballot(nib[u] != 0)) granule_ranks(nib[u], cu[u], below[u]);  // wave-uniform
+                total += cu[u];
+            }
+            word = total;
+            if (total <= A.slots) {
+                // staged: pairs in index order, residual zeroed where sent (+0)
+                uint2   *slot = A.stage + (size_t)tile * A.slots;
+                uint32_t pre  = 0;
+#pragma unroll
+                for (uint32_t u = 0; u < kTileGran; ++u) {
+                    if (nib[u]) {
+                        uint32_t       r  = pre + below[u];
+                        const uint32_t i0 = ((gran0 + u) << 8) + lane * 4u;
+                        if (nib[u] & 1u) { slot[r++] = make_uint2(i0, __float_as_uint(a[u].x)); a[u].x = 0.f; }
+                        if (nib[u] & 2u) { slot[r++] = make_uint2(i0 + 1u, __float_as_uint(a[u].y)); a[u].y = 0.f; }
+                        if (nib[u] & 4u) { slot[r++] = make_uint2(i0 + 2u, __float_as_uint(a[u].z)); a[u].z = 0.f; }
+                        if (nib[u] & 8u) { slot[r++] = make_uint2(i0 + 3u, __float_as_uint(a[u].w)); a[u].w = 0.f; }
+                    }
+                    pre += cu[u];
+                }
+            } else {
+                word = total | kFlag;  // too many for the slots: compaction re-reads this tile
+            }
+            if (lane == 0) {
+                // per-block counters; consecutive granules of one block are added together.
+                // One counter per block / chunk keeps same-address atomics rare (they
+                // serialise at roughly 150 ns each across the dies).
+                uint32_t blk = A.gpb_shift < 32u ? gran0 >> A.gpb_shift : gran0 / A.gran_per_blk;
+                uint32_t in_blk = gran0 - blk * A.gran_per_blk;  // granule's position inside its block
+                uint32_t run = cu[0];
+#pragma unroll
+                for (uint32_t u = 1; u < kTileGran; ++u) {
+                    if (++in_blk == A.gran_per_blk) {  // granule gran0 + u starts the next block
+                        if (run) atomicAdd(&A.blk_cnt[blk], run);
+                        ++blk;
+                        in_blk = 0;
+                        run = 0;
+                    }
+                    run += cu[u];
+                }
+                if (run) atomicAdd(&A.blk_cnt[blk], run);
+                atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
+            }
+        }
+
+#pragma unroll
+        for (uint32_t u = 0; u < kTileGran; ++u) {
+            const size_t off = ((size_t)(gran0 + u) << 8) + lane * 4u;
+            __builtin_nontemporal_store(a[u], reinterpret_cast<f32x4 *>(A.e + off));
+        }
+        if (lane == 0) A.tile_cnt[tile] = word;
+    } else if (live) {
+        // The ragged end of the vector (at most the last workgroup): guarded
+        // scalar accesses, one granule at a time.  The tile is only counted and
+        // flagged; compaction ranks and zeroes it from the residual.
+        uint32_t total = 0;
+#pragma unroll 1
+        for (uint32_t u = 0; u < kTileGran; ++u) {
+            const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
+            uint32_t f = 0;
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) {
-                const uint64_t i = base + q;
-                if (i < n_g) {
-                    const float a = e[i] + g[i];
-                    e[i] = a;
-                    const uint32_t f = sel<CMP>(a, delta);
-                    nib |= f << q;
-                    if (NORM) nrm += f ? 0.f : a * a;
+                if (base + q < A.n_g) {
+                    const float v = A.e[base + q] + A.g[base + q];
+                    A.e[base + q] = v;
+                    const uint32_t hit = sel<CMP>(v, delta);
+                    f |= hit << q;
+                    if (NORM) nrm += hit ? 0.f : v * v;
                 }
             }
-            publish_granule(gran, nib, lane, mask, blk_cnt, gran_per_blk);
+            uint32_t cu, below;
+            granule_ranks(f, cu, below);
+            if (cu && lane == 0) atomicAdd(&A.blk_cnt[(gran0 + u) / A.gran_per_blk], cu);
+            total += cu;
+        }
+        if (lane == 0) {
+            if (total) atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
+            A.tile_cnt[tile] = total ? (total | kFlag) : 0u;
         }
     }
 
@@ -213,7 +298,7 @@ k_stream(const float *__restrict__ g, float *__restrict__ e, const DevState *__r
         __syncthreads();
         if (threadIdx.x == 0) {
             double tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
-            atomicAdd(&err_slots[blockIdx.x % kErrSlots], tot);
+            atomicAdd(&A.err_slots[blockIdx.x % kErrSlots], tot);
         }
     }
 }
@@ -222,13 +307,15 @@ k_stream(const float *__restrict__ g, float *__restrict__ e, const DevState *__r
 struct FinishArgs {
     DevState       *st;
     float          *e;
-    const uint32_t *mask;
-    const uint32_t *blk_cnt;       // this iteration's per-block counters (complete)
-    const uint32_t *sup_cnt;       // sums of 64 counters each; only valid when use_sup
-    uint32_t       *blk_cnt_next;  // the other parity's counters, cleared here
-    const int32_t  *cur_part;      // topology this iteration selected with
+    const uint2    *stage;
+    const uint32_t *tile_cnt;
+    const uint32_t *blk_cnt;         // this iteration's per-block counters (complete)
+    const uint32_t *seg_cnt;         // this iteration's per-segment counters (complete)
+    uint32_t       *blk_cnt_next;    // the other parity's counters, cleared here
+    uint32_t       *seg_cnt_next;
+    const int32_t  *cur_part;        // topology this iteration selected with
     const int32_t  *cur_pos;
-    int32_t        *nxt_part;      // receives Alg. 3's adjusted topology
+    int32_t        *nxt_part;        // receives Alg. 3's adjusted topology
     int32_t        *nxt_pos;
     uint64_t       *part_cnt;
     uint64_t       *part_off;
@@ -236,24 +323,9 @@ struct FinishArgs {
     float          *out_val;
     double         *err_slots;       // this iteration's norm partials
     double         *err_slots_next;  // cleared here
-    uint32_t        use_sup;
     uint64_t        t_next;          // iterations completed once this kernel is done
+    uint32_t        n_tiles, n_chunks, n_segs, seg_shift, slots, parity;
 };
-
-// Only for very many blocks (n_b > kSupThreshold): sup_cnt[i] = sum of the 64
-// block counters of group i, one wavefront per group.
-__global__ void __launch_bounds__(kFinishWG)
-k_sup(const uint32_t *__restrict__ blk_cnt, uint32_t *__restrict__ sup_cnt, uint32_t n_b,
-      uint32_t n_sup)
-{
-    const uint32_t i = blockIdx.x * (kFinishWG / 64) + (threadIdx.x >> 6);
-    if (i >= n_sup) return;
-    const uint32_t idx = (i << kSupShift) + (threadIdx.x & 63u);
-    uint32_t s = idx < n_b ? blk_cnt[idx] : 0u;
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
-    if ((threadIdx.x & 63u) == 0) sup_cnt[i] = s;
-}
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
 //
@@ -301,7 +373,7 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
         c4[q] = i < n_b ? A.blk_cnt[i] : 0u;
     }
     float delta = 0.f;
-    if (tid == 0) delta = A.st->delta;
+    if (tid == 0) delta = A.st->delta[A.parity];
     const int32_t part = tid < P ? A.cur_part[tid] : 0;
     const int32_t pos  = tid < P ? A.cur_pos[tid] : 0;
     if (tid < P) {
@@ -325,6 +397,11 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
                 const uint32_t i = i0 + q * kFinishWG;
                 c4[q] = i < n_b ? A.blk_cnt[i] : 0u;
             }
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {  // clean block counters for the next iteration
+            const uint32_t i = i0 + q * kFinishWG;
+            if (i < n_b) A.blk_cnt_next[i] = 0u;
         }
 #pragma unroll
         for (uint32_t q = 0; q < 4; ++q) {
@@ -472,8 +549,10 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
             sf = prm.sf_mid;
         else
             sf = prm.sf_lo;
+        const float next = delta * sf;
+        st->delta[A.parity ^ 1u] = next;  // the other slot: this iteration's compaction still reads delta[parity]
         st->delta_used = delta;
-        st->delta      = delta * sf;
+        st->delta_next = next;
 
         // ---- Eq. 2 / 5 / 6 ----
         uint64_t m_t = 0;
@@ -489,140 +568,160 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     }
 }
 
-// ---- compaction: a workgroup takes 16 consecutive blocks, one wavefront per
-// block.  The workgroup first sums the counters in front of its first block
-// (all 1024 threads, counters sit in L2), which is the output position of its
-// first pair.  The block's mask is read 256 words (8192 gradients) per load
-// instruction, lane l taking words 4l..4l+3 of each such slice, and up to four
-// slices are requested before anything waits on memory; a wave scan of the
-// popcounts per slice gives every lane the rank of its first set bit, so pairs
-// come out in ascending index order. ----
-constexpr uint32_t kLaneVec   = 4;                    // uint4 loads per lane and pass
-constexpr uint32_t kPassWords = 64 * kLaneVec * 4;    // 1024 words = 32768 gradients per pass
+// ---- compaction: a workgroup takes 16 consecutive chunks, one wavefront per
+// chunk, one lane per wave tile.  The output position of the chunk's first pair
+// is the number of selected gradients in front of it: the workgroup sums the
+// segment counters before its first chunk (all 1024 threads, counters sit in L2)
+// and the wave totals inside the workgroup; a wave scan of the 64 tile counts
+// then gives every lane the position of its tile's first pair.  Tiles, and the
+// pairs staged inside a tile, are in index order, so the output is ascending. ----
 
-template <bool NORM>
-__device__ void finish_compact(const FinishArgs &A, uint32_t n_b, uint32_t block_size, uint32_t n_g,
-                               uint64_t cap)
+// A flagged tile (more selected gradients than staging slots; its residual
+// still holds acc): the whole wave re-reads its 1024 gradients, repeats the
+// comparison with the threshold the streaming pass used, emits the pairs that
+// fit the output and zeroes them in the residual.
+template <bool NORM, int CMP>
+__device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32_t tile, uint64_t r0,
+                                                     float delta, uint32_t lane, uint32_t n_g,
+                                                     uint64_t cap, float &spill)
 {
-    __shared__ uint32_t red[kFinishWG / 64];
-    __shared__ uint32_t wcnt[kFinishWG / 64];
-    const uint32_t tid  = threadIdx.x;
-    const uint32_t lane = tid & 63u;
-    const uint32_t wave = tid >> 6;
-    const uint32_t j0   = (blockIdx.x - 1u) * (kFinishWG / 64);
-    const uint32_t j    = j0 + wave;
-
-    // this block's mask words (first pass) are requested up front, with the counter loads
-    const uint64_t first = (uint64_t)j * block_size;
-    uint32_t len = 0;
-    if (j < n_b) len = (uint64_t)n_g - first < block_size ? (uint32_t)(n_g - first) : block_size;
-    const uint32_t words = (((len + 31u) >> 5) + 3u) & ~3u;
-    const uint32_t *mw   = A.mask + (size_t)j * (block_size >> 5);
-    uint4 mv[kLaneVec];
+    if (!NORM && r0 >= cap) return;  // nothing fits: the tile stays in the residual as it is
+    float *__restrict__ e = A.e;
+    uint64_t running = r0;
+#pragma unroll 1
+    for (uint32_t u = 0; u < kTileGran; ++u) {
+        const uint64_t base = ((uint64_t)(tile * kTileGran + u) << 8) + lane * 4u;
+        float    v[4];
+        uint32_t nib = 0;
 #pragma unroll
-    for (uint32_t q = 0; q < kLaneVec; ++q) {
-        const uint32_t w = q * 256u + lane * 4u;
-        mv[q] = make_uint4(0, 0, 0, 0);
-        if (w < words) mv[q] = *reinterpret_cast<const uint4 *>(mw + w);
-    }
-    const uint32_t cnt_j = j < n_b ? A.blk_cnt[j] : 0u;
-
-    uint32_t s0 = 0, s1 = 0, s2 = 0, s3 = 0;
-    uint32_t lo = 0;
-    if (A.use_sup) {
-        const uint32_t sb = j0 >> kSupShift;
-        for (uint32_t i = tid; i < sb; i += kFinishWG) s0 += A.sup_cnt[i];
-        lo = sb << kSupShift;
-    }
-    {
-        uint32_t i = lo + tid;
-        for (; i + 3u * kFinishWG < j0; i += 4u * kFinishWG) {
-            s0 += A.blk_cnt[i];
-            s1 += A.blk_cnt[i + kFinishWG];
-            s2 += A.blk_cnt[i + 2u * kFinishWG];
-            s3 += A.blk_cnt[i + 3u * kFinishWG];
+        for (uint32_t q = 0; q < 4; ++q) {
+            v[q] = 0.f;
+            if (base + q < n_g) {
+                v[q] = e[base + q];
+                nib |= sel<CMP>(v[q], delta) << q;
+            }
         }
-        for (; i < j0; i += kFinishWG) s0 += A.blk_cnt[i];
+        uint32_t cu, below;
+        granule_ranks(nib, cu, below);
+        uint64_t r = running + below;
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q) {
+            if (nib & (1u << q)) {
+                if (r < cap) {
+                    A.out_idx[r]  = (uint32_t)(base + q);
+                    A.out_val[r]  = v[q];
+                    e[base + q]   = 0.0f;  // +0 where sent (Alg. 1 line 17)
+                } else if (NORM) {
+                    spill += v[q] * v[q];  // selected but not emitted: stays in the residual
+                }
+                ++r;
+            }
+        }
+        running += cu;
+    }
+}
+
+template <bool NORM, int CMP>
+__device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
+{
+    constexpr uint32_t kWaves = kFinishWG / 64;
+    __shared__ uint32_t red[kWaves];
+    __shared__ uint32_t wtot[kWaves];
+    const uint32_t tid    = threadIdx.x;
+    const uint32_t lane   = tid & 63u;
+    const uint32_t wave   = tid >> 6;
+    const uint32_t chunk0 = (blockIdx.x - 1u) * kWaves;
+    const uint32_t chunk  = chunk0 + wave;
+    const uint32_t tile   = (chunk << kChunkShift) + lane;
+
+    // all first loads are requested before anything waits on them
+    uint32_t word = 0;
+    if (chunk < A.n_chunks && tile < A.n_tiles) word = A.tile_cnt[tile];
+    float delta = 0.f;
+    if (word & kFlag) delta = A.st->delta[A.parity];
+    uint32_t s0 = 0, s1 = 0, s2 = 0, s3 = 0;
+    {
+        const uint32_t seg0 = chunk0 << (kChunkShift - A.seg_shift);  // segments in front of this workgroup
+        uint32_t i = tid;
+        for (; i + 3u * kFinishWG < seg0; i += 4u * kFinishWG) {
+            s0 += A.seg_cnt[i];
+            s1 += A.seg_cnt[i + kFinishWG];
+            s2 += A.seg_cnt[i + 2u * kFinishWG];
+            s3 += A.seg_cnt[i + 3u * kFinishWG];
+        }
+        for (; i < seg0; i += kFinishWG) s0 += A.seg_cnt[i];
     }
     uint32_t s = (s0 + s1) + (s2 + s3);
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+
+    const uint32_t c    = word & ~kFlag;
+    const uint32_t incl = wave_incl_scan(c, lane);
+    const uint32_t tot  = __shfl(incl, 63, 64);
     if (lane == 0) {
         red[wave]  = s;
-        wcnt[wave] = cnt_j;
+        wtot[wave] = tot;
     }
     __syncthreads();
-    if (j >= n_b) return;
-    uint64_t base = 0;  // selected gradients in front of block j = its output position
+    if (chunk >= A.n_chunks) return;
+    uint64_t base = 0;  // selected gradients in front of this chunk
 #pragma unroll
-    for (uint32_t w = 0; w < kFinishWG / 64; ++w) base += red[w] + (w < wave ? wcnt[w] : 0u);
+    for (uint32_t w = 0; w < kWaves; ++w) base += red[w] + (w < wave ? wtot[w] : 0u);
 
-    if (lane == 0) A.blk_cnt_next[j] = 0u;  // clean counter for the next iteration
-    if (cnt_j == 0) return;
-    if (!NORM && base >= cap) return;  // nothing of this block fits: it all stays in the residual
+    {   // clean segment counters for the next iteration
+        const uint32_t per_chunk = 1u << (kChunkShift - A.seg_shift);
+        const uint32_t sg        = chunk * per_chunk + lane;
+        if (lane < per_chunk && sg < A.n_segs) A.seg_cnt_next[sg] = 0u;
+    }
+    if (tot == 0) return;
 
-    float *__restrict__ e = A.e;
-    uint64_t running = base;
-    float    spill   = 0.f;
+    const uint64_t r0    = base + (incl - c);  // output position of this tile's first pair
+    float          spill = 0.f;
 
-    for (uint32_t w0 = 0; w0 < words; w0 += kPassWords) {
-        if (w0 != 0) {  // blocks above 32768 gradients take further passes
-#pragma unroll
-            for (uint32_t q = 0; q < kLaneVec; ++q) {
-                const uint32_t w = w0 + q * 256u + lane * 4u;
-                mv[q] = make_uint4(0, 0, 0, 0);
-                if (w < words) mv[q] = *reinterpret_cast<const uint4 *>(mw + w);
+    if (c && !(word & kFlag)) {
+        const uint2 *slot = A.stage + (size_t)tile * A.slots;
+        for (uint32_t t = 0; t < c; ++t) {
+            const uint2    pr = slot[t];
+            const uint64_t r  = r0 + t;
+            if (r < cap) {
+                A.out_idx[r] = pr.x;
+                A.out_val[r] = __uint_as_float(pr.y);
+            } else {
+                // beyond the output capacity: not sent, so it goes back into the residual
+                const float v = __uint_as_float(pr.y);
+                A.e[pr.x] = v;
+                if (NORM) spill += v * v;
             }
-        }
-#pragma unroll
-        for (uint32_t q = 0; q < kLaneVec; ++q) {
-            if (w0 + q * 256u >= words) break;  // uniform
-            const uint32_t c =
-                __popc(mv[q].x) + __popc(mv[q].y) + __popc(mv[q].z) + __popc(mv[q].w);
-            if (__ballot(c != 0) == 0) continue;  // uniform: nothing selected in this slice
-            const uint32_t incl = wave_incl_scan(c, lane);
-            const uint32_t tot  = __shfl(incl, 63, 64);
-            uint64_t r = running + (incl - c);
-            const uint32_t wv[4] = {mv[q].x, mv[q].y, mv[q].z, mv[q].w};
-#pragma unroll
-            for (uint32_t h = 0; h < 4; ++h) {
-                uint32_t       bits  = wv[h];
-                const uint32_t ebase = (uint32_t)first + (w0 + q * 256u + lane * 4u + h) * 32u;
-                while (bits) {
-                    const uint32_t i = ebase + (uint32_t)(__ffs(bits) - 1);
-                    bits &= bits - 1u;
-                    if (r < cap) {
-                        const float v = e[i];
-                        A.out_idx[r] = i;
-                        A.out_val[r] = v;
-                        e[i]         = 0.0f;  // +0 where sent (Alg. 1 line 17)
-                    } else if (NORM) {
-                        const float v = e[i];  // selected but not emitted: stays in the residual
-                        spill += v * v;
-                    }
-                    ++r;
-                }
-            }
-            running += tot;
         }
     }
+
+    uint64_t flagged = __ballot((word & kFlag) != 0);
+    while (flagged) {  // wave-uniform
+        const uint32_t l = (uint32_t)__ffsll((unsigned long long)flagged) - 1u;
+        flagged &= flagged - 1u;
+        const uint32_t lo = __shfl((uint32_t)r0, l, 64), hi = __shfl((uint32_t)(r0 >> 32), l, 64);
+        const float    dl = __shfl(delta, l, 64);
+        compact_flagged_tile<NORM, CMP>(A, (chunk << kChunkShift) + l, ((uint64_t)hi << 32) | lo, dl,
+                                        lane, n_g, cap, spill);
+    }
+
     if (NORM) {
         double sq = (double)spill;
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, 64);
-        if (lane == 0 && sq != 0.0) atomicAdd(&A.err_slots[j % kErrSlots], sq);
+        if (lane == 0 && sq != 0.0) atomicAdd(&A.err_slots[chunk % kErrSlots], sq);
     }
 }
 
 // 8 waves per SIMD (64 VGPRs) so that two of these 16-wave workgroups fit a CU
-template <bool NORM>
+template <bool NORM, int CMP>
 __global__ void __launch_bounds__(kFinishWG, 8)
 k_finish(FinishArgs A, CtrlParams prm)
 {
     if (blockIdx.x == 0)
         finish_control(A, prm);
     else
-        finish_compact<NORM>(A, prm.n_b, prm.block_size, (uint32_t)prm.n_g, prm.cap);
+        finish_compact<NORM, CMP>(A, (uint32_t)prm.n_g, prm.cap);
 }
 
 // ---------------------------------------------------------------------------
@@ -657,8 +756,10 @@ __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_
     if (tid == P) part_off[P] = 0;
     if (tid < 2 * kErrSlots) err_slots[tid] = 0.0;
     if (tid == 0) {
-        st->delta = delta0;
+        st->delta[0] = delta0;
+        st->delta[1] = delta0;
         st->delta_used = delta0;
+        st->delta_next = delta0;
         st->overflow = 0; st->moves = 0; st->t = 0;
         st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
         st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
@@ -687,7 +788,7 @@ struct exdyna_ctx {
     exdyna_config cfg;
     CtrlParams    prm;
     Layout        lay;
-    uint64_t      n_b, cap, n_gran;
+    uint64_t      n_b, cap;
     uint64_t      t;  // iterations enqueued
     float        *d_residual;
     char         *ws;
@@ -705,7 +806,6 @@ int validate_config(const exdyna_config *c, uint64_t *n_b_out, uint64_t *cap_out
     if (c->n_g == 0 || c->n_g > 0xFFFFFFFFull) return EXDYNA_EINVAL;
     if (c->block_size == 0 || c->block_size % kGran != 0) return EXDYNA_EINVAL;
     const uint64_t n_b = (c->n_g + c->block_size - 1) / c->block_size;
-    if (n_b > kMaxBlocks) return EXDYNA_EINVAL;
     if (c->n_parts == 0 || c->n_parts > n_b || c->n_parts > kMaxParts) return EXDYNA_EINVAL;
     if (!(c->density > 0.0 && c->density <= 1.0)) return EXDYNA_EINVAL;
     if (!(c->threshold0 > 0.0f) || std::isinf(c->threshold0)) return EXDYNA_EINVAL;
@@ -727,23 +827,48 @@ int validate_config(const exdyna_config *c, uint64_t *n_b_out, uint64_t *cap_out
     return EXDYNA_OK;
 }
 
+// Staging slots per wave tile: room for four times the expected number of
+// selected gradients in 1024 (density d), a power of two between 8 and 64.
+uint32_t staging_slots(double density)
+{
+    const double want = 4.0 * density * (double)kTile + 4.0;
+    uint32_t s = 8;
+    while (s < 64 && (double)s < want) s <<= 1;
+    return s;
+}
+
+// Wave tiles per segment counter.  Every tile with a selected gradient adds to
+// its segment's counter, and same-address atomics from many workgroups
+// serialise; the segment is sized so that about ten tiles per segment are
+// expected to add anything (a tile does with probability 1 - exp(-1024 d)).
+uint32_t segment_shift(double density)
+{
+    const double p_hit = 1.0 - std::exp(-(double)kTile * density);
+    uint32_t sh = kChunkShift;
+    while (sh > 2 && (double)(1u << sh) * p_hit > 12.0) --sh;
+    return sh;
+}
+
 Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
 {
     Layout L{};
     const size_t P = c->n_parts;
-    const size_t n_gran = (c->n_g + kGran - 1) / kGran;
+    L.n_tiles  = (c->n_g + kTile - 1) / kTile;
+    L.n_chunks = (L.n_tiles + (1u << kChunkShift) - 1) >> kChunkShift;
+    L.slots    = staging_slots(c->density);
+    L.seg_shift = segment_shift(c->density);
+    L.n_segs   = (L.n_tiles + (1u << L.seg_shift) - 1) >> L.seg_shift;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L.state     = take(sizeof(DevState));
-    L.parts     = take(4 * P * sizeof(int32_t));        // slot0 part,pos ; slot1 part,pos
+    L.parts     = take(4 * P * sizeof(int32_t));             // slot0 part,pos ; slot1 part,pos
     L.part_cnt  = take(P * sizeof(uint64_t));
     L.part_off  = take((P + 1) * sizeof(uint64_t));
-    L.blk_cnt   = take(2 * n_b * sizeof(uint32_t));      // two alternating counter arrays
-    L.n_sup     = (n_b >> kSupShift) + 1;
-    L.sup_cnt   = take(L.n_sup * sizeof(uint32_t));      // coarse counters (many-block case)
+    L.blk_cnt   = take(2 * n_b * sizeof(uint32_t));           // two alternating counter arrays
+    L.seg_cnt   = take(2 * L.n_segs * sizeof(uint32_t));      // likewise
+    L.tile_cnt  = take(L.n_tiles * sizeof(uint32_t));
     L.err_slots = take(2 * kErrSlots * sizeof(double));
-    L.mask_words = n_gran * kGranWords;
-    L.mask      = take(L.mask_words * sizeof(uint32_t));
+    L.stage     = take(L.n_tiles * L.slots * sizeof(uint2));
     L.out_idx   = take(cap * sizeof(uint32_t));
     L.out_val   = take(cap * sizeof(float));
     L.total     = off;
@@ -771,16 +896,66 @@ int32_t *slot_pos(exdyna_ctx *c, uint64_t slot) { return slot_part(c, slot) + c-
 uint32_t *blk_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.blk_cnt) + (t & 1) * c->n_b; }
 double *err_slots_of(exdyna_ctx *c, uint64_t t) { return at<double>(c, c->lay.err_slots) + (t & 1) * kErrSlots; }
 
+uint32_t *seg_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.seg_cnt) + (t & 1) * c->lay.n_segs; }
+
 template <int CMP, bool NORM>
 void launch_stream(exdyna_ctx *c, const float *g, hipStream_t s)
 {
-    constexpr int U = EXDYNA_UNROLL;
-    const uint32_t per_wg = kWavesPerWG * U;
-    const uint32_t grid = (uint32_t)((c->n_gran + per_wg - 1) / per_wg);
-    hipLaunchKernelGGL((k_stream<CMP, NORM, U>), dim3(grid), dim3(kStreamWG), 0, s, g, c->d_residual,
-                       at<DevState>(c, c->lay.state), at<uint32_t>(c, c->lay.mask),
-                       blk_cnt_of(c, c->t), err_slots_of(c, c->t), (uint32_t)c->cfg.n_g,
-                       (uint32_t)c->n_gran, c->cfg.block_size / kGran);
+    StreamArgs A;
+    A.g = g;
+    A.e = c->d_residual;
+    A.st = at<DevState>(c, c->lay.state);
+    A.stage = at<uint2>(c, c->lay.stage);
+    A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
+    A.blk_cnt = blk_cnt_of(c, c->t);
+    A.seg_cnt = seg_cnt_of(c, c->t);
+    A.seg_shift = c->lay.seg_shift;
+    A.err_slots = err_slots_of(c, c->t);
+    A.n_g = (uint32_t)c->cfg.n_g;
+    A.n_tiles = (uint32_t)c->lay.n_tiles;
+    A.gran_per_blk = c->cfg.block_size / kGran;
+    A.gpb_shift = 32;
+    for (uint32_t sh = 0; sh < 32; ++sh)
+        if ((1u << sh) == A.gran_per_blk) A.gpb_shift = sh;
+    A.slots = c->lay.slots;
+    A.parity = (uint32_t)(c->t & 1);
+    const uint32_t grid = (uint32_t)((c->lay.n_tiles + kWavesPerWG - 1) / kWavesPerWG);
+    hipLaunchKernelGGL((k_stream<CMP, NORM>), dim3(grid), dim3(kStreamWG), 0, s, A);
+}
+
+template <bool NORM, int CMP>
+void launch_finish(exdyna_ctx *c, hipStream_t s)
+{
+    const uint64_t t = c->t;
+    FinishArgs A;
+    A.st = at<DevState>(c, c->lay.state);
+    A.e = c->d_residual;
+    A.stage = at<uint2>(c, c->lay.stage);
+    A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
+    A.blk_cnt = blk_cnt_of(c, t);
+    A.seg_cnt = seg_cnt_of(c, t);
+    A.blk_cnt_next = blk_cnt_of(c, t + 1);
+    A.seg_cnt_next = seg_cnt_of(c, t + 1);
+    A.cur_part = slot_part(c, t);
+    A.cur_pos = slot_pos(c, t);
+    A.nxt_part = slot_part(c, t + 1);
+    A.nxt_pos = slot_pos(c, t + 1);
+    A.part_cnt = at<uint64_t>(c, c->lay.part_cnt);
+    A.part_off = at<uint64_t>(c, c->lay.part_off);
+    A.out_idx = at<uint32_t>(c, c->lay.out_idx);
+    A.out_val = at<float>(c, c->lay.out_val);
+    A.err_slots = err_slots_of(c, t);
+    A.err_slots_next = err_slots_of(c, t + 1);
+    A.t_next = t + 1;
+    A.n_tiles = (uint32_t)c->lay.n_tiles;
+    A.n_chunks = (uint32_t)c->lay.n_chunks;
+    A.n_segs = (uint32_t)c->lay.n_segs;
+    A.seg_shift = c->lay.seg_shift;
+    A.slots = c->lay.slots;
+    A.parity = (uint32_t)(t & 1);
+    const uint32_t per_wg = kFinishWG / 64;
+    const uint32_t grid = 1u + (uint32_t)((c->lay.n_chunks + per_wg - 1) / per_wg);
+    hipLaunchKernelGGL((k_finish<NORM, CMP>), dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
 }
 
 }  // namespace
@@ -839,7 +1014,6 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
     c->lay = L;
     c->n_b = n_b;
     c->cap = cap;
-    c->n_gran = (cfg->n_g + kGran - 1) / kGran;
     c->t = 0;
     c->d_residual = d_residual;
     c->ws = static_cast<char *>(d_workspace);
@@ -867,15 +1041,15 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
 
     hipStream_t s = c->stream;
     const uint32_t P = cfg->n_parts;
-    // residual <- 0 (Alg. 1 line 3); counters and mask start clean
+    // residual <- 0 (Alg. 1 line 3); counters start clean
     hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, s,
                        reinterpret_cast<uint32_t *>(d_residual), 0u, (size_t)cfg->n_g);
     hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
                        (size_t)(2 * n_b));
-    hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.sup_cnt), 0u,
-                       (size_t)L.n_sup);
-    hipLaunchKernelGGL(k_fill_u32, dim3(1024), dim3(256), 0, s, at<uint32_t>(c, L.mask), 0u,
-                       L.mask_words);
+    hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.seg_cnt), 0u,
+                       (size_t)(2 * L.n_segs));
+    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.tile_cnt), 0u,
+                       L.n_tiles);
     const uint32_t init_threads = (P + 1 > 2 * kErrSlots ? P + 1 : 2 * kErrSlots);
     hipLaunchKernelGGL(k_init_state, dim3((init_threads + 255) / 256), dim3(256), 0, s,
                        at<DevState>(c, L.state), slot_part(c, 0), slot_pos(c, 0), slot_part(c, 1),
@@ -911,37 +1085,11 @@ int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
     if (prof) HIP_TRY(c, hipEventRecord(ev[1], s));
 
     const uint64_t t = c->t;
-    FinishArgs A;
-    A.st = at<DevState>(c, c->lay.state);
-    A.e = c->d_residual;
-    A.mask = at<uint32_t>(c, c->lay.mask);
-    A.blk_cnt = blk_cnt_of(c, t);
-    A.sup_cnt = at<uint32_t>(c, c->lay.sup_cnt);
-    A.blk_cnt_next = blk_cnt_of(c, t + 1);
-    A.use_sup = c->n_b > kSupThreshold ? 1u : 0u;
-    A.t_next = t + 1;
-    if (A.use_sup) {
-        const uint32_t n_sup = (uint32_t)c->lay.n_sup;
-        hipLaunchKernelGGL(k_sup, dim3((n_sup + kFinishWG / 64 - 1) / (kFinishWG / 64)),
-                           dim3(kFinishWG), 0, s, A.blk_cnt, at<uint32_t>(c, c->lay.sup_cnt),
-                           (uint32_t)c->n_b, n_sup);
+    if (c->cfg.cmp_mode == 0) {
+        if (norm) launch_finish<true, 0>(c, s); else launch_finish<false, 0>(c, s);
+    } else {
+        if (norm) launch_finish<true, 1>(c, s); else launch_finish<false, 1>(c, s);
     }
-    A.cur_part = slot_part(c, t);
-    A.cur_pos = slot_pos(c, t);
-    A.nxt_part = slot_part(c, t + 1);
-    A.nxt_pos = slot_pos(c, t + 1);
-    A.part_cnt = at<uint64_t>(c, c->lay.part_cnt);
-    A.part_off = at<uint64_t>(c, c->lay.part_off);
-    A.out_idx = at<uint32_t>(c, c->lay.out_idx);
-    A.out_val = at<float>(c, c->lay.out_val);
-    A.err_slots = err_slots_of(c, t);
-    A.err_slots_next = err_slots_of(c, t + 1);
-    const uint32_t per_wg = kFinishWG / 64;
-    const uint32_t grid = 1u + (uint32_t)((c->n_b + per_wg - 1) / per_wg);
-    if (norm)
-        hipLaunchKernelGGL(k_finish<true>, dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
-    else
-        hipLaunchKernelGGL(k_finish<false>, dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
     if (prof) HIP_TRY(c, hipEventRecord(ev[2], s));
     HIP_TRY(c, hipGetLastError());
     c->t = t + 1;
@@ -1043,7 +1191,7 @@ int exdyna_get_stats(exdyna_ctx *c, exdyna_stats *h_out)
     h_out->traffic_ratio = st.traffic_ratio;
     h_out->err_norm = (c->cfg.want_err_norm && c->t > 0) ? st.err_norm : -1.0;
     h_out->delta_used = st.delta_used;
-    h_out->delta_next = st.delta;
+    h_out->delta_next = st.delta_next;
     h_out->overflow = st.overflow;
     h_out->moves = st.moves;
     return EXDYNA_OK;

@@ -49,8 +49,8 @@ def test_workspace_bytes_accepts_the_five_configurations():
     for w in WORKLOADS.values():
         cfg = _good(n_g=w.n_g, block_size=w.block_size, n_parts=w.n_parts, density=w.density)
         nbytes = binding.workspace_bytes(cfg)
-        # 1 bit per gradient for the mask dominates; far below one fp32 vector
-        assert w.n_g // 8 <= nbytes < w.n_g * 4 // 8 + (64 << 20)
+        # staging slots dominate (8..64 pairs per 1024 gradients): below one fp32 vector
+        assert w.n_g // 1024 * 8 * 8 <= nbytes < w.n_g * 4 // 4 + (64 << 20)
 
 
 @pytest.mark.parametrize("bad", [
@@ -60,7 +60,6 @@ def test_workspace_bytes_accepts_the_five_configurations():
     dict(threshold0=float("inf")), dict(threshold0=float("nan")), dict(cmp_mode=2),
     dict(alpha=0.99), dict(alpha=float("nan")), dict(beta=1.0), dict(gamma=0.0), dict(gamma=1.0),
     dict(min_blk=0), dict(reserved=1), dict(max_selected=(1 << 20) + 1),
-    dict(n_g=1 << 29, block_size=256),        # more than 2^20 blocks
 ])
 def test_bad_configurations_are_rejected(bad):
     with pytest.raises(binding.ExDynaError) as ei:

@@ -22,15 +22,16 @@ def _thr(w):
     return synthetic.initial_threshold(g0, w.density)
 
 
-# unroll 4 x 4 waves x 256 = 4096 gradients per workgroup: these sizes span several
-# workgroups, leave partial workgroups, partial granules and n_g % 4 != 0 tails
+# a wavefront owns 1024 gradients and a workgroup 4096: these sizes span several
+# workgroups and compaction chunks (65536), leave partial workgroups, partial wave
+# tiles, partial granules and n_g % 4 != 0 tails
 @pytest.mark.parametrize("n_g,b,P,d", [
     (4096 * 5 + 777, 256, 4, 0.01),
     (4096 * 3, 1024, 3, 0.02),
     (100_003, 768, 7, 0.005),
     (65_536 * 3 + 1, 65_536, 2, 0.001),
     (1_000_001, 4096, 16, 0.01),
-    (196_608 * 3 + 5, 196_608, 2, 0.002),      # blocks above 65536 gradients: several mask passes
+    (196_608 * 3 + 5, 196_608, 2, 0.002),      # blocks larger than a compaction chunk
     (300_000, 512, 40, 0.01),
 ])
 def test_small_trajectories_bit_exact(n_g, b, P, d):
@@ -140,8 +141,8 @@ def test_partition_count_extremes():
     x.close()
 
 
-def test_many_small_blocks_use_the_coarse_counter_path():
-    """More than 32768 blocks: the finishing kernel reads per-64-block sums built by a pre-pass."""
+def test_many_small_blocks():
+    """Blocks of one granule, tens of thousands of them, wave tiles straddling four blocks each."""
     n = 256 * 40_000 + 100
     w = synthetic.WORKLOADS[5].scaled(n, 256, 1024)
     log("case n_b = 40001")
