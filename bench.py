@@ -23,21 +23,26 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ALG_BYTES_PER_ELEM = 12.0      # read g (4) + read e (4) + write e' (4)
 ALG_BYTES_PER_PAIR = 8.0       # u32 index + fp32 value per selected gradient
 
-# HBM bytes per k_stream launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# (profiles/), keyed by workload index; None until measured for that workload.
-MEASURED_TRAFFIC_BYTES = {}
+# HBM bytes per k_stream launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# summarised in profiles/k_stream_cfg4_hbm_traffic.txt (each counter scaled by what it reads for
+# a plain device copy of one gradient vector: FETCH_SIZE x2.000, WRITE_SIZE x1.000, KiB), keyed
+# by workload index; None for workloads that have not been measured.
+MEASURED_TRAFFIC_BYTES = {4: int((540622.0 * 2.0 + 548717.6) * 1024)}
 
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=60)
     ap.add_argument("--config", type=int, default=4, help="workload 1..5 (default 4: n_g=138,357,544)")
     ap.add_argument("--cpu-steps", type=int, default=-1,
                     help="oracle steps for the CPU baseline (-1: sized for ~15 s, 0: skip)")
     ap.add_argument("--no-profile-events", action="store_true",
                     help="do not record per-kernel HIP events in the timed region")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain device copy of one gradient vector before the timed "
+                         "region (a known-size reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--hbm-budget-gb", type=float, default=160.0,
                     help="HBM to spend on pre-generated gradient vectors")
     args = ap.parse_args()
@@ -105,6 +110,12 @@ def main() -> int:
                "sample": f"first {cpu_steps} iterations of the same trajectory at full n_g, "
                          f"single thread, {cpu_s:.1f} s; GPU outputs bit-equal on these steps"}
         torch.cuda.empty_cache()
+
+    if args.calibration_copy:
+        ref = torch.empty_like(grads[0])
+        ref.copy_(grads[0])        # reads 4*n_g bytes, writes 4*n_g bytes
+        torch.cuda.synchronize()
+        del ref
 
     # ---- timed region ---------------------------------------------------------
     x = binding.ExDyna(cfg, dev)
