@@ -132,6 +132,9 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    ms_events = None
+    if prof:
+        ms_events = np.array([x.get_kernel_ms(t) for t in range(W, W + K)], dtype=np.float64)
     st = x.get_stats()
     ms_per_step = elapsed / K * 1e3
     value = w.n_g * K / elapsed / 1e9
@@ -139,7 +142,7 @@ def main() -> int:
     kern = None
     roofline = None
     if prof:
-        ms = np.array([x.get_kernel_ms(t) for t in range(W, W + K)], dtype=np.float64)
+        ms = ms_events
         kern = {"k_stream_ms": round(float(ms[:, 0].mean()), 5),
                 "k_finish_ms": round(float(ms[:, 1].mean()), 5)}
         achieved = ALG_BYTES_PER_ELEM * w.n_g / (ms[:, 0].mean() * 1e-3) / 1e9

@@ -110,7 +110,15 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
 
 /* One iteration (see the top of this file).  d_grad: n_g floats, 16-byte
  * aligned, read only, already scaled by the learning rate (the accumulate is a
- * single fp32 add).  Asynchronous: returns after enqueueing two kernels. */
+ * single fp32 add).  Asynchronous: returns after enqueueing two kernels.
+ *
+ * HIP graphs: the two launches are plain kernel nodes (no memset, no event
+ * unless profiling is on), all state they read or write is in the workspace,
+ * and consecutive iterations alternate between two sets of counters.  A
+ * stream capture of an EVEN number of consecutive exdyna_step calls (with
+ * profiling off and fixed d_grad addresses) can therefore be replayed any
+ * number of times; each replay advances the device state by that many
+ * iterations and the getters keep reporting the last iteration. */
 int exdyna_step(exdyna_ctx *ctx, const float *d_grad, void *hip_stream);
 
 /* Results of the last step.  *d_idx / *d_val: device arrays of k_emitted

@@ -323,7 +323,6 @@ struct FinishArgs {
     float          *out_val;
     double         *err_slots;       // this iteration's norm partials
     double         *err_slots_next;  // cleared here
-    uint64_t        t_next;          // iterations completed once this kernel is done
     uint32_t        n_tiles, n_chunks, n_segs, seg_shift, slots, parity;
 };
 
@@ -372,8 +371,12 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
         const uint32_t i = tid + q * kFinishWG;
         c4[q] = i < n_b ? A.blk_cnt[i] : 0u;
     }
-    float delta = 0.f;
-    if (tid == 0) delta = A.st->delta[A.parity];
+    float    delta  = 0.f;
+    uint64_t t_done = 0;
+    if (tid == 0) {
+        delta  = A.st->delta[A.parity];
+        t_done = A.st->t;
+    }
     const int32_t part = tid < P ? A.cur_part[tid] : 0;
     const int32_t pos  = tid < P ? A.cur_pos[tid] : 0;
     if (tid < P) {
@@ -563,7 +566,7 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
         st->k_max_part    = m_t;
         st->density_error = fabs(prm.k - (double)k_actual) / (double)prm.n_g;
         st->traffic_ratio = k_actual ? (double)P * (double)m_t / (double)k_actual : 0.0;
-        st->t     = A.t_next;
+        st->t     = t_done + 1;  // counted on the device so that a captured graph can be replayed
         st->moves = n_moves;
     }
 }
@@ -587,32 +590,50 @@ __device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32
 {
     if (!NORM && r0 >= cap) return;  // nothing fits: the tile stays in the residual as it is
     float *__restrict__ e = A.e;
-    uint64_t running = r0;
-#pragma unroll 1
-    for (uint32_t u = 0; u < kTileGran; ++u) {
-        const uint64_t base = ((uint64_t)(tile * kTileGran + u) << 8) + lane * 4u;
-        float    v[4];
-        uint32_t nib = 0;
+    const uint32_t gran0 = tile * kTileGran;
+    float    v[kTileGran][4];
+    uint32_t nib[kTileGran];
+    if (gran0 + kTileGran <= (n_g >> 8)) {  // whole tile inside the vector: four float4 loads in flight
+        f32x4 a[kTileGran];
 #pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            v[q] = 0.f;
-            if (base + q < n_g) {
-                v[q] = e[base + q];
-                nib |= sel<CMP>(v[q], delta) << q;
-            }
+        for (uint32_t u = 0; u < kTileGran; ++u)
+            a[u] = *reinterpret_cast<const f32x4 *>(e + ((size_t)(gran0 + u) << 8) + lane * 4u);
+#pragma unroll
+        for (uint32_t u = 0; u < kTileGran; ++u) {
+            v[u][0] = a[u].x; v[u][1] = a[u].y; v[u][2] = a[u].z; v[u][3] = a[u].w;
         }
+    } else {
+#pragma unroll
+        for (uint32_t u = 0; u < kTileGran; ++u) {
+            const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) v[u][q] = base + q < n_g ? e[base + q] : 0.f;
+        }
+    }
+#pragma unroll
+    for (uint32_t u = 0; u < kTileGran; ++u) {
+        const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
+        nib[u] = 0;
+#pragma unroll
+        for (uint32_t q = 0; q < 4; ++q)
+            if (base + q < n_g) nib[u] |= sel<CMP>(v[u][q], delta) << q;
+    }
+    uint64_t running = r0;
+#pragma unroll
+    for (uint32_t u = 0; u < kTileGran; ++u) {
+        const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
         uint32_t cu, below;
-        granule_ranks(nib, cu, below);
+        granule_ranks(nib[u], cu, below);
         uint64_t r = running + below;
 #pragma unroll
         for (uint32_t q = 0; q < 4; ++q) {
-            if (nib & (1u << q)) {
+            if (nib[u] & (1u << q)) {
                 if (r < cap) {
-                    A.out_idx[r]  = (uint32_t)(base + q);
-                    A.out_val[r]  = v[q];
-                    e[base + q]   = 0.0f;  // +0 where sent (Alg. 1 line 17)
+                    A.out_idx[r] = (uint32_t)(base + q);
+                    A.out_val[r] = v[u][q];
+                    e[base + q]  = 0.0f;  // +0 where sent (Alg. 1 line 17)
                 } else if (NORM) {
-                    spill += v[q] * v[q];  // selected but not emitted: stays in the residual
+                    spill += v[u][q] * v[u][q];  // selected but not emitted: stays in the residual
                 }
                 ++r;
             }
@@ -713,9 +734,8 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
     }
 }
 
-// 8 waves per SIMD (64 VGPRs) so that two of these 16-wave workgroups fit a CU
 template <bool NORM, int CMP>
-__global__ void __launch_bounds__(kFinishWG, 8)
+__global__ void __launch_bounds__(kFinishWG)
 k_finish(FinishArgs A, CtrlParams prm)
 {
     if (blockIdx.x == 0)
@@ -946,7 +966,6 @@ void launch_finish(exdyna_ctx *c, hipStream_t s)
     A.out_val = at<float>(c, c->lay.out_val);
     A.err_slots = err_slots_of(c, t);
     A.err_slots_next = err_slots_of(c, t + 1);
-    A.t_next = t + 1;
     A.n_tiles = (uint32_t)c->lay.n_tiles;
     A.n_chunks = (uint32_t)c->lay.n_chunks;
     A.n_segs = (uint32_t)c->lay.n_segs;
