@@ -57,7 +57,7 @@ constexpr uint32_t kTileGran    = 4;     // granules per wave tile
 constexpr uint32_t kTile        = kGran * kTileGran;  // 1024 gradients per wavefront
 constexpr uint32_t kStreamWG    = 256;   // k_stream: 4 wavefronts = 4096 contiguous gradients
 constexpr uint32_t kWavesPerWG  = kStreamWG / 64;
-constexpr uint32_t kChunkShift  = 6;     // 64 wave tiles (65536 gradients) per compaction wavefront
+constexpr uint32_t kChunkShift  = 6;     // at most 64 wave tiles (65536 gradients) per compaction wavefront
 constexpr uint32_t kMaxParts    = 1024;
 constexpr uint32_t kFinishWG    = 1024;  // k_finish: 16 waves = control, or 16 chunks
 constexpr uint32_t kErrSlots    = 256;
@@ -92,8 +92,11 @@ struct CtrlParams {
 struct Layout {
     size_t state, parts, part_cnt, part_off, blk_cnt, seg_cnt, tile_cnt, err_slots, stage,
         out_idx, out_val, total;
-    size_t n_tiles, n_chunks, n_segs;
-    uint32_t slots;      // staging slots per wave tile
+    size_t n_tiles, n_chunks, n_segs, pool_pairs;
+    uint32_t chunk_shift; // log2(wave tiles per compaction wavefront)
+    size_t slot_tab;
+    uint32_t pool_extra; // staging pairs handed out in proportion to the last counts
+    uint32_t slots;      // staging slots every wave tile always has
     uint32_t seg_shift;  // log2(wave tiles per segment counter)
 };
 
@@ -145,12 +148,13 @@ struct StreamArgs {
     const float    *g;
     float          *e;
     const DevState *st;
-    uint2          *stage;      // n_tiles x slots pairs (index, value bits)
+    uint2          *stage;      // staging pool of (index, value bits) pairs
+    const uint2    *slot_tab;   // per tile: {first slot, number of slots} for this iteration
     uint32_t       *tile_cnt;   // n_tiles: selected in the tile, kFlag if not staged
     uint32_t       *blk_cnt;    // this iteration's per-block counters (zero on entry)
     uint32_t       *seg_cnt;    // this iteration's per-segment counters (zero on entry)
     double         *err_slots;
-    uint32_t        n_g, n_tiles, gran_per_blk, slots, parity;
+    uint32_t        n_g, n_tiles, gran_per_blk, parity;
     uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
     uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
 };
@@ -162,7 +166,8 @@ k_stream(StreamArgs A)
     const float    delta  = A.st->delta[A.parity];
     const uint32_t lane   = threadIdx.x & 63u;
     const uint32_t wave   = threadIdx.x >> 6;
-    const uint32_t tile   = blockIdx.x * kWavesPerWG + wave;
+    // the tile index is the same in all lanes: keep it in a scalar register
+    const uint32_t tile   = __builtin_amdgcn_readfirstlane(blockIdx.x * kWavesPerWG + wave);
     const uint32_t gran0  = tile * kTileGran;
     const uint32_t n_full = A.n_g >> 8;  // complete granules
     const bool     live   = tile < A.n_tiles;            // wave-uniform
@@ -172,6 +177,7 @@ k_stream(StreamArgs A)
     if (live && fast) {
         f32x4    a[kTileGran];
         uint32_t nib[kTileGran];
+        const uint2 tab = A.slot_tab[tile];  // requested with the data, used only if something is selected
         {
             f32x4 gv[kTileGran], ev[kTileGran];
 #pragma unroll
@@ -212,9 +218,9 @@ k_stream(StreamArgs A)
                 total += cu[u];
             }
             word = total;
-            if (total <= A.slots) {
+            if (total <= tab.y) {
                 // staged: pairs in index order, residual zeroed where sent (+0)
-                uint2   *slot = A.stage + (size_t)tile * A.slots;
+                uint2   *slot = A.stage + tab.x;
                 uint32_t pre  = 0;
 #pragma unroll
                 for (uint32_t u = 0; u < kTileGran; ++u) {
@@ -308,6 +314,8 @@ struct FinishArgs {
     DevState       *st;
     float          *e;
     const uint2    *stage;
+    const uint2    *slot_tab;        // this iteration's {first slot, slots} per tile
+    uint2          *slot_tab_next;   // the next iteration's, written here
     const uint32_t *tile_cnt;
     const uint32_t *blk_cnt;         // this iteration's per-block counters (complete)
     const uint32_t *seg_cnt;         // this iteration's per-segment counters (complete)
@@ -323,7 +331,7 @@ struct FinishArgs {
     float          *out_val;
     double         *err_slots;       // this iteration's norm partials
     double         *err_slots_next;  // cleared here
-    uint32_t        n_tiles, n_chunks, n_segs, seg_shift, slots, parity;
+    uint32_t        n_tiles, n_chunks, n_segs, seg_shift, chunk_shift, slots_min, pool_extra, parity;
 };
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
@@ -648,21 +656,30 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
     constexpr uint32_t kWaves = kFinishWG / 64;
     __shared__ uint32_t red[kWaves];
     __shared__ uint32_t wtot[kWaves];
+    __shared__ uint32_t s_incl[kWaves][64];  // per wave: running count of staged pairs over its tiles
+    __shared__ uint32_t s_off[kWaves][64];   // first staging slot of each tile
+    __shared__ uint32_t s_rel[kWaves][64];   // output position of each tile's first pair, minus the chunk's
     const uint32_t tid    = threadIdx.x;
     const uint32_t lane   = tid & 63u;
     const uint32_t wave   = tid >> 6;
+    const uint32_t cs     = A.chunk_shift;             // log2(wave tiles per chunk)
     const uint32_t chunk0 = (blockIdx.x - 1u) * kWaves;
     const uint32_t chunk  = chunk0 + wave;
-    const uint32_t tile   = (chunk << kChunkShift) + lane;
+    const uint32_t tile   = (chunk << cs) + lane;
 
     // all first loads are requested before anything waits on them
     uint32_t word = 0;
-    if (chunk < A.n_chunks && tile < A.n_tiles) word = A.tile_cnt[tile];
+    uint2    tab  = make_uint2(0u, 0u);
+    const bool have_tile = chunk < A.n_chunks && lane < (1u << cs) && tile < A.n_tiles;
+    if (have_tile) {
+        word = A.tile_cnt[tile];
+        tab  = A.slot_tab[tile];
+    }
     float delta = 0.f;
     if (word & kFlag) delta = A.st->delta[A.parity];
     uint32_t s0 = 0, s1 = 0, s2 = 0, s3 = 0;
     {
-        const uint32_t seg0 = chunk0 << (kChunkShift - A.seg_shift);  // segments in front of this workgroup
+        const uint32_t seg0 = (chunk0 << cs) >> A.seg_shift;  // segments in front of this workgroup
         uint32_t i = tid;
         for (; i + 3u * kFinishWG < seg0; i += 4u * kFinishWG) {
             s0 += A.seg_cnt[i];
@@ -676,9 +693,15 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
 #pragma unroll
     for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
 
-    const uint32_t c    = word & ~kFlag;
-    const uint32_t incl = wave_incl_scan(c, lane);
-    const uint32_t tot  = __shfl(incl, 63, 64);
+    const uint32_t c     = word & ~kFlag;                 // selected in this lane's tile
+    const uint32_t cstg  = (word & kFlag) ? 0u : c;       // ... of which staged
+    const uint32_t incl  = wave_incl_scan(c, lane);
+    const uint32_t incls = wave_incl_scan(cstg, lane);
+    const uint32_t tot   = __shfl(incl, 63, 64);
+    const uint32_t tots  = __shfl(incls, 63, 64);
+    s_incl[wave][lane] = incls;
+    s_off[wave][lane]  = tab.x;
+    s_rel[wave][lane]  = incl - c;
     if (lane == 0) {
         red[wave]  = s;
         wtot[wave] = tot;
@@ -689,29 +712,77 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
 #pragma unroll
     for (uint32_t w = 0; w < kWaves; ++w) base += red[w] + (w < wave ? wtot[w] : 0u);
 
-    {   // clean segment counters for the next iteration
-        const uint32_t per_chunk = 1u << (kChunkShift - A.seg_shift);
+    {   // clean segment counters for the next iteration (a chunk holds whole segments)
+        const uint32_t per_chunk = 1u << (cs - A.seg_shift);
         const uint32_t sg        = chunk * per_chunk + lane;
         if (lane < per_chunk && sg < A.n_segs) A.seg_cnt_next[sg] = 0u;
     }
+    const uint64_t r0 = base + (incl - c);  // output position of this tile's first pair
+
+    // Staging slots for the next iteration follow this iteration's counts: every
+    // tile keeps slots_min slots and gets about two more per gradient it selected
+    // now, as long as the pool's extra part lasts (it covers three times the
+    // ranks the output can hold: tiles just beyond the capacity are the ones
+    // that come within it next time).  Offsets are the running sum of the
+    // sizes, taken from the same prefix that gives the output positions, and
+    // rounded down to 16 pairs = 128 bytes, so two tiles never write into the
+    // same cache line (partial writes to one line from different dies are slow).
+    if (have_tile) {
+        const uint64_t ex  = A.pool_extra;  // multiple of 16
+        const uint64_t a2  = (2u * r0) & ~15ull, b2 = (2u * (r0 + c)) & ~15ull;
+        const uint64_t lo2 = a2 < ex ? a2 : ex;
+        const uint64_t hi2 = b2 < ex ? b2 : ex;
+        A.slot_tab_next[tile] = make_uint2((uint32_t)((uint64_t)tile * A.slots_min + lo2),
+                                           A.slots_min + (uint32_t)(hi2 - lo2));
+    }
+
     if (tot == 0) return;
+    float spill = 0.f;
 
-    const uint64_t r0    = base + (incl - c);  // output position of this tile's first pair
-    float          spill = 0.f;
-
-    if (c && !(word & kFlag)) {
-        const uint2 *slot = A.stage + (size_t)tile * A.slots;
-        for (uint32_t t = 0; t < c; ++t) {
-            const uint2    pr = slot[t];
-            const uint64_t r  = r0 + t;
-            if (r < cap) {
-                A.out_idx[r] = pr.x;
-                A.out_val[r] = __uint_as_float(pr.y);
-            } else {
-                // beyond the output capacity: not sent, so it goes back into the residual
-                const float v = __uint_as_float(pr.y);
-                A.e[pr.x] = v;
-                if (NORM) spill += v * v;
+    // Staged pairs of the whole chunk, copied by all lanes: pair number j of the
+    // chunk (tiles in order, pairs in order inside a tile) belongs to the first
+    // tile whose running staged count exceeds j.
+    {
+        const uint2 *__restrict__    stage   = A.stage;
+        uint32_t *__restrict__       out_idx = A.out_idx;
+        float *__restrict__          out_val = A.out_val;
+        const uint32_t *__restrict__ incl_w  = s_incl[wave];
+        const uint32_t *__restrict__ off_w = s_off[wave];
+        const uint32_t *__restrict__ rel_w = s_rel[wave];
+        // four pairs per lane and trip, so that four independent loads are in flight
+        for (uint32_t j0 = lane; j0 < tots; j0 += 256u) {
+            uint2    pr[4];
+            uint32_t rr[4];
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                const uint32_t j = j0 + q * 64u;
+                pr[q] = make_uint2(0u, 0u);
+                rr[q] = 0;
+                if (j < tots) {
+                    uint32_t lo = 0, hi = 63;
+                    while (lo < hi) {  // first tile with incl_w[tile] > j
+                        const uint32_t mid = (lo + hi) >> 1;
+                        if (incl_w[mid] > j) hi = mid; else lo = mid + 1;
+                    }
+                    const uint32_t within = j - (lo ? incl_w[lo - 1] : 0u);
+                    pr[q] = stage[off_w[lo] + within];
+                    rr[q] = rel_w[lo] + within;
+                }
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < 4; ++q) {
+                if (j0 + q * 64u < tots) {
+                    const uint64_t r = base + rr[q];
+                    if (r < cap) {
+                        out_idx[r] = pr[q].x;
+                        out_val[r] = __uint_as_float(pr[q].y);
+                    } else {
+                        // beyond the output capacity: not sent, so it goes back into the residual
+                        const float v = __uint_as_float(pr[q].y);
+                        A.e[pr[q].x] = v;
+                        if (NORM) spill += v * v;
+                    }
+                }
             }
         }
     }
@@ -722,8 +793,8 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
         flagged &= flagged - 1u;
         const uint32_t lo = __shfl((uint32_t)r0, l, 64), hi = __shfl((uint32_t)(r0 >> 32), l, 64);
         const float    dl = __shfl(delta, l, 64);
-        compact_flagged_tile<NORM, CMP>(A, (chunk << kChunkShift) + l, ((uint64_t)hi << 32) | lo, dl,
-                                        lane, n_g, cap, spill);
+        compact_flagged_tile<NORM, CMP>(A, (chunk << cs) + l, ((uint64_t)hi << 32) | lo, dl, lane,
+                                        n_g, cap, spill);
     }
 
     if (NORM) {
@@ -783,6 +854,16 @@ __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_
         st->overflow = 0; st->moves = 0; st->t = 0;
         st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
         st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
+    }
+}
+
+// Before the first iteration every wave tile has its slots_min staging slots.
+__global__ void k_init_slot_tab(uint2 *tab0, uint2 *tab1, uint32_t n_tiles, uint32_t slots_min)
+{
+    for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_tiles; i += gridDim.x * blockDim.x) {
+        const uint2 v = make_uint2(i * slots_min, slots_min);
+        tab0[i] = v;
+        tab1[i] = v;
     }
 }
 
@@ -847,12 +928,13 @@ int validate_config(const exdyna_config *c, uint64_t *n_b_out, uint64_t *cap_out
     return EXDYNA_OK;
 }
 
-// Staging slots per wave tile: room for four times the expected number of
-// selected gradients in 1024 (density d), a power of two between 8 and 64.
+// Staging slots every wave tile has: room for four times the expected number of
+// selected gradients in 1024 (density d), a power of two between 16 and 64
+// (16 pairs = one 128-byte line).
 uint32_t staging_slots(double density)
 {
     const double want = 4.0 * density * (double)kTile + 4.0;
-    uint32_t s = 8;
+    uint32_t s = 16;
     while (s < 64 && (double)s < want) s <<= 1;
     return s;
 }
@@ -869,14 +951,26 @@ uint32_t segment_shift(double density)
     return sh;
 }
 
+// Wave tiles per compaction wavefront (a "chunk"): about 128 selected gradients
+// per wavefront at the target density, between 4 and 64 tiles.
+uint32_t chunk_shift_for(double density)
+{
+    const double per_tile = (double)kTile * density;
+    uint32_t sh = kChunkShift;
+    while (sh > 2 && (double)(1u << sh) * per_tile > 128.0) --sh;
+    return sh;
+}
+
 Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
 {
     Layout L{};
     const size_t P = c->n_parts;
     L.n_tiles  = (c->n_g + kTile - 1) / kTile;
-    L.n_chunks = (L.n_tiles + (1u << kChunkShift) - 1) >> kChunkShift;
+    L.chunk_shift = chunk_shift_for(c->density);
+    L.n_chunks = (L.n_tiles + (1u << L.chunk_shift) - 1) >> L.chunk_shift;
     L.slots    = staging_slots(c->density);
     L.seg_shift = segment_shift(c->density);
+    if (L.seg_shift > L.chunk_shift) L.seg_shift = L.chunk_shift;  // a chunk holds whole segments
     L.n_segs   = (L.n_tiles + (1u << L.seg_shift) - 1) >> L.seg_shift;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -888,7 +982,16 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
     L.seg_cnt   = take(2 * L.n_segs * sizeof(uint32_t));      // likewise
     L.tile_cnt  = take(L.n_tiles * sizeof(uint32_t));
     L.err_slots = take(2 * kErrSlots * sizeof(double));
-    L.stage     = take(L.n_tiles * L.slots * sizeof(uint2));
+    // staging pool: slots for every tile plus two per pair for three output capacities
+    {
+        uint64_t extra = (6 * cap + 15) & ~15ull;
+        const uint64_t fixed = (uint64_t)L.n_tiles * L.slots;
+        if (fixed + extra > 0xFFFF0000ull) extra = (0xFFFF0000ull - fixed) & ~15ull;  // slot offsets are u32
+        L.pool_extra = (uint32_t)extra;
+        L.pool_pairs = fixed + extra;
+    }
+    L.slot_tab  = take(2 * L.n_tiles * sizeof(uint2));        // {first slot, slots} per tile, two parities
+    L.stage     = take(L.pool_pairs * sizeof(uint2));
     L.out_idx   = take(cap * sizeof(uint32_t));
     L.out_val   = take(cap * sizeof(float));
     L.total     = off;
@@ -916,6 +1019,7 @@ int32_t *slot_pos(exdyna_ctx *c, uint64_t slot) { return slot_part(c, slot) + c-
 uint32_t *blk_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.blk_cnt) + (t & 1) * c->n_b; }
 double *err_slots_of(exdyna_ctx *c, uint64_t t) { return at<double>(c, c->lay.err_slots) + (t & 1) * kErrSlots; }
 
+uint2 *slot_tab_of(exdyna_ctx *c, uint64_t t) { return at<uint2>(c, c->lay.slot_tab) + (t & 1) * c->lay.n_tiles; }
 uint32_t *seg_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.seg_cnt) + (t & 1) * c->lay.n_segs; }
 
 template <int CMP, bool NORM>
@@ -926,6 +1030,7 @@ void launch_stream(exdyna_ctx *c, const float *g, hipStream_t s)
     A.e = c->d_residual;
     A.st = at<DevState>(c, c->lay.state);
     A.stage = at<uint2>(c, c->lay.stage);
+    A.slot_tab = slot_tab_of(c, c->t);
     A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
     A.blk_cnt = blk_cnt_of(c, c->t);
     A.seg_cnt = seg_cnt_of(c, c->t);
@@ -937,7 +1042,6 @@ void launch_stream(exdyna_ctx *c, const float *g, hipStream_t s)
     A.gpb_shift = 32;
     for (uint32_t sh = 0; sh < 32; ++sh)
         if ((1u << sh) == A.gran_per_blk) A.gpb_shift = sh;
-    A.slots = c->lay.slots;
     A.parity = (uint32_t)(c->t & 1);
     const uint32_t grid = (uint32_t)((c->lay.n_tiles + kWavesPerWG - 1) / kWavesPerWG);
     hipLaunchKernelGGL((k_stream<CMP, NORM>), dim3(grid), dim3(kStreamWG), 0, s, A);
@@ -951,6 +1055,8 @@ void launch_finish(exdyna_ctx *c, hipStream_t s)
     A.st = at<DevState>(c, c->lay.state);
     A.e = c->d_residual;
     A.stage = at<uint2>(c, c->lay.stage);
+    A.slot_tab = slot_tab_of(c, t);
+    A.slot_tab_next = slot_tab_of(c, t + 1);
     A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
     A.blk_cnt = blk_cnt_of(c, t);
     A.seg_cnt = seg_cnt_of(c, t);
@@ -970,7 +1076,9 @@ void launch_finish(exdyna_ctx *c, hipStream_t s)
     A.n_chunks = (uint32_t)c->lay.n_chunks;
     A.n_segs = (uint32_t)c->lay.n_segs;
     A.seg_shift = c->lay.seg_shift;
-    A.slots = c->lay.slots;
+    A.chunk_shift = c->lay.chunk_shift;
+    A.slots_min = c->lay.slots;
+    A.pool_extra = c->lay.pool_extra;
     A.parity = (uint32_t)(t & 1);
     const uint32_t per_wg = kFinishWG / 64;
     const uint32_t grid = 1u + (uint32_t)((c->lay.n_chunks + per_wg - 1) / per_wg);
@@ -1069,6 +1177,8 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
                        (size_t)(2 * L.n_segs));
     hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.tile_cnt), 0u,
                        L.n_tiles);
+    hipLaunchKernelGGL(k_init_slot_tab, dim3(256), dim3(256), 0, s, slot_tab_of(c, 0), slot_tab_of(c, 1),
+                       (uint32_t)L.n_tiles, L.slots);
     const uint32_t init_threads = (P + 1 > 2 * kErrSlots ? P + 1 : 2 * kErrSlots);
     hipLaunchKernelGGL(k_init_state, dim3((init_threads + 255) / 256), dim3(256), 0, s,
                        at<DevState>(c, L.state), slot_part(c, 0), slot_pos(c, 0), slot_part(c, 1),
