@@ -6,25 +6,28 @@
 //   k_stream   acc = e + g (Alg. 1 line 7), |acc| cmp delta (Alg. 4 line 2).
 //              Each wavefront owns 1024 contiguous gradients (a "wave tile").
 //              It ranks its selected gradients with ballots, writes their
-//              (index, value) pairs in index order into the tile's slots of a
-//              staging buffer, writes the residual with those entries already
-//              zeroed (Alg. 1 lines 17-18), stores the tile's count, and adds
-//              the count to a per-block and a per-segment counter.  A tile with
-//              more selected gradients than slots is only counted and flagged;
-//              its residual is written unzeroed.
+//              (index, value) pairs in index order into the tile's staging
+//              slots, writes the residual with those entries already zeroed
+//              (Alg. 1 lines 17-18), stores the tile's count, and adds the
+//              count to a per-block and a per-segment counter.  A tile with
+//              more selected gradients than it has slots is only counted and
+//              flagged; its residual is written unzeroed.
 //              Pure streaming: 8 B read + 4 B written per gradient, no
 //              workgroup barrier, no fence.
 //   k_finish   workgroup 0 = control: per-partition counts k_{p,t} and k'
 //              (Alg. 1 lines 10, 13), output segment offsets, threshold
 //              scaling (Alg. 5), adjacent-partition rebalancing (Alg. 3 lines
 //              8-28), Eq. 2/5/6 statistics.
-//              other workgroups = compaction, one wavefront per chunk of 64
-//              wave tiles: prefix of the segment counters in front (summed by
-//              the whole workgroup), a wave scan of the 64 tile counts, then each
-//              lane copies its tile's staged pairs to their final positions
-//              (Alg. 1 lines 9-11).  Flagged tiles are re-read from the
-//              residual and compacted by the whole wave.  Pairs beyond the
-//              output capacity are put back into the residual.
+//              other workgroups = compaction, one wavefront per chunk of up to
+//              64 wave tiles: prefix of the segment counters in front (summed
+//              by the whole workgroup), a wave scan of the tile counts, then
+//              all lanes copy the chunk's staged pairs to their final
+//              positions (Alg. 1 lines 9-11).  Flagged tiles are re-read from
+//              the residual and compacted by the whole wave.  Pairs beyond the
+//              output capacity are put back into the residual.  The same
+//              prefix lays out the next iteration's staging slots: a tile gets
+//              slots in proportion to what it selected this time, so dense
+//              regions and threshold transients stay on the staged path.
 //              Control and compaction read the same finished counters and do
 //              not depend on each other, so they overlap inside one launch.
 //
@@ -372,13 +375,6 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     const uint32_t P    = prm.n_parts;
     const uint32_t n_b  = prm.n_b;
 
-    // all first loads are requested before anything waits on them
-    uint32_t c4[4];
-#pragma unroll
-    for (uint32_t q = 0; q < 4; ++q) {
-        const uint32_t i = tid + q * kFinishWG;
-        c4[q] = i < n_b ? A.blk_cnt[i] : 0u;
-    }
     float    delta  = 0.f;
     uint64_t t_done = 0;
     if (tid == 0) {
@@ -387,6 +383,19 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     }
     const int32_t part = tid < P ? A.cur_part[tid] : 0;
     const int32_t pos  = tid < P ? A.cur_pos[tid] : 0;
+    // k_{p,t} (Sec. 4.2: the workload of a partition).  Each wave takes a
+    // contiguous run of the block counters, 64 at a time; its first slices are
+    // requested before anything waits on memory.
+    const uint32_t per_wave = (n_b + kWaves - 1) / kWaves;
+    const uint32_t beg      = wave * per_wave < n_b ? wave * per_wave : n_b;
+    const uint32_t end      = beg + per_wave < n_b ? beg + per_wave : n_b;
+    constexpr uint32_t kAhead = 4;
+    uint32_t cbuf[kAhead];
+#pragma unroll
+    for (uint32_t q = 0; q < kAhead; ++q) {
+        const uint32_t i = beg + q * 64u + lane;
+        cbuf[q] = i < end ? A.blk_cnt[i] : 0u;
+    }
     if (tid < P) {
         cnt_s[tid] = 0u;
         lpos[tid]  = pos;
@@ -396,45 +405,46 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     if (tid < kErrSlots) A.err_slots_next[tid] = 0.0;
     __syncthreads();
 
-    // k_{p,t} (Sec. 4.2: the workload of a partition): every thread walks a
-    // strided share of the block counters and adds each non-zero one to the
-    // partition that holds the block (largest p with blk_pos[p] <= block).
-    // the loop condition is the same for all lanes of a wave (it tests the
-    // wave's first block), so the cross-lane steps below see every lane
-    for (uint32_t i0 = tid; i0 - lane < n_b; i0 += 4u * kFinishWG) {
-        if (i0 != tid) {
+    if (beg < end) {  // wave-uniform
+        // partition of the run's first block: the largest p with blk_pos[p] <= beg
+        uint32_t plo = 0, phi = P - 1;
+        while (plo < phi) {
+            const uint32_t mid = (plo + phi + 1) >> 1;
+            if ((uint32_t)lpos[mid] <= beg) plo = mid; else phi = mid - 1;
+        }
+        uint32_t pcur       = plo;
+        uint32_t next_start = pcur + 1 < P ? (uint32_t)lpos[pcur + 1] : 0xFFFFFFFFu;
+        uint32_t acc        = 0;  // this lane's share of partition pcur so far
+        for (uint32_t i0 = beg; i0 < end; i0 += kAhead * 64u) {
+            if (i0 != beg) {
 #pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) {
-                const uint32_t i = i0 + q * kFinishWG;
-                c4[q] = i < n_b ? A.blk_cnt[i] : 0u;
+                for (uint32_t q = 0; q < kAhead; ++q) {
+                    const uint32_t i = i0 + q * 64u + lane;
+                    cbuf[q] = i < end ? A.blk_cnt[i] : 0u;
+                }
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < kAhead; ++q) {
+                const uint32_t s0 = i0 + q * 64u;  // first block of this slice
+                const uint32_t i  = s0 + lane;
+                if (i < end) A.blk_cnt_next[i] = 0u;  // clean block counters for the next iteration
+                uint32_t c = cbuf[q];
+                while (next_start < s0 + 64u && next_start < end) {  // the slice reaches the next partition
+                    acc += i < next_start ? c : 0u;
+                    c = i < next_start ? 0u : c;
+#pragma unroll
+                    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+                    if (lane == 0 && acc) atomicAdd(&cnt_s[pcur], acc);
+                    acc = 0;
+                    ++pcur;
+                    next_start = pcur + 1 < P ? (uint32_t)lpos[pcur + 1] : 0xFFFFFFFFu;
+                }
+                acc += c;
             }
         }
 #pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {  // clean block counters for the next iteration
-            const uint32_t i = i0 + q * kFinishWG;
-            if (i < n_b) A.blk_cnt_next[i] = 0u;
-        }
-#pragma unroll
-        for (uint32_t q = 0; q < 4; ++q) {
-            // a wave's 64 blocks are consecutive, so they usually share a partition:
-            // then one lane adds the wave's sum instead of 64 lanes colliding
-            const uint32_t i  = i0 + q * kFinishWG;
-            const uint32_t ib = i < n_b ? i : n_b - 1;
-            uint32_t lo = 0, hi = P - 1;
-            while (lo < hi) {
-                const uint32_t mid = (lo + hi + 1) >> 1;
-                if ((uint32_t)lpos[mid] <= ib) lo = mid; else hi = mid - 1;
-            }
-            const uint32_t p0 = __shfl(lo, 0, 64);
-            if (__ballot(lo != p0) == 0) {
-                uint32_t v = c4[q];
-#pragma unroll
-                for (int d = 32; d >= 1; d >>= 1) v += __shfl_xor(v, d, 64);
-                if (lane == 0 && v) atomicAdd(&cnt_s[p0], v);
-            } else if (c4[q]) {
-                atomicAdd(&cnt_s[lo], c4[q]);
-            }
-        }
+        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+        if (lane == 0 && acc) atomicAdd(&cnt_s[pcur], acc);
     }
     __syncthreads();
 
