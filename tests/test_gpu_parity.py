@@ -103,6 +103,41 @@ def test_everything_selected_overflows_the_capacity():
     x.close()
 
 
+def test_threshold_transient_walks_every_compaction_path():
+    """A threshold 20x too low that recovers at 10 % per step: tiles overflow their staging
+    slots (re-read path), then get slots in proportion to their last count (staged path),
+    staged pairs beyond the output capacity go back into the residual, and finally the
+    sparse steady state returns."""
+    n = 2_000_000 + 333
+    w = synthetic.WORKLOADS[1].scaled(n, 4096, 8)
+    thr = _thr(w) / 20.0
+    log("case threshold transient")
+    x, o = make_pair(n, 4096, 8, 0.002, thr, gamma=0.1, want_err_norm=1)
+    run_trajectory(x, o, _grads(w, 70), tag="transient", check_norm=True, every=1)
+    assert x.get_stats().overflow == 0          # it did recover
+    x.close()
+
+
+def test_clustered_density_far_above_the_slots():
+    """A narrow band whose gradients are all selected, next to bands with none."""
+    n = 700_000
+    rng = np.random.default_rng(21)
+    base = rng.laplace(0, 1e-4, n).astype(np.float32)
+    grads = []
+    for t in range(6):
+        g = base * np.float32(1 + 0.1 * t)
+        g[100_000:160_000] += np.float32(1.0) * (1 if t % 2 == 0 else -1)   # 60 tiles, every gradient
+        g[500_000:500_300] = np.float32(5.0)
+        grads.append(torch.from_numpy(g).to(DEV))
+    log("case clustered density")
+    x, o = make_pair(n, 1024, 16, 0.05, 0.5, max_selected=200_000, want_err_norm=1)
+    run_trajectory(x, o, grads, tag="clustered", check_norm=True)
+    x.close()
+    x, o = make_pair(n, 1024, 16, 0.05, 0.5, max_selected=50_000)        # capacity inside the band
+    run_trajectory(x, o, grads, tag="clustered-cap")
+    x.close()
+
+
 def test_nothing_selected():
     n = 30_000
     w = synthetic.WORKLOADS[1].scaled(n, 256, 4)
