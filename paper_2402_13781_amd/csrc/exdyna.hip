@@ -97,6 +97,7 @@ struct Layout {
         out_idx, out_val, total;
     size_t n_tiles, n_chunks, n_segs, pool_pairs;
     uint32_t chunk_shift; // log2(wave tiles per compaction wavefront)
+    uint32_t one_counter; // blocks coincide with segments: one counter array serves both
     size_t slot_tab;
     uint32_t pool_extra; // staging pairs handed out in proportion to the last counts
     uint32_t slots;      // staging slots every wave tile always has
@@ -160,6 +161,7 @@ struct StreamArgs {
     uint32_t        n_g, n_tiles, gran_per_blk, parity;
     uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
     uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
+    uint32_t        one_counter;  // a block is exactly one segment: blk_cnt doubles as seg_cnt
 };
 
 template <int CMP, bool NORM>
@@ -241,24 +243,29 @@ k_stream(StreamArgs A)
                 word = total | kFlag;  // too many for the slots: compaction re-reads this tile
             }
             if (lane == 0) {
-                // per-block counters; consecutive granules of one block are added together.
-                // One counter per block / chunk keeps same-address atomics rare (they
+                // One counter per block / segment keeps same-address atomics rare (they
                 // serialise at roughly 150 ns each across the dies).
-                uint32_t blk = A.gpb_shift < 32u ? gran0 >> A.gpb_shift : gran0 / A.gran_per_blk;
-                uint32_t in_blk = gran0 - blk * A.gran_per_blk;  // granule's position inside its block
-                uint32_t run = cu[0];
+                if (A.one_counter) {
+                    // a block is exactly one segment: the same counter serves both
+                    atomicAdd(&A.blk_cnt[tile >> A.seg_shift], total);
+                } else {
+                    // per-block counters; consecutive granules of one block are added together
+                    uint32_t blk = A.gpb_shift < 32u ? gran0 >> A.gpb_shift : gran0 / A.gran_per_blk;
+                    uint32_t in_blk = gran0 - blk * A.gran_per_blk;  // granule's position inside its block
+                    uint32_t run = cu[0];
 #pragma unroll
-                for (uint32_t u = 1; u < kTileGran; ++u) {
-                    if (++in_blk == A.gran_per_blk) {  // granule gran0 + u starts the next block
-                        if (run) atomicAdd(&A.blk_cnt[blk], run);
-                        ++blk;
-                        in_blk = 0;
-                        run = 0;
+                    for (uint32_t u = 1; u < kTileGran; ++u) {
+                        if (++in_blk == A.gran_per_blk) {  // granule gran0 + u starts the next block
+                            if (run) atomicAdd(&A.blk_cnt[blk], run);
+                            ++blk;
+                            in_blk = 0;
+                            run = 0;
+                        }
+                        run += cu[u];
                     }
-                    run += cu[u];
+                    if (run) atomicAdd(&A.blk_cnt[blk], run);
+                    atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
                 }
-                if (run) atomicAdd(&A.blk_cnt[blk], run);
-                atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
             }
         }
 
@@ -289,11 +296,11 @@ k_stream(StreamArgs A)
             }
             uint32_t cu, below;
             granule_ranks(f, cu, below);
-            if (cu && lane == 0) atomicAdd(&A.blk_cnt[(gran0 + u) / A.gran_per_blk], cu);
+            if (cu && lane == 0) atomicAdd(&A.blk_cnt[(gran0 + u) / A.gran_per_blk], cu);  // = its segment if one_counter
             total += cu;
         }
         if (lane == 0) {
-            if (total) atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
+            if (total && !A.one_counter) atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
             A.tile_cnt[tile] = total ? (total | kFlag) : 0u;
         }
     }
@@ -981,6 +988,15 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
     L.slots    = staging_slots(c->density);
     L.seg_shift = segment_shift(c->density);
     if (L.seg_shift > L.chunk_shift) L.seg_shift = L.chunk_shift;  // a chunk holds whole segments
+    // When a block is a power-of-two number of tiles that is no coarser than that
+    // segment size (and there are not too many blocks to sum over), let segments
+    // be the blocks: the streaming pass then adds to one counter instead of two.
+    L.one_counter = 0;
+    for (uint32_t sh = 2; sh <= L.seg_shift; ++sh)
+        if (c->block_size == (kTile << sh) && (sh == L.seg_shift || n_b <= 32768)) {
+            L.seg_shift = sh;
+            L.one_counter = 1;
+        }
     L.n_segs   = (L.n_tiles + (1u << L.seg_shift) - 1) >> L.seg_shift;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -1043,8 +1059,9 @@ void launch_stream(exdyna_ctx *c, const float *g, hipStream_t s)
     A.slot_tab = slot_tab_of(c, c->t);
     A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
     A.blk_cnt = blk_cnt_of(c, c->t);
-    A.seg_cnt = seg_cnt_of(c, c->t);
+    A.seg_cnt = c->lay.one_counter ? blk_cnt_of(c, c->t) : seg_cnt_of(c, c->t);
     A.seg_shift = c->lay.seg_shift;
+    A.one_counter = c->lay.one_counter;
     A.err_slots = err_slots_of(c, c->t);
     A.n_g = (uint32_t)c->cfg.n_g;
     A.n_tiles = (uint32_t)c->lay.n_tiles;
@@ -1069,9 +1086,9 @@ void launch_finish(exdyna_ctx *c, hipStream_t s)
     A.slot_tab_next = slot_tab_of(c, t + 1);
     A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
     A.blk_cnt = blk_cnt_of(c, t);
-    A.seg_cnt = seg_cnt_of(c, t);
+    A.seg_cnt = c->lay.one_counter ? blk_cnt_of(c, t) : seg_cnt_of(c, t);
     A.blk_cnt_next = blk_cnt_of(c, t + 1);
-    A.seg_cnt_next = seg_cnt_of(c, t + 1);
+    A.seg_cnt_next = c->lay.one_counter ? blk_cnt_of(c, t + 1) : seg_cnt_of(c, t + 1);
     A.cur_part = slot_part(c, t);
     A.cur_pos = slot_pos(c, t);
     A.nxt_part = slot_part(c, t + 1);
