@@ -27,7 +27,7 @@ ALG_BYTES_PER_PAIR = 8.0       # u32 index + fp32 value per selected gradient
 # summarised in profiles/k_stream_cfg4_hbm_traffic.txt (each counter scaled by what it reads for
 # a plain device copy of one gradient vector: FETCH_SIZE x2.000, WRITE_SIZE x1.000, KiB), keyed
 # by workload index; None for workloads that have not been measured.
-MEASURED_TRAFFIC_BYTES = {4: int((540622.0 * 2.0 + 548717.6) * 1024)}
+MEASURED_TRAFFIC_BYTES = {4: int((542666.0 * 2.0 + 546328.1) * 1024)}
 
 
 def main() -> int:
