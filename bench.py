@@ -1,9 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the ExDyna gradient-selection hot path on one MI355X.
 
-A step is one exdyna_step (streaming accumulate+compare+mask pass, then the
-finishing kernel: control + compaction) over one synthetic gradient vector that is already resident
-in HBM.  Prints ONE JSON line: whole-step throughput in G elements/s, the HBM
+A step is one exdyna_step (the streaming accumulate + compare + stage pass, then
+the finishing kernel: control + compaction) over one synthetic gradient vector
+that is already resident in HBM.  Prints ONE JSON line: whole-step throughput in G elements/s, the HBM
 roofline of the dominant kernel measured with HIP events over the timed steps,
 and the CPU oracle timed on a bounded sample of the same trajectory.
 """

@@ -60,8 +60,10 @@ typedef struct {
     uint32_t cmp_mode;     /* 0: |acc| >= delta (Alg. 4 line 2); 1: |acc| > delta           */
     double   alpha;        /* >= 1, imbalance band of Alg. 3 lines 13/21                    */
     double   beta;         /* > 1, density band of Alg. 5 lines 2/4                         */
-    double   gamma;        /* in (0, 1), threshold step of Alg. 5 lines 3-7                 */
-    uint32_t blk_move;     /* blocks moved per adjustment (Alg. 3 line 12); 0 = static      */
+    double   gamma;        /* in [0, 1), threshold step of Alg. 5 lines 3-7; 0 keeps delta
+                              fixed (the hard-threshold sparsifier of Sec. 3)               */
+    uint32_t blk_move;     /* blocks moved per adjustment (Alg. 3 line 12); 0 = static
+                              partitions (the coarse-grained partitioning of Sec. 4.1)      */
     uint32_t min_blk;      /* >= 1, smallest partition in blocks (Alg. 3 lines 14/22)       */
     uint64_t max_selected; /* output capacity in pairs; 0 = max(ceil(4k), 1024), <= n_g     */
     uint32_t want_err_norm;/* != 0: also compute ||residual||_2 (Eq. 1, one worker)         */

@@ -151,7 +151,7 @@ exo_state *exo_create(uint64_t n_g, uint32_t block_size, uint32_t n_parts,
     if (n_parts == 0 || n_parts > n_b) return NULL;
     if (!(density > 0.0 && density <= 1.0)) return NULL;
     if (!(threshold0 > 0.0f) || isinf(threshold0)) return NULL;
-    if (!(alpha >= 1.0) || !(beta > 1.0) || !(gamma > 0.0 && gamma < 1.0)) return NULL;
+    if (!(alpha >= 1.0) || !(beta > 1.0) || !(gamma >= 0.0 && gamma < 1.0)) return NULL;
     if (min_blk == 0 || cmp_mode > 1) return NULL;
 
     exo_state *s = (exo_state *)calloc(1, sizeof *s);

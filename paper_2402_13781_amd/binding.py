@@ -126,7 +126,7 @@ class ExDyna:
     """One sparsifier context on the current torch device.
 
     Owns (through torch) the residual vector and the workspace the library lays
-    its state, counters, selection mask and output pairs in.
+    its state, counters, staging slots and output pairs in.
     """
 
     def __init__(self, cfg: Config, device="cuda:0", stream=None):

@@ -930,7 +930,7 @@ int validate_config(const exdyna_config *c, uint64_t *n_b_out, uint64_t *cap_out
     if (c->cmp_mode > 1) return EXDYNA_EINVAL;
     if (!(c->alpha >= 1.0) || std::isinf(c->alpha)) return EXDYNA_EINVAL;
     if (!(c->beta > 1.0) || std::isinf(c->beta)) return EXDYNA_EINVAL;
-    if (!(c->gamma > 0.0 && c->gamma < 1.0)) return EXDYNA_EINVAL;
+    if (!(c->gamma >= 0.0 && c->gamma < 1.0)) return EXDYNA_EINVAL;  // 0: fixed threshold
     if (c->min_blk == 0) return EXDYNA_EINVAL;
     if (c->reserved != 0) return EXDYNA_EINVAL;
     if (c->max_selected > c->n_g) return EXDYNA_EINVAL;

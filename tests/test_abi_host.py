@@ -58,7 +58,7 @@ def test_workspace_bytes_accepts_the_five_configurations():
     dict(n_parts=0), dict(n_parts=4097), dict(n_g=1 << 22, n_parts=1025), dict(density=0.0),
     dict(density=1.01), dict(density=float("nan")), dict(threshold0=0.0), dict(threshold0=-1.0),
     dict(threshold0=float("inf")), dict(threshold0=float("nan")), dict(cmp_mode=2),
-    dict(alpha=0.99), dict(alpha=float("nan")), dict(beta=1.0), dict(gamma=0.0), dict(gamma=1.0),
+    dict(alpha=0.99), dict(alpha=float("nan")), dict(beta=1.0), dict(gamma=-0.1), dict(gamma=1.0),
     dict(min_blk=0), dict(reserved=1), dict(max_selected=(1 << 20) + 1),
 ])
 def test_bad_configurations_are_rejected(bad):

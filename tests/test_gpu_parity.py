@@ -154,6 +154,8 @@ def test_nothing_selected():
     dict(alpha=1.5),
     dict(beta=2.0, gamma=0.1),
     dict(cmp_mode=1),
+    dict(gamma=0.0),                          # fixed threshold (hard-threshold ablation)
+    dict(gamma=0.0, blk_move=0),
 ])
 def test_hyper_parameter_variants(kw):
     n = 300_000

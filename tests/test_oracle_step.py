@@ -214,6 +214,25 @@ def test_closed_loop_density_settles_near_target():
     assert abs(tail.mean() - k) / k < 0.2
 
 
+def test_hard_threshold_special_case():
+    """Sec. 3: one worker and a fixed threshold is the hard-threshold sparsifier, i.e. plain
+    `where(|acc| >= delta)` over the whole vector with error feedback."""
+    n = 5000
+    rng = np.random.default_rng(8)
+    o = oracle.Oracle(n, 32, 1, 0.01, 2e-3, gamma=0.0, max_selected=n)
+    e = np.zeros(n, np.float32)
+    for t in range(6):
+        g = _rand_grad(rng, n)
+        o.step(g)
+        acc = (e + g).astype(np.float32)
+        sel = np.flatnonzero(np.abs(acc) >= np.float32(2e-3))
+        assert np.array_equal(o.out_idx(), sel.astype(np.uint32))
+        assert o.threshold == np.float32(2e-3)              # never scaled
+        e = acc.copy()
+        e[sel] = 0
+        assert np.array_equal(o.residual(), e)
+
+
 def test_stats_equations():
     """Eq. 1 (one worker), Eq. 5, Eq. 6 from their printed definitions."""
     n = 2048
@@ -234,7 +253,7 @@ def test_rejects_bad_configurations():
     oracle.Oracle(**ok)
     for bad in (dict(n_g=0), dict(block_size=0), dict(block_size=100), dict(n_parts=0),
                 dict(n_parts=5), dict(density=0.0), dict(density=1.5), dict(threshold0=0.0),
-                dict(threshold0=float("inf")), dict(alpha=0.5), dict(beta=1.0), dict(gamma=0.0),
+                dict(threshold0=float("inf")), dict(alpha=0.5), dict(beta=1.0), dict(gamma=-0.1),
                 dict(gamma=1.0), dict(min_blk=0), dict(cmp_mode=2), dict(n_g=2 ** 32)):
         with pytest.raises(ValueError):
             oracle.Oracle(**{**ok, **bad})
