@@ -152,6 +152,21 @@ int exdyna_get_stats(exdyna_ctx *ctx, exdyna_stats *h_out);
 /* Capacity and block count the context was created with.  Host only. */
 int exdyna_get_dims(const exdyna_ctx *ctx, uint64_t *h_n_blocks, uint64_t *h_capacity);
 
+/* Checkpoint / resume.  Besides the residual (caller-owned device memory: save
+ * and restore those n_g floats yourself) the loop of Alg. 1 carries the iteration
+ * number t, the threshold delta_t and the partition topology; the partial-k
+ * vector needs no saving because Alg. 3 has already been applied for the next
+ * iteration.  exdyna_state_bytes gives the size of that state for this context,
+ * exdyna_get_state synchronises and writes it to host memory, exdyna_set_state
+ * loads it into a context created with the same n_g, block_size and n_parts
+ * (EXDYNA_EINVAL otherwise, or if the topology does not tile the blocks) and
+ * synchronises hip_stream.  After set_state plus restoring the residual, further
+ * steps give bit-identical results to the run that was saved.  Profiling, if on,
+ * is turned off by set_state. */
+int exdyna_state_bytes(const exdyna_ctx *ctx, size_t *h_bytes);
+int exdyna_get_state(exdyna_ctx *ctx, void *h_state, size_t bytes);
+int exdyna_set_state(exdyna_ctx *ctx, const void *h_state, size_t bytes, void *hip_stream);
+
 /* Per-kernel timing for benchmarks.  exdyna_set_profiling(ctx, n_slots) with
  * n_slots > 0 makes every later exdyna_step record HIP events around its two
  * kernels on the step's stream, into a ring of n_slots (<= 65536) event sets;

@@ -21,7 +21,8 @@ SYMBOLS = (
     "exdyna_default_config", "exdyna_block_size_from_nb", "exdyna_workspace_bytes", "exdyna_init",
     "exdyna_step", "exdyna_get_selected", "exdyna_get_partitions", "exdyna_get_block_counts",
     "exdyna_get_part_counts", "exdyna_get_stats", "exdyna_get_dims", "exdyna_set_profiling",
-    "exdyna_get_kernel_ms", "exdyna_strerror", "exdyna_last_hip_error", "exdyna_destroy",
+    "exdyna_get_kernel_ms", "exdyna_state_bytes", "exdyna_get_state", "exdyna_set_state",
+    "exdyna_strerror", "exdyna_last_hip_error", "exdyna_destroy",
 )
 
 
@@ -77,6 +78,9 @@ def load() -> C.CDLL:
     L.exdyna_get_dims.argtypes = [vp, P(u64), P(u64)]
     L.exdyna_set_profiling.argtypes = [vp, u32]
     L.exdyna_get_kernel_ms.argtypes = [vp, u64, P(C.c_float)]
+    L.exdyna_state_bytes.argtypes = [vp, P(C.c_size_t)]
+    L.exdyna_get_state.argtypes = [vp, vp, C.c_size_t]
+    L.exdyna_set_state.argtypes = [vp, vp, C.c_size_t, vp]
     L.exdyna_strerror.argtypes = [C.c_int]
     L.exdyna_strerror.restype = C.c_char_p
     L.exdyna_last_hip_error.argtypes = [vp]
@@ -234,6 +238,20 @@ class ExDyna:
         st = Stats()
         self._check(self._L.exdyna_get_stats(self._h, C.byref(st)), "exdyna_get_stats")
         return st
+
+    def get_state(self) -> bytes:
+        """exdyna_get_state: the saved state as bytes (the residual is `self.residual`)."""
+        n = C.c_size_t()
+        self._check(self._L.exdyna_state_bytes(self._h, C.byref(n)), "exdyna_state_bytes")
+        buf = (C.c_char * n.value)()
+        self._check(self._L.exdyna_get_state(self._h, buf, n.value), "exdyna_get_state")
+        return bytes(buf)
+
+    def set_state(self, state: bytes, stream=None):
+        """exdyna_set_state: resume from `state`; restore `self.residual` separately."""
+        buf = (C.c_char * len(state)).from_buffer_copy(state)
+        self._check(self._L.exdyna_set_state(self._h, buf, len(state), self._stream_ptr(stream)),
+                    "exdyna_set_state")
 
     def set_profiling(self, n_slots: int):
         self._check(self._L.exdyna_set_profiling(self._h, int(n_slots)), "exdyna_set_profiling")

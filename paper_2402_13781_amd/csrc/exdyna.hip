@@ -884,6 +884,18 @@ __global__ void k_init_slot_tab(uint2 *tab0, uint2 *tab1, uint32_t n_tiles, uint
     }
 }
 
+// Resume: iteration counter and threshold as saved; statistics of "the last step" are cleared.
+__global__ void k_restore_state(DevState *st, uint64_t t, float delta)
+{
+    st->delta[0] = delta;
+    st->delta[1] = delta;
+    st->delta_used = delta;
+    st->delta_next = delta;
+    st->overflow = 0; st->moves = 0; st->t = t;
+    st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
+    st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
+}
+
 __global__ void k_norm_finalize(DevState *st, const double *err_slots)
 {
     __shared__ double s[kErrSlots];
@@ -1362,6 +1374,99 @@ int exdyna_get_dims(const exdyna_ctx *c, uint64_t *h_n_blocks, uint64_t *h_capac
 }
 
 namespace {
+void drop_events_fwd(exdyna_ctx *c);
+// Saved state (Alg. 1's loop-carried variables other than the residual, which the
+// caller owns): a small header, then blk_part[P] and blk_pos[P] of the topology
+// the next iteration will select with.
+struct StateHeader {
+    uint64_t magic, n_g, t;
+    uint32_t block_size, n_parts;
+    float    delta;
+    uint32_t pad;
+};
+constexpr uint64_t kStateMagic = 0x4578447953743031ull;
+}  // namespace
+
+int exdyna_state_bytes(const exdyna_ctx *c, size_t *h_bytes)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!h_bytes) return EXDYNA_ENULL;
+    *h_bytes = sizeof(StateHeader) + 2 * (size_t)c->cfg.n_parts * sizeof(int32_t);
+    return EXDYNA_OK;
+}
+
+int exdyna_get_state(exdyna_ctx *c, void *h_state, size_t bytes)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!h_state) return EXDYNA_ENULL;
+    const size_t P = c->cfg.n_parts;
+    if (bytes < sizeof(StateHeader) + 2 * P * sizeof(int32_t)) return EXDYNA_ENOMEM;
+    DevState st;
+    char *out = static_cast<char *>(h_state);
+    HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st, hipMemcpyDeviceToHost,
+                              c->stream));
+    HIP_TRY(c, hipMemcpyAsync(out + sizeof(StateHeader), slot_part(c, c->t),
+                              2 * P * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
+    HIP_TRY(c, hipStreamSynchronize(c->stream));
+    StateHeader h{};
+    h.magic = kStateMagic;
+    h.n_g = c->cfg.n_g;
+    h.t = st.t;
+    h.block_size = c->cfg.block_size;
+    h.n_parts = c->cfg.n_parts;
+    h.delta = st.delta_next;
+    memcpy(out, &h, sizeof h);
+    return EXDYNA_OK;
+}
+
+int exdyna_set_state(exdyna_ctx *c, const void *h_state, size_t bytes, void *hip_stream)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!h_state) return EXDYNA_ENULL;
+    const size_t P = c->cfg.n_parts;
+    if (bytes < sizeof(StateHeader) + 2 * P * sizeof(int32_t)) return EXDYNA_EINVAL;
+    StateHeader h;
+    memcpy(&h, h_state, sizeof h);
+    if (h.magic != kStateMagic || h.n_g != c->cfg.n_g || h.block_size != c->cfg.block_size ||
+        h.n_parts != c->cfg.n_parts || !(h.delta > 0.0f) || std::isinf(h.delta))
+        return EXDYNA_EINVAL;
+    // the topology must tile the blocks: positive sizes, contiguous, covering n_b
+    const int32_t *part = reinterpret_cast<const int32_t *>(static_cast<const char *>(h_state) + sizeof h);
+    const int32_t *pos = part + P;
+    int64_t next = 0;
+    for (size_t p = 0; p < P; ++p) {
+        if (part[p] < 1 || pos[p] != next) return EXDYNA_EINVAL;
+        next += part[p];
+    }
+    if ((uint64_t)next != c->n_b) return EXDYNA_EINVAL;
+
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    c->stream = s;
+    if (c->prof_slots) {
+        HIP_TRY(c, hipStreamSynchronize(s));
+        drop_events_fwd(c);
+    }
+    c->t = h.t;
+    const Layout &L = c->lay;
+    HIP_TRY(c, hipMemcpyAsync(slot_part(c, c->t), part, 2 * P * sizeof(int32_t),
+                              hipMemcpyHostToDevice, s));
+    HIP_TRY(c, hipMemcpyAsync(slot_part(c, c->t + 1), part, 2 * P * sizeof(int32_t),
+                              hipMemcpyHostToDevice, s));
+    hipLaunchKernelGGL(k_restore_state, dim3(1), dim3(1), 0, s, at<DevState>(c, L.state), h.t, h.delta);
+    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
+                       (size_t)(2 * c->n_b));
+    hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.seg_cnt), 0u,
+                       (size_t)(2 * L.n_segs));
+    hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.err_slots), 0u,
+                       (size_t)(2 * kErrSlots * 2));
+    hipLaunchKernelGGL(k_init_slot_tab, dim3(256), dim3(256), 0, s, slot_tab_of(c, 0), slot_tab_of(c, 1),
+                       (uint32_t)L.n_tiles, L.slots);
+    HIP_TRY(c, hipGetLastError());
+    HIP_TRY(c, hipStreamSynchronize(s));  // h_state may be freed by the caller on return
+    return EXDYNA_OK;
+}
+
+namespace {
 void drop_events(exdyna_ctx *c)
 {
     if (c->ev) {
@@ -1371,6 +1476,10 @@ void drop_events(exdyna_ctx *c)
     c->ev = nullptr;
     c->prof_slots = 0;
 }
+}  // namespace
+
+namespace {
+void drop_events_fwd(exdyna_ctx *c) { drop_events(c); }
 }  // namespace
 
 int exdyna_set_profiling(exdyna_ctx *c, uint32_t n_slots)

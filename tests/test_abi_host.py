@@ -89,6 +89,9 @@ def test_init_and_step_argument_errors_without_a_gpu():
     assert L.exdyna_step(None, fake_res, None) == binding.EXDYNA_ENULL
     assert L.exdyna_get_stats(None, None) == binding.EXDYNA_ENULL
     assert L.exdyna_destroy(None) == binding.EXDYNA_ENULL
+    assert L.exdyna_state_bytes(None, None) == binding.EXDYNA_ENULL
+    assert L.exdyna_get_state(None, None, 0) == binding.EXDYNA_ENULL
+    assert L.exdyna_set_state(None, None, 0, None) == binding.EXDYNA_ENULL
     # a block of host memory that is not a context
     junk = (C.c_uint64 * 256)()
     assert L.exdyna_step(C.cast(junk, C.c_void_p), fake_res, None) == binding.EXDYNA_ESTATE
