@@ -45,6 +45,9 @@ enum {
     EXDYNA_EHIP    = -6  /* a HIP runtime call failed (see exdyna_last_hip_error) */
 };
 
+/* gradient element types of exdyna_step_scaled */
+enum { EXDYNA_F32 = 0, EXDYNA_BF16 = 1, EXDYNA_F16 = 2 };
+
 typedef struct exdyna_ctx exdyna_ctx; /* opaque, host memory, library-owned */
 
 /* Problem statement of Alg. 1 / Alg. 3 / Alg. 5.  The paper names alpha, beta,
@@ -122,6 +125,17 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
  * number of times; each replay advances the device state by that many
  * iterations and the getters keep reporting the last iteration. */
 int exdyna_step(exdyna_ctx *ctx, const float *d_grad, void *hip_stream);
+
+/* The same iteration with the learning rate fused in and a choice of gradient
+ * element type (Alg. 1 line 7 as printed: acc = e + eta * G).  d_grad: n_g
+ * elements of grad_dtype (EXDYNA_F32 / EXDYNA_BF16 / EXDYNA_F16), 16-byte
+ * aligned.  Each gradient is widened to fp32 exactly, multiplied by eta in fp32
+ * (rounded), then added to the residual in fp32 (rounded): fl(e + fl(eta * g)),
+ * never a fused multiply-add.  With 16-bit gradients the streaming pass moves
+ * 10 instead of 12 bytes per gradient.  eta must be finite.  Steps of both
+ * kinds can be mixed freely on one context. */
+int exdyna_step_scaled(exdyna_ctx *ctx, const void *d_grad, int grad_dtype, float eta,
+                       void *hip_stream);
 
 /* Results of the last step.  *d_idx / *d_val: device arrays of k_emitted
  * ascending gradient indices and the accumulated values at them (Alg. 1 lines

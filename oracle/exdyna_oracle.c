@@ -204,10 +204,11 @@ void exo_destroy(exo_state *s)
     free(s);
 }
 
+static void step_after_accumulate(exo_state *s);
+
 void exo_step(exo_state *s, const float *g)
 {
     const uint64_t n_g = s->n_g;
-    const uint32_t n = s->n;
     float *acc = s->e;
 
     /* Alg. 1 line 7: acc = e + g (g carries the learning rate already). */
@@ -215,6 +216,60 @@ void exo_step(exo_state *s, const float *g)
         float a = acc[i] + g[i];
         acc[i] = a;
     }
+    step_after_accumulate(s);
+}
+
+/* bf16 is the upper half of an fp32. */
+static float bf16_to_float(uint16_t h)
+{
+    uint32_t bits = (uint32_t)h << 16;
+    float v;
+    memcpy(&v, &bits, sizeof v);
+    return v;
+}
+
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits. */
+static float half_to_float(uint16_t h)
+{
+    uint32_t sign = (h >> 15) & 1u, ex = (h >> 10) & 31u, man = h & 1023u;
+    float v;
+    if (ex == 0)
+        v = ldexpf((float)man, -24);                       /* subnormal or zero */
+    else if (ex == 31)
+        v = man ? NAN : INFINITY;
+    else
+        v = ldexpf((float)(man | 1024u), (int)ex - 25);    /* 1.f x 2^(ex-15) */
+    return sign ? -v : v;
+}
+
+/* Alg. 1 line 7 as printed: acc = e + eta * G, with G in fp32 (dtype 0), bf16
+ * (1) or fp16 (2).  The gradient is widened exactly, the product is rounded
+ * to fp32, then the sum is rounded to fp32 (no fused multiply-add: the file
+ * is built with -ffp-contract=off). */
+void exo_step_scaled(exo_state *s, const void *g, int dtype, float eta)
+{
+    const uint64_t n_g = s->n_g;
+    float *acc = s->e;
+    for (uint64_t i = 0; i < n_g; ++i) {
+        float gi;
+        if (dtype == 0)
+            gi = ((const float *)g)[i];
+        else if (dtype == 1)
+            gi = bf16_to_float(((const uint16_t *)g)[i]);
+        else
+            gi = half_to_float(((const uint16_t *)g)[i]);
+        float p = eta * gi;
+        float a = acc[i] + p;
+        acc[i] = a;
+    }
+    step_after_accumulate(s);
+}
+
+static void step_after_accumulate(exo_state *s)
+{
+    const uint64_t n_g = s->n_g;
+    const uint32_t n = s->n;
+    float *acc = s->e;
 
     /* Alg. 1 line 8: Allocate adjusts the topology from last iteration's
      * per-partition counts; selection below uses the adjusted topology. */

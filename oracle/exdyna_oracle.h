@@ -76,6 +76,10 @@ void exo_destroy(exo_state *s);
  * carry the residual. */
 void exo_step(exo_state *s, const float *g);
 
+/* The same iteration with Alg. 1 line 7 as printed, acc = e + eta * G, for
+ * gradients stored as fp32 (dtype 0), bf16 (1) or fp16 (2): fl(e + fl(eta * g)). */
+void exo_step_scaled(exo_state *s, const void *g, int dtype, float eta);
+
 /* Accessors: pointers stay valid until the next exo_step / exo_destroy. */
 uint64_t        exo_n_blocks(const exo_state *s);
 uint64_t        exo_capacity(const exo_state *s);

@@ -61,6 +61,8 @@ def _load():
     L.exo_destroy.argtypes = [vp]
     L.exo_step.restype = None
     L.exo_step.argtypes = [vp, P(f32)]
+    L.exo_step_scaled.restype = None
+    L.exo_step_scaled.argtypes = [vp, vp, C.c_int, f32]
     for name, rt in [("exo_n_blocks", u64), ("exo_capacity", u64), ("exo_iteration", u64),
                      ("exo_threshold", f32), ("exo_threshold_used", f32),
                      ("exo_residual", P(f32)), ("exo_out_idx", P(u32)), ("exo_out_val", P(f32)),
@@ -153,6 +155,12 @@ class Oracle:
     def step(self, g: np.ndarray):
         assert g.dtype == np.float32 and g.flags.c_contiguous and g.size == self.n_g
         self._L.exo_step(self._h, _ptr(g, C.c_float))
+
+    def step_scaled(self, g: np.ndarray, dtype: int, eta: float):
+        """g: float32 array (dtype 0) or uint16 array of bf16 (1) / fp16 (2) bit patterns."""
+        assert g.flags.c_contiguous and g.size == self.n_g
+        assert g.dtype == (np.float32 if dtype == 0 else np.uint16)
+        self._L.exo_step_scaled(self._h, g.ctypes.data_as(C.c_void_p), dtype, np.float32(eta))
 
     # --- views (copied so they survive the next step) ---
     def _arr(self, p, n, dtype):

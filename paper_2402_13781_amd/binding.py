@@ -13,13 +13,14 @@ from typing import Optional
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libexdyna.so")
 
+EXDYNA_F32, EXDYNA_BF16, EXDYNA_F16 = 0, 1, 2
 EXDYNA_OK, EXDYNA_EINVAL, EXDYNA_ENULL, EXDYNA_EALIGN, EXDYNA_ESTATE, EXDYNA_ENOMEM, EXDYNA_EHIP = (
     0, -1, -2, -3, -4, -5, -6)
 
 # every symbol include/exdyna.h declares
 SYMBOLS = (
     "exdyna_default_config", "exdyna_block_size_from_nb", "exdyna_workspace_bytes", "exdyna_init",
-    "exdyna_step", "exdyna_get_selected", "exdyna_get_partitions", "exdyna_get_block_counts",
+    "exdyna_step", "exdyna_step_scaled", "exdyna_get_selected", "exdyna_get_partitions", "exdyna_get_block_counts",
     "exdyna_get_part_counts", "exdyna_get_stats", "exdyna_get_dims", "exdyna_set_profiling",
     "exdyna_get_kernel_ms", "exdyna_state_bytes", "exdyna_get_state", "exdyna_set_state",
     "exdyna_strerror", "exdyna_last_hip_error", "exdyna_destroy",
@@ -70,6 +71,7 @@ def load() -> C.CDLL:
     L.exdyna_workspace_bytes.argtypes = [P(Config), P(C.c_size_t)]
     L.exdyna_init.argtypes = [P(vp), P(Config), vp, vp, C.c_size_t, vp]
     L.exdyna_step.argtypes = [vp, vp, vp]
+    L.exdyna_step_scaled.argtypes = [vp, vp, C.c_int, C.c_float, vp]
     L.exdyna_get_selected.argtypes = [vp, P(vp), P(vp), P(vp), P(u64), P(u64)]
     L.exdyna_get_partitions.argtypes = [vp, C.c_int, P(u32), P(u32), P(u64), P(u64), P(u32)]
     L.exdyna_get_block_counts.argtypes = [vp, P(u32)]
@@ -194,6 +196,16 @@ class ExDyna:
             raise ValueError("grad must be a contiguous fp32 tensor of n_g elements on the context's device")
         self._check(self._L.exdyna_step(self._h, C.c_void_p(grad.data_ptr()), self._stream_ptr(stream)),
                     "exdyna_step")
+
+    def step_scaled(self, grad, eta: float, stream=None):
+        """exdyna_step_scaled: acc = e + eta * grad with fp32, bf16 or fp16 gradients."""
+        torch = self._torch
+        dt = {torch.float32: EXDYNA_F32, torch.bfloat16: EXDYNA_BF16, torch.float16: EXDYNA_F16}.get(grad.dtype)
+        if dt is None or grad.device != self.device or not grad.is_contiguous() \
+                or grad.numel() != self.cfg.n_g:
+            raise ValueError("grad must be a contiguous fp32/bf16/fp16 tensor of n_g elements on the context's device")
+        self._check(self._L.exdyna_step_scaled(self._h, C.c_void_p(grad.data_ptr()), dt, float(eta),
+                                               self._stream_ptr(stream)), "exdyna_step_scaled")
 
     def get_selected(self):
         """exdyna_get_selected: (idx[int32 view of u32], val[fp32], part_off[int64], k_actual, k_emitted)."""

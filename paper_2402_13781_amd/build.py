@@ -21,7 +21,7 @@ def hipcc() -> str:
 
 def build(extra_defines=(), out: str = LIB, verbose: bool = False) -> str:
     cmd = [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
-           "-fno-fast-math", "-Wall", "-Wno-unused-command-line-argument",
+           "-fno-fast-math", "-ffp-contract=off", "-Wall", "-Wno-unused-command-line-argument",
            # keep the compiler from forming packed-fp32 instructions
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
            "-I", INC, "-o", out, SRC]

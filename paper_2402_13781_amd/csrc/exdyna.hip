@@ -144,12 +144,62 @@ __device__ __forceinline__ void granule_ranks(uint32_t nib, uint32_t &count, uin
     below = lanes_below(b0) + lanes_below(b1) + lanes_below(b2) + lanes_below(b3);
 }
 
+// Gradient element types of exdyna_step_scaled.  16-bit inputs are widened to
+// fp32 exactly (bf16: the bits are the upper half of an fp32; fp16: hardware
+// conversion), then the accumulate is fl(e + fl(eta * g)): one fp32 multiply,
+// one fp32 add, never contracted into an FMA (the file is built with
+// -ffp-contract=off and the pragma below repeats it).
+typedef unsigned short u16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+
+template <int GT>
+__device__ __forceinline__ f32x4 load_grad4(const void *g, size_t elem)
+{
+    if (GT == EXDYNA_F32) {
+        return __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(static_cast<const float *>(g) + elem));
+    } else if (GT == EXDYNA_BF16) {
+        const u16x4 r = __builtin_nontemporal_load(
+            reinterpret_cast<const u16x4 *>(static_cast<const unsigned short *>(g) + elem));
+        f32x4 v;
+        v.x = __uint_as_float((uint32_t)r.x << 16);
+        v.y = __uint_as_float((uint32_t)r.y << 16);
+        v.z = __uint_as_float((uint32_t)r.z << 16);
+        v.w = __uint_as_float((uint32_t)r.w << 16);
+        return v;
+    } else {
+        const f16x4 r = __builtin_nontemporal_load(
+            reinterpret_cast<const f16x4 *>(static_cast<const _Float16 *>(g) + elem));
+        return __builtin_convertvector(r, f32x4);
+    }
+}
+
+template <int GT>
+__device__ __forceinline__ float load_grad1(const void *g, uint64_t elem)
+{
+    if (GT == EXDYNA_F32) return static_cast<const float *>(g)[elem];
+    if (GT == EXDYNA_BF16)
+        return __uint_as_float((uint32_t) static_cast<const unsigned short *>(g)[elem] << 16);
+    return (float)static_cast<const _Float16 *>(g)[elem];
+}
+
+template <bool SCALE>
+__device__ __forceinline__ float accumulate(float e, float g, float eta)
+{
+#pragma clang fp contract(off)
+    if (SCALE) {
+        const float p = eta * g;  // rounded to fp32 before the add
+        return e + p;
+    }
+    return e + g;
+}
+
 // ---------------------------------------------------------------------------
 // k_stream: error-feedback accumulate + compare + rank + stage + zeroed
 // write-back.  Workgroup w streams gradients [4096 w, 4096 (w+1)); its wave v
 // owns wave tile 4w + v = four consecutive granules.
 struct StreamArgs {
-    const float    *g;
+    const void     *g;          // n_g gradients of the kernel's element type
+    float           eta;        // learning rate (used by the scaled variants only)
     float          *e;
     const DevState *st;
     uint2          *stage;      // staging pool of (index, value bits) pairs
@@ -164,7 +214,7 @@ struct StreamArgs {
     uint32_t        one_counter;  // a block is exactly one segment: blk_cnt doubles as seg_cnt
 };
 
-template <int CMP, bool NORM>
+template <int CMP, bool NORM, int GT, bool SCALE>
 __global__ void __launch_bounds__(kStreamWG)
 k_stream(StreamArgs A)
 {
@@ -188,15 +238,15 @@ k_stream(StreamArgs A)
 #pragma unroll
             for (uint32_t u = 0; u < kTileGran; ++u) {
                 const size_t off = ((size_t)(gran0 + u) << 8) + lane * 4u;
-                gv[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(A.g + off));
+                gv[u] = load_grad4<GT>(A.g, off);
                 ev[u] = __builtin_nontemporal_load(reinterpret_cast<const f32x4 *>(A.e + off));
             }
 #pragma unroll
             for (uint32_t u = 0; u < kTileGran; ++u) {
-                a[u].x = ev[u].x + gv[u].x;
-                a[u].y = ev[u].y + gv[u].y;
-                a[u].z = ev[u].z + gv[u].z;
-                a[u].w = ev[u].w + gv[u].w;
+                a[u].x = accumulate<SCALE>(ev[u].x, gv[u].x, A.eta);
+                a[u].y = accumulate<SCALE>(ev[u].y, gv[u].y, A.eta);
+                a[u].z = accumulate<SCALE>(ev[u].z, gv[u].z, A.eta);
+                a[u].w = accumulate<SCALE>(ev[u].w, gv[u].w, A.eta);
                 nib[u] = sel<CMP>(a[u].x, delta) | (sel<CMP>(a[u].y, delta) << 1) |
                          (sel<CMP>(a[u].z, delta) << 2) | (sel<CMP>(a[u].w, delta) << 3);
             }
@@ -287,7 +337,7 @@ k_stream(StreamArgs A)
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) {
                 if (base + q < A.n_g) {
-                    const float v = A.e[base + q] + A.g[base + q];
+                    const float v = accumulate<SCALE>(A.e[base + q], load_grad1<GT>(A.g, base + q), A.eta);
                     A.e[base + q] = v;
                     const uint32_t hit = sel<CMP>(v, delta);
                     f |= hit << q;
@@ -1060,11 +1110,12 @@ double *err_slots_of(exdyna_ctx *c, uint64_t t) { return at<double>(c, c->lay.er
 uint2 *slot_tab_of(exdyna_ctx *c, uint64_t t) { return at<uint2>(c, c->lay.slot_tab) + (t & 1) * c->lay.n_tiles; }
 uint32_t *seg_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.seg_cnt) + (t & 1) * c->lay.n_segs; }
 
-template <int CMP, bool NORM>
-void launch_stream(exdyna_ctx *c, const float *g, hipStream_t s)
+template <int CMP, bool NORM, int GT, bool SCALE>
+void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
 {
     StreamArgs A;
     A.g = g;
+    A.eta = eta;
     A.e = c->d_residual;
     A.st = at<DevState>(c, c->lay.state);
     A.stage = at<uint2>(c, c->lay.stage);
@@ -1083,7 +1134,7 @@ void launch_stream(exdyna_ctx *c, const float *g, hipStream_t s)
         if ((1u << sh) == A.gran_per_blk) A.gpb_shift = sh;
     A.parity = (uint32_t)(c->t & 1);
     const uint32_t grid = (uint32_t)((c->lay.n_tiles + kWavesPerWG - 1) / kWavesPerWG);
-    hipLaunchKernelGGL((k_stream<CMP, NORM>), dim3(grid), dim3(kStreamWG), 0, s, A);
+    hipLaunchKernelGGL((k_stream<CMP, NORM, GT, SCALE>), dim3(grid), dim3(kStreamWG), 0, s, A);
 }
 
 template <bool NORM, int CMP>
@@ -1122,6 +1173,52 @@ void launch_finish(exdyna_ctx *c, hipStream_t s)
     const uint32_t per_wg = kFinishWG / 64;
     const uint32_t grid = 1u + (uint32_t)((c->lay.n_chunks + per_wg - 1) / per_wg);
     hipLaunchKernelGGL((k_finish<NORM, CMP>), dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
+}
+
+template <int GT, bool SCALE>
+void dispatch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
+{
+    const bool norm = c->cfg.want_err_norm != 0;
+    if (c->cfg.cmp_mode == 0) {
+        if (norm) launch_stream<0, true, GT, SCALE>(c, g, eta, s); else launch_stream<0, false, GT, SCALE>(c, g, eta, s);
+    } else {
+        if (norm) launch_stream<1, true, GT, SCALE>(c, g, eta, s); else launch_stream<1, false, GT, SCALE>(c, g, eta, s);
+    }
+}
+
+// grad_dtype < 0: the unscaled fp32 path of exdyna_step (one add per gradient)
+int step_impl(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, void *hip_stream)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!d_grad) return EXDYNA_ENULL;
+    if (grad_dtype > EXDYNA_F16) return EXDYNA_EINVAL;
+    if (grad_dtype >= 0 && !std::isfinite(eta)) return EXDYNA_EINVAL;
+    if ((uintptr_t)d_grad % 16 != 0) return EXDYNA_EALIGN;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    c->stream = s;
+    const bool norm = c->cfg.want_err_norm != 0;
+    const bool prof = c->prof_slots != 0;
+    hipEvent_t *ev = prof ? c->ev + 3 * (c->t % c->prof_slots) : nullptr;
+
+    if (prof) HIP_TRY(c, hipEventRecord(ev[0], s));
+    switch (grad_dtype) {
+    case EXDYNA_F32: dispatch_stream<EXDYNA_F32, true>(c, d_grad, eta, s); break;
+    case EXDYNA_BF16: dispatch_stream<EXDYNA_BF16, true>(c, d_grad, eta, s); break;
+    case EXDYNA_F16: dispatch_stream<EXDYNA_F16, true>(c, d_grad, eta, s); break;
+    default: dispatch_stream<EXDYNA_F32, false>(c, d_grad, 1.0f, s); break;
+    }
+    if (prof) HIP_TRY(c, hipEventRecord(ev[1], s));
+
+    const uint64_t t = c->t;
+    if (c->cfg.cmp_mode == 0) {
+        if (norm) launch_finish<true, 0>(c, s); else launch_finish<false, 0>(c, s);
+    } else {
+        if (norm) launch_finish<true, 1>(c, s); else launch_finish<false, 1>(c, s);
+    }
+    if (prof) HIP_TRY(c, hipEventRecord(ev[2], s));
+    HIP_TRY(c, hipGetLastError());
+    c->t = t + 1;
+    return EXDYNA_OK;
 }
 
 }  // namespace
@@ -1235,33 +1332,13 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
 
 int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
 {
-    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
-    if (!d_grad) return EXDYNA_ENULL;
-    if ((uintptr_t)d_grad % 16 != 0) return EXDYNA_EALIGN;
-    hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    c->stream = s;
-    const bool norm = c->cfg.want_err_norm != 0;
-    const bool prof = c->prof_slots != 0;
-    hipEvent_t *ev = prof ? c->ev + 3 * (c->t % c->prof_slots) : nullptr;
+    return step_impl(c, d_grad, -1, 1.0f, hip_stream);
+}
 
-    if (prof) HIP_TRY(c, hipEventRecord(ev[0], s));
-    if (c->cfg.cmp_mode == 0) {
-        if (norm) launch_stream<0, true>(c, d_grad, s); else launch_stream<0, false>(c, d_grad, s);
-    } else {
-        if (norm) launch_stream<1, true>(c, d_grad, s); else launch_stream<1, false>(c, d_grad, s);
-    }
-    if (prof) HIP_TRY(c, hipEventRecord(ev[1], s));
-
-    const uint64_t t = c->t;
-    if (c->cfg.cmp_mode == 0) {
-        if (norm) launch_finish<true, 0>(c, s); else launch_finish<false, 0>(c, s);
-    } else {
-        if (norm) launch_finish<true, 1>(c, s); else launch_finish<false, 1>(c, s);
-    }
-    if (prof) HIP_TRY(c, hipEventRecord(ev[2], s));
-    HIP_TRY(c, hipGetLastError());
-    c->t = t + 1;
-    return EXDYNA_OK;
+int exdyna_step_scaled(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, void *hip_stream)
+{
+    if (grad_dtype < EXDYNA_F32) return c ? EXDYNA_EINVAL : EXDYNA_ENULL;
+    return step_impl(c, d_grad, grad_dtype, eta, hip_stream);
 }
 
 int exdyna_get_selected(exdyna_ctx *c, const uint32_t **d_idx, const float **d_val,

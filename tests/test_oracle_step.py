@@ -257,3 +257,65 @@ def test_rejects_bad_configurations():
                 dict(gamma=1.0), dict(min_blk=0), dict(cmp_mode=2), dict(n_g=2 ** 32)):
         with pytest.raises(ValueError):
             oracle.Oracle(**{**ok, **bad})
+
+
+def _bf16_bits(x32):
+    return (torch.from_numpy(x32).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+
+
+@pytest.mark.parametrize("dtype", [0, 1, 2])
+def test_scaled_step_rounds_product_then_sum(dtype):
+    """Alg. 1 line 7 as printed, acc = e + eta*G: the gradient is widened exactly (checked
+    against torch's bf16 and numpy's fp16 conversions), the product is rounded to fp32, then
+    the sum -- numpy's separate fp32 multiply and add, never a fused multiply-add."""
+    n = 3000
+    rng = np.random.default_rng(40 + dtype)
+    eta = np.float32(0.0371)
+    o = oracle.Oracle(n, 32, 3, 0.05, 1e-4, max_selected=n)
+    e = np.zeros(n, np.float32)
+    for t in range(5):
+        g32 = (rng.laplace(0, 1e-3, n) * 30).astype(np.float32)
+        if dtype == 0:
+            stored, wide = g32, g32
+        elif dtype == 1:
+            stored = _bf16_bits(g32)
+            wide = torch.from_numpy(stored.view(np.int16)).view(torch.bfloat16).float().numpy()
+        else:
+            h = g32.astype(np.float16)
+            h[:8] = np.array([0.0, -0.0, 6e-8, -6.1e-5, 65504.0, np.inf, -np.inf, 1e-7], np.float16)
+            stored, wide = h.view(np.uint16), h.astype(np.float32)
+        o.step_scaled(np.ascontiguousarray(stored), dtype, eta)
+        prod = (eta * wide).astype(np.float32)
+        acc = (e + prod).astype(np.float32)
+        sel = np.flatnonzero(np.abs(acc) >= o.threshold_used)
+        assert np.array_equal(o.out_idx(), sel.astype(np.uint32))
+        assert np.array_equal(o.out_val().view(np.uint32), acc[sel].view(np.uint32))
+        e = acc.copy()
+        e[sel] = 0
+        assert np.array_equal(o.residual().view(np.uint32), e.view(np.uint32))
+
+
+def test_scaled_step_with_eta_one_equals_plain_step():
+    n = 2048
+    rng = np.random.default_rng(77)
+    a = oracle.Oracle(n, 256, 2, 0.02, 2e-3)
+    b = oracle.Oracle(n, 256, 2, 0.02, 2e-3)
+    for _ in range(4):
+        g = _rand_grad(rng, n)
+        a.step(g)
+        b.step_scaled(g, 0, 1.0)
+        assert np.array_equal(a.out_idx(), b.out_idx())
+        assert np.array_equal(a.residual().view(np.uint32), b.residual().view(np.uint32))
+        assert a.threshold == b.threshold
+
+
+def test_product_is_rounded_before_the_sum():
+    """A case where fma(eta, g, e) and fl(e + fl(eta*g)) differ in the last bit."""
+    eta, g, e0 = np.float32(1.4099537), np.float32(1.5942448), np.float32(-1.3154374)
+    exact = float(eta) * float(g) + float(e0)                 # what a fused multiply-add rounds
+    two_step = np.float32(np.float32(eta * g) + e0)
+    assert np.float32(exact) != two_step
+    o = oracle.Oracle(32, 32, 1, 0.5, 10.0)
+    o.set_residual(np.full(32, e0, np.float32))
+    o.step_scaled(np.full(32, g, np.float32), 0, eta)
+    assert o.residual()[0] == two_step
