@@ -43,6 +43,12 @@ def main() -> int:
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain device copy of one gradient vector before the timed "
                          "region (a known-size reference for rocprofv3 --pmc byte counters)")
+    ap.add_argument("--grad-dtype", choices=("f32", "bf16", "f16"), default="f32",
+                    help="f32 (default): exdyna_step on learning-rate-scaled fp32 gradients, the "
+                         "headline configuration.  bf16 / f16: exdyna_step_scaled on 16-bit raw "
+                         "gradients with the learning rate fused in (10 instead of 12 B/gradient)")
+    ap.add_argument("--eta", type=float, default=1.0 / 1024.0,
+                    help="learning rate of the --grad-dtype bf16/f16 variant")
     ap.add_argument("--hbm-budget-gb", type=float, default=160.0,
                     help="HBM to spend on pre-generated gradient vectors")
     args = ap.parse_args()
@@ -66,11 +72,28 @@ def main() -> int:
     src = synthetic.GradientSource(w, dev)
 
     # ---- gradients resident in HBM before the clock starts -------------------
-    vec_gb = w.n_g * 4 / 1e9
+    vec_gb = w.n_g * (4 if args.grad_dtype == "f32" else 2) / 1e9
     n_vec = int(max(2, min(W + K, args.hbm_budget_gb // vec_gb)))
-    grads = [src.grad(t) for t in range(n_vec)]
+    scaled = args.grad_dtype != "f32"
+    eta = float(np.float32(args.eta))
+    if scaled:
+        # raw gradients g / eta stored in 16 bits; eta * raw has the scale of the fp32 workload
+        tdt = torch.bfloat16 if args.grad_dtype == "bf16" else torch.float16
+        odt = 1 if args.grad_dtype == "bf16" else 2
+        grads = [(src.grad(t) / eta).to(tdt) for t in range(n_vec)]
+        thr = synthetic.initial_threshold(grads[0].float() * eta, w.density)
+        alg_bytes_per_elem = ALG_BYTES_PER_ELEM - 2.0
+    else:
+        grads = [src.grad(t) for t in range(n_vec)]
+        thr = synthetic.initial_threshold(grads[0], w.density)
+        alg_bytes_per_elem = ALG_BYTES_PER_ELEM
     recycled = n_vec < W + K
-    thr = synthetic.initial_threshold(grads[0], w.density)
+
+    def gpu_step(ctx, g):
+        if scaled:
+            ctx.step_scaled(g, eta)
+        else:
+            ctx.step(g)
     cfg = binding.default_config(n_g=w.n_g, block_size=w.block_size, n_parts=w.n_parts,
                                  density=w.density, threshold0=thr)
 
@@ -85,11 +108,17 @@ def main() -> int:
         xv = binding.ExDyna(cfg, dev)
         cpu_s = 0.0
         for t in range(cpu_steps):
-            h = grads[t % n_vec].cpu().numpy()
+            if scaled:
+                h = grads[t % n_vec].view(torch.int16).cpu().numpy().view(np.uint16)
+            else:
+                h = grads[t % n_vec].cpu().numpy()
             t0 = time.perf_counter()
-            o.step(h)
+            if scaled:
+                o.step_scaled(h, odt, eta)
+            else:
+                o.step(h)
             cpu_s += time.perf_counter() - t0
-            xv.step(grads[t % n_vec])
+            gpu_step(xv, grads[t % n_vec])
             idx, val, off, ka, ke = xv.get_selected()
             ok = (ka == o.k_actual and ke == o.k_emitted
                   and np.array_equal(idx.cpu().numpy().view(np.uint32), o.out_idx())
@@ -120,7 +149,7 @@ def main() -> int:
     # ---- timed region ---------------------------------------------------------
     x = binding.ExDyna(cfg, dev)
     for t in range(W):
-        x.step(grads[t % n_vec])
+        gpu_step(x, grads[t % n_vec])
     torch.cuda.synchronize()
     prof = not args.no_profile_events
     if prof:
@@ -128,7 +157,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for t in range(W, W + K):
-        x.step(grads[t % n_vec])
+        gpu_step(x, grads[t % n_vec])
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
@@ -138,18 +167,18 @@ def main() -> int:
     st = x.get_stats()
     ms_per_step = elapsed / K * 1e3
     value = w.n_g * K / elapsed / 1e9
-    step_bytes = ALG_BYTES_PER_ELEM * w.n_g + ALG_BYTES_PER_PAIR * st.k_emitted
+    step_bytes = alg_bytes_per_elem * w.n_g + ALG_BYTES_PER_PAIR * st.k_emitted
     kern = None
     roofline = None
     if prof:
         ms = ms_events
         kern = {"k_stream_ms": round(float(ms[:, 0].mean()), 5),
                 "k_finish_ms": round(float(ms[:, 1].mean()), 5)}
-        achieved = ALG_BYTES_PER_ELEM * w.n_g / (ms[:, 0].mean() * 1e-3) / 1e9
+        achieved = alg_bytes_per_elem * w.n_g / (ms[:, 0].mean() * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
-                    "alg_bytes_per_launch": ALG_BYTES_PER_ELEM * w.n_g}
+                    "traffic": None if scaled else MEASURED_TRAFFIC_BYTES.get(args.config),
+                    "alg_bytes_per_launch": alg_bytes_per_elem * w.n_g}
     out = {
         "metric": "gradient elements sparsified/sec",
         "value": round(value, 3),
@@ -166,7 +195,8 @@ def main() -> int:
         "config": {"workload": w.name, "n_g": w.n_g, "block_size": w.block_size,
                    "n_parts": w.n_parts, "density": w.density, "threshold0": thr,
                    "gradient_vectors_in_hbm": n_vec, "recycled": recycled,
-                   "cmp": ">=", "parallelism": "1 GPU, P partitions as index ranges"},
+                   "cmp": ">=", "grad_dtype": args.grad_dtype, "eta_fused": eta if scaled else None,
+                   "parallelism": "1 GPU, P partitions as index ranges"},
         "hbm_roofline_pct_per_step": round(100.0 * step_bytes / (elapsed / K) / (HBM_PEAK_GBS * 1e9), 2),
         "step_alg_gb_per_s": round(step_bytes / (elapsed / K) / 1e9, 1),
         "last_step": {"k_actual": st.k_actual, "k_emitted": st.k_emitted,
