@@ -370,3 +370,228 @@ double exo_traffic_ratio(const exo_state *s)
         if (s->part_cnt[p] > m) m = s->part_cnt[p];
     return (double)s->n * (double)m / (double)s->k_actual;
 }
+
+/* ================================================================== */
+/* Alg. 1 with n workers, each with its own gradient and residual.     */
+/* One statement of the algorithm = one loop below, workers in rank    */
+/* order; the two collectives are plain loops over the workers.        */
+
+/* Alg. 3 lines 2-7: the all-gathered partial-k vector is indexed by rank;
+ * rank i selected partition ((t-1) mod n + i) mod n at iteration t-1, so
+ * temp[that partition] = k_t[i].  The modulo is the mathematical one
+ * ((-1) mod n = n-1), which only matters at t = 0. */
+void exo_reindex(const double *k_rank, uint32_t n, uint64_t t, double *k_part)
+{
+    uint64_t shift = (t == 0) ? (uint64_t)(n - 1) : (t - 1) % n;
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t j = (uint32_t)((shift + i) % n);
+        k_part[j] = k_rank[i];
+    }
+}
+
+struct exo_workers {
+    uint64_t n_g, n_b, cap, t;
+    uint32_t b, n, blk_move, min_blk, cmp_mode;
+    double   k, alpha, beta, gamma;
+    float    delta, delta_used;
+    float  **e;                    /* e[i]: worker i's residual; holds acc_i during a step */
+    double  *k_t;                  /* partial-k vector in RANK order, as all-gathered */
+    double  *temp;                 /* the same in partition order */
+    int64_t *blk_part, *blk_pos, *used_part, *used_pos;
+    uint32_t **idx;                /* idx[i]: worker i's own index list */
+    uint64_t *k_rank;              /* k_{i,t}, untruncated */
+    uint64_t *rank_off;            /* n+1 offsets of the workers' lists inside idx_t */
+    uint32_t *idx_t;               /* gathered list, rank order */
+    float  **g;                    /* g[i] = acc_i[idx_t] */
+    float   *g_t;                  /* sum over workers */
+    uint64_t k_actual;
+};
+
+void exo_workers_destroy(exo_workers *s)
+{
+    if (!s) return;
+    for (uint32_t i = 0; i < s->n; ++i) {
+        if (s->e) free(s->e[i]);
+        if (s->idx) free(s->idx[i]);
+        if (s->g) free(s->g[i]);
+    }
+    free(s->e); free(s->idx); free(s->g);
+    free(s->k_t); free(s->temp); free(s->blk_part); free(s->blk_pos);
+    free(s->used_part); free(s->used_pos); free(s->k_rank); free(s->rank_off);
+    free(s->idx_t); free(s->g_t);
+    free(s);
+}
+
+exo_workers *exo_workers_create(uint64_t n_g, uint32_t block_size, uint32_t n,
+                                double density, float threshold0, double alpha, double beta,
+                                double gamma, uint32_t blk_move, uint32_t min_blk,
+                                uint32_t cmp_mode, uint64_t cap)
+{
+    if (n_g == 0 || n_g > 0xFFFFFFFFull) return NULL;
+    if (block_size == 0 || block_size % 32 != 0) return NULL;
+    uint64_t n_b = (n_g + block_size - 1) / block_size;
+    if (n == 0 || n > n_b) return NULL;
+    if (!(density > 0.0 && density <= 1.0)) return NULL;
+    if (!(threshold0 > 0.0f) || isinf(threshold0)) return NULL;
+    if (!(alpha >= 1.0) || !(beta > 1.0) || !(gamma >= 0.0 && gamma < 1.0)) return NULL;
+    if (min_blk == 0 || cmp_mode > 1) return NULL;
+
+    exo_workers *s = (exo_workers *)calloc(1, sizeof *s);
+    if (!s) return NULL;
+    s->n_g = n_g; s->b = block_size; s->n = n; s->n_b = n_b;
+    s->k = density * (double)n_g;
+    s->alpha = alpha; s->beta = beta; s->gamma = gamma;
+    s->blk_move = blk_move; s->min_blk = min_blk; s->cmp_mode = cmp_mode;
+    if (cap == 0) {
+        double c = ceil(4.0 * s->k);
+        cap = c < 1024.0 ? 1024 : (uint64_t)c;
+    }
+    if (cap > n_g) cap = n_g;
+    s->cap = cap;
+    s->delta = threshold0;
+    s->delta_used = threshold0;
+
+    s->e   = (float **)calloc(n, sizeof(float *));
+    s->idx = (uint32_t **)calloc(n, sizeof(uint32_t *));
+    s->g   = (float **)calloc(n, sizeof(float *));
+    s->k_t = (double *)malloc(n * sizeof(double));
+    s->temp = (double *)malloc(n * sizeof(double));
+    s->blk_part = (int64_t *)malloc(n * sizeof(int64_t));
+    s->blk_pos = (int64_t *)malloc(n * sizeof(int64_t));
+    s->used_part = (int64_t *)malloc(n * sizeof(int64_t));
+    s->used_pos = (int64_t *)malloc(n * sizeof(int64_t));
+    s->k_rank = (uint64_t *)calloc(n, sizeof(uint64_t));
+    s->rank_off = (uint64_t *)calloc(n + 1, sizeof(uint64_t));
+    s->idx_t = (uint32_t *)malloc(n * cap * sizeof(uint32_t));
+    s->g_t = (float *)malloc(n * cap * sizeof(float));
+    int ok = s->e && s->idx && s->g && s->k_t && s->temp && s->blk_part && s->blk_pos &&
+             s->used_part && s->used_pos && s->k_rank && s->rank_off && s->idx_t && s->g_t;
+    for (uint32_t i = 0; ok && i < n; ++i) {
+        s->e[i]   = (float *)calloc(n_g, sizeof(float));            /* Alg. 1 line 3 */
+        s->idx[i] = (uint32_t *)malloc(cap * sizeof(uint32_t));
+        s->g[i]   = (float *)malloc(n * cap * sizeof(float));
+        ok = s->e[i] && s->idx[i] && s->g[i];
+    }
+    if (!ok) {
+        exo_workers_destroy(s);
+        return NULL;
+    }
+    for (uint32_t i = 0; i < n; ++i) s->k_t[i] = s->k / (double)n;  /* Alg. 1 line 4 */
+    exo_partition(n_b, n, s->blk_part, s->blk_pos);                  /* Alg. 1 line 6 */
+    memcpy(s->used_part, s->blk_part, n * sizeof(int64_t));
+    memcpy(s->used_pos, s->blk_pos, n * sizeof(int64_t));
+    return s;
+}
+
+/* One iteration of Alg. 1 for all n workers.  g[i] is worker i's gradient,
+ * already scaled by the learning rate (n_g fp32 each). */
+void exo_workers_step(exo_workers *s, const float *const *g)
+{
+    const uint64_t n_g = s->n_g;
+    const uint32_t n = s->n;
+    const float delta = s->delta;
+    s->delta_used = delta;
+
+    /* line 7: acc_i = e_i + g_i */
+    for (uint32_t i = 0; i < n; ++i) {
+        float *acc = s->e[i];
+        for (uint64_t j = 0; j < n_g; ++j) {
+            float a = acc[j] + g[i][j];
+            acc[j] = a;
+        }
+    }
+
+    /* line 8: Allocate.  Every worker computes the same thing from the same
+     * gathered vector, so it is computed once. */
+    exo_reindex(s->k_t, n, s->t, s->temp);
+    exo_allocate(s->temp, s->blk_part, s->blk_pos, n, n_g, s->b,
+                 (int64_t)s->blk_move, (int64_t)s->min_blk, s->alpha);
+    memcpy(s->used_part, s->blk_part, n * sizeof(int64_t));
+    memcpy(s->used_pos, s->blk_pos, n * sizeof(int64_t));
+
+    /* line 9: every worker sparsifies its own partition of its own acc */
+    for (uint32_t i = 0; i < n; ++i) {
+        uint32_t alloc = exo_owner(s->t, i, n);                      /* Alg. 3 line 29 */
+        uint64_t st  = (uint64_t)s->used_pos[alloc] * s->b;          /* Alg. 3 lines 30-31 */
+        uint64_t end = (uint64_t)(s->used_pos[alloc] + s->used_part[alloc]) * s->b;
+        if (end > n_g) end = n_g;
+        if (st > n_g) st = n_g;
+        s->k_rank[i] = exo_select(s->e[i], st, end, delta, (int)s->cmp_mode, s->idx[i], s->cap);
+    }
+
+    /* line 10: AllGather of the index lists (rank order) and of the counts */
+    uint64_t total = 0, len = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        uint64_t sent = s->k_rank[i] < s->cap ? s->k_rank[i] : s->cap;
+        s->rank_off[i] = len;
+        for (uint64_t j = 0; j < sent; ++j) s->idx_t[len + j] = s->idx[i][j];
+        len += sent;
+        total += s->k_rank[i];
+        s->k_t[i] = (double)s->k_rank[i];                            /* also line 15 */
+    }
+    s->rank_off[n] = len;
+
+    /* line 11: g_i = acc_i[idx_t] */
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint64_t j = 0; j < len; ++j) s->g[i][j] = s->e[i][s->idx_t[j]];
+
+    /* line 12: AllReduce(SUM); the order of the sum is rank order here */
+    for (uint64_t j = 0; j < len; ++j) {
+        float sum = s->g[0][j];
+        for (uint32_t i = 1; i < n; ++i) sum = sum + s->g[i][j];
+        s->g_t[j] = sum;
+    }
+
+    /* lines 13-14 */
+    s->k_actual = total;
+    s->delta = exo_estimate(s->k, (double)total, delta, s->beta, s->gamma);
+
+    /* line 17: every worker zeroes its acc at the gathered indices */
+    for (uint32_t i = 0; i < n; ++i)
+        for (uint64_t j = 0; j < len; ++j) s->e[i][s->idx_t[j]] = 0.0f;
+
+    /* line 18: e_{i,t+1} = acc_i (same buffer) */
+    s->t += 1;
+}
+
+uint64_t        exo_workers_capacity(const exo_workers *s)        { return s->cap; }
+uint64_t        exo_workers_n_blocks(const exo_workers *s)        { return s->n_b; }
+uint64_t        exo_workers_iteration(const exo_workers *s)       { return s->t; }
+float           exo_workers_threshold(const exo_workers *s)       { return s->delta; }
+float           exo_workers_threshold_used(const exo_workers *s)  { return s->delta_used; }
+float          *exo_workers_residual(exo_workers *s, uint32_t i)  { return s->e[i]; }
+const uint64_t *exo_workers_k_rank(const exo_workers *s)          { return s->k_rank; }
+const uint64_t *exo_workers_rank_off(const exo_workers *s)        { return s->rank_off; }
+const uint32_t *exo_workers_idx(const exo_workers *s)             { return s->idx_t; }
+const float    *exo_workers_values(const exo_workers *s, uint32_t i) { return s->g[i]; }
+const float    *exo_workers_sum(const exo_workers *s)             { return s->g_t; }
+uint64_t        exo_workers_k_actual(const exo_workers *s)        { return s->k_actual; }
+const int64_t  *exo_workers_blk_part(const exo_workers *s, int which) { return which ? s->blk_part : s->used_part; }
+const int64_t  *exo_workers_blk_pos(const exo_workers *s, int which)  { return which ? s->blk_pos : s->used_pos; }
+
+/* Eq. 1: the mean over the workers of ||e_{i,t+1}||_2, each summed in fp64;
+ * one worker's term when `i` < n, the mean when i == n. */
+double exo_workers_err_norm(const exo_workers *s, uint32_t i)
+{
+    double mean = 0.0;
+    for (uint32_t w = 0; w < s->n; ++w) {
+        double acc = 0.0;
+        for (uint64_t j = 0; j < s->n_g; ++j) {
+            double v = (double)s->e[w][j];
+            acc += v * v;
+        }
+        if (w == i) return sqrt(acc);
+        mean += sqrt(acc);
+    }
+    return mean / (double)s->n;
+}
+
+/* Eq. 5: n * max_i k_{i,t} / k' (0 when nothing was selected) */
+double exo_workers_traffic_ratio(const exo_workers *s)
+{
+    if (s->k_actual == 0) return 0.0;
+    uint64_t m = 0;
+    for (uint32_t i = 0; i < s->n; ++i)
+        if (s->k_rank[i] > m) m = s->k_rank[i];
+    return (double)s->n * (double)m / (double)s->k_actual;
+}

@@ -16,7 +16,11 @@
  * produce their expectation (hand-evaluated cases stored as text fixtures,
  * numpy sort / nonzero brute force, invariants).  The output-capacity rule
  * and the default hyper-parameters are this build's reading, not the
- * paper's: "parity unpinned" for those two (see exo_step).
+ * paper's: "parity unpinned" for those two (see exo_step).  The n-worker
+ * form (exo_workers_*) is pinned by the same definitions written in numpy,
+ * by its reduction to the one-device form for n = 1 and for identical
+ * gradients, and by Alg. 3 line 29 for the re-indexing of lines 2-7; the
+ * order of the AllReduce sum (rank order) is this build's reading.
  */
 #ifndef EXDYNA_ORACLE_H
 #define EXDYNA_ORACLE_H
@@ -101,6 +105,44 @@ const int64_t  *exo_blk_pos(const exo_state *s, int which);
 double          exo_err_norm(const exo_state *s);  /* Eq. 1, one worker: ||e_{t+1}||_2 */
 double          exo_density_error(const exo_state *s); /* Eq. 6 */
 double          exo_traffic_ratio(const exo_state *s); /* Eq. 5; 0 when k' = 0 */
+
+/* ---- Alg. 1 with n workers (each its own gradient and residual) ------- */
+
+/* Alg. 3 lines 2-7: partial-k vector from rank order (as all-gathered after
+ * iteration t-1) to partition order, k_part[((t-1) mod n + i) mod n] = k_rank[i]. */
+void exo_reindex(const double *k_rank, uint32_t n, uint64_t t, double *k_part);
+
+typedef struct exo_workers exo_workers;
+
+/* Same arguments and checks as exo_create; n workers = n partitions.  The
+ * capacity is per worker (each worker's own index list). */
+exo_workers *exo_workers_create(uint64_t n_g, uint32_t block_size, uint32_t n,
+                                double density, float threshold0, double alpha, double beta,
+                                double gamma, uint32_t blk_move, uint32_t min_blk,
+                                uint32_t cmp_mode, uint64_t cap);
+void exo_workers_destroy(exo_workers *s);
+
+/* One iteration of Alg. 1 lines 7-18 for all workers; g[i] = worker i's
+ * gradient (n_g fp32, learning rate applied).  AllGather concatenates the
+ * workers' lists in rank order; AllReduce sums in rank order in fp32. */
+void exo_workers_step(exo_workers *s, const float *const *g);
+
+uint64_t        exo_workers_capacity(const exo_workers *s);
+uint64_t        exo_workers_n_blocks(const exo_workers *s);
+uint64_t        exo_workers_iteration(const exo_workers *s);
+float           exo_workers_threshold(const exo_workers *s);
+float           exo_workers_threshold_used(const exo_workers *s);
+float          *exo_workers_residual(exo_workers *s, uint32_t i);      /* e_i, n_g */
+const uint64_t *exo_workers_k_rank(const exo_workers *s);              /* k_{i,t}, n, untruncated */
+const uint64_t *exo_workers_rank_off(const exo_workers *s);            /* n+1 offsets into idx_t */
+const uint32_t *exo_workers_idx(const exo_workers *s);                 /* idx_t */
+const float    *exo_workers_values(const exo_workers *s, uint32_t i);  /* g_i = acc_i[idx_t] */
+const float    *exo_workers_sum(const exo_workers *s);                 /* g_t */
+uint64_t        exo_workers_k_actual(const exo_workers *s);            /* k' */
+const int64_t  *exo_workers_blk_part(const exo_workers *s, int which);
+const int64_t  *exo_workers_blk_pos(const exo_workers *s, int which);
+double          exo_workers_err_norm(const exo_workers *s, uint32_t i); /* Eq. 1; i == n: the mean */
+double          exo_workers_traffic_ratio(const exo_workers *s);        /* Eq. 5 */
 
 #ifdef __cplusplus
 }

@@ -73,10 +73,32 @@ def _load():
         fn = getattr(L, name)
         fn.restype = rt
         fn.argtypes = [vp]
-    for name in ("exo_blk_part", "exo_blk_pos"):
+    for name in ("exo_blk_part", "exo_blk_pos", "exo_workers_blk_part", "exo_workers_blk_pos"):
         fn = getattr(L, name)
         fn.restype = P(i64)
         fn.argtypes = [vp, C.c_int]
+    L.exo_reindex.restype = None
+    L.exo_reindex.argtypes = [P(f64), u32, u64, P(f64)]
+    L.exo_workers_create.restype = vp
+    L.exo_workers_create.argtypes = [u64, u32, u32, f64, f32, f64, f64, f64, u32, u32, u32, u64]
+    L.exo_workers_destroy.restype = None
+    L.exo_workers_destroy.argtypes = [vp]
+    L.exo_workers_step.restype = None
+    L.exo_workers_step.argtypes = [vp, P(P(f32))]
+    for name, rt in [("exo_workers_capacity", u64), ("exo_workers_n_blocks", u64),
+                     ("exo_workers_iteration", u64), ("exo_workers_threshold", f32),
+                     ("exo_workers_threshold_used", f32), ("exo_workers_k_rank", P(u64)),
+                     ("exo_workers_rank_off", P(u64)), ("exo_workers_idx", P(u32)),
+                     ("exo_workers_sum", P(f32)), ("exo_workers_k_actual", u64),
+                     ("exo_workers_traffic_ratio", f64)]:
+        fn = getattr(L, name)
+        fn.restype = rt
+        fn.argtypes = [vp]
+    for name, rt in [("exo_workers_residual", P(f32)), ("exo_workers_values", P(f32)),
+                     ("exo_workers_err_norm", f64)]:
+        fn = getattr(L, name)
+        fn.restype = rt
+        fn.argtypes = [vp, u32]
     _lib = L
     return L
 
@@ -125,6 +147,77 @@ def scale_factor(k, k_actual, beta, gamma) -> float:
 
 def estimate(k, k_actual, delta, beta, gamma) -> float:
     return float(_load().exo_estimate(k, k_actual, np.float32(delta), beta, gamma))
+
+
+def reindex(k_rank, t: int):
+    """Alg. 3 lines 2-7: partial-k vector from rank order to partition order."""
+    kr = np.array(k_rank, np.float64)
+    out = np.empty_like(kr)
+    _load().exo_reindex(_ptr(kr, C.c_double), len(kr), t, _ptr(out, C.c_double))
+    return out
+
+
+class Workers:
+    """Alg. 1 for n workers with their own gradients and residuals (exo_workers_*)."""
+
+    def __init__(self, n_g, block_size, n, density, threshold0, alpha=1.0, beta=1.1,
+                 gamma=0.01, blk_move=1, min_blk=1, cmp_mode=0, max_selected=0):
+        self._L = _load()
+        self._h = self._L.exo_workers_create(n_g, block_size, n, density, np.float32(threshold0),
+                                             alpha, beta, gamma, blk_move, min_blk, cmp_mode,
+                                             max_selected)
+        if not self._h:
+            raise ValueError("exo_workers_create rejected the configuration")
+        self.n_g, self.b, self.n = n_g, block_size, n
+        self.n_b = int(self._L.exo_workers_n_blocks(self._h))
+        self.cap = int(self._L.exo_workers_capacity(self._h))
+
+    def close(self):
+        if self._h:
+            self._L.exo_workers_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def step(self, grads):
+        """grads: n contiguous float32 arrays of n_g elements, one per worker."""
+        assert len(grads) == self.n
+        for g in grads:
+            assert g.dtype == np.float32 and g.flags.c_contiguous and g.size == self.n_g
+        arr = (C.POINTER(C.c_float) * self.n)(*[_ptr(g, C.c_float) for g in grads])
+        self._L.exo_workers_step(self._h, arr)
+
+    def _arr(self, p, n, dtype):
+        if n == 0:
+            return np.empty(0, dtype)
+        return np.ctypeslib.as_array(p, shape=(n,)).astype(dtype, copy=True)
+
+    @property
+    def t(self): return int(self._L.exo_workers_iteration(self._h))
+    @property
+    def threshold(self): return np.float32(self._L.exo_workers_threshold(self._h))
+    @property
+    def threshold_used(self): return np.float32(self._L.exo_workers_threshold_used(self._h))
+    @property
+    def k_actual(self): return int(self._L.exo_workers_k_actual(self._h))
+
+    def residual(self, i, copy=True):
+        a = np.ctypeslib.as_array(self._L.exo_workers_residual(self._h, i), shape=(self.n_g,))
+        return a.copy() if copy else a
+
+    def k_rank(self): return self._arr(self._L.exo_workers_k_rank(self._h), self.n, np.uint64)
+    def rank_off(self): return self._arr(self._L.exo_workers_rank_off(self._h), self.n + 1, np.uint64)
+    def idx(self): return self._arr(self._L.exo_workers_idx(self._h), int(self.rank_off()[-1]), np.uint32)
+    def values(self, i): return self._arr(self._L.exo_workers_values(self._h, i), int(self.rank_off()[-1]), np.float32)
+    def sum(self): return self._arr(self._L.exo_workers_sum(self._h), int(self.rank_off()[-1]), np.float32)
+    def blk_part(self, which=0): return self._arr(self._L.exo_workers_blk_part(self._h, which), self.n, np.int64)
+    def blk_pos(self, which=0): return self._arr(self._L.exo_workers_blk_pos(self._h, which), self.n, np.int64)
+    def err_norm(self, i=None): return float(self._L.exo_workers_err_norm(self._h, self.n if i is None else i))
+    def traffic_ratio(self): return float(self._L.exo_workers_traffic_ratio(self._h))
 
 
 class Oracle:
