@@ -10,7 +10,8 @@
  *   delta   <- online threshold scaling           (Alg. 5, Sec. 4.4)
  *   topology <- adjacent-partition rebalancing    (Alg. 3 lines 8-28, Sec. 4.2)
  * The collectives of Alg. 1 (lines 10, 12) and the model update (line 16) are
- * not part of this library.
+ * not part of this library.  The "worker view" calls further down split the
+ * iteration at those collectives for callers that have one context per worker.
  *
  * Conventions
  *  - Pointers named d_* are DEVICE pointers, h_* are HOST pointers.
@@ -84,8 +85,10 @@ typedef struct {
     double   err_norm;      /* ||e_{t+1}||_2 (Eq. 1 with one worker); -1 when not requested */
     float    delta_used;    /* delta_t the step compared with                               */
     float    delta_next;    /* delta_{t+1} (Alg. 5 line 8)                                  */
-    uint32_t overflow;      /* 1 when k' > capacity                                         */
+    uint32_t overflow;      /* 1 when k' > capacity (worker view: some worker's k_i > capacity) */
     uint32_t moves;         /* boundary moves Alg. 3 made for the next iteration            */
+    uint32_t bad_index;     /* worker view: gathered indices >= n_g, skipped by the exchange */
+    uint32_t reserved;
 } exdyna_stats;
 
 /* Fill *cfg with defaults: alpha 1.0, beta 1.1, gamma 0.01, blk_move 1,
@@ -136,6 +139,50 @@ int exdyna_step(exdyna_ctx *ctx, const float *d_grad, void *hip_stream);
  * kinds can be mixed freely on one context. */
 int exdyna_step_scaled(exdyna_ctx *ctx, const void *d_grad, int grad_dtype, float eta,
                        void *hip_stream);
+
+/* ---- worker view --------------------------------------------------------
+ * For callers that run Alg. 1 as printed, one context per worker, each with its
+ * own gradient and residual, and do the two collectives (Alg. 1 lines 10 and
+ * 12) themselves.  An iteration is exdyna_worker_select, the caller's
+ * AllGather, exdyna_worker_exchange, the caller's AllReduce.  All contexts of
+ * a job are created with the same configuration (n_parts = number of workers)
+ * and stay replicas of each other in threshold and topology, because Alg. 5
+ * and Alg. 3 see the same gathered counts everywhere.
+ *
+ * exdyna_worker_select (Alg. 1 lines 7-9 for worker `rank`): acc = e + eta * g
+ * over all n_g gradients as in exdyna_step_scaled (same d_grad, grad_dtype,
+ * eta rules; eta = 1 with EXDYNA_F32 is bit-identical to the single add of
+ * exdyna_step), but the comparison runs only inside the partition that worker
+ * `rank` < n_parts owns at this iteration, (t mod P + rank) mod P of the
+ * current topology (Alg. 3 lines 29-31).  Afterwards exdyna_get_selected gives
+ * this worker's list idx_{i,t} (ascending, cut at the capacity; the values are
+ * acc at them; k_actual is the uncut count k_{i,t}), and those entries of the
+ * residual are already zero.  Threshold, topology and t do not change yet.
+ * Returns EXDYNA_ESTATE if a selection is already waiting for its exchange;
+ * exdyna_step / exdyna_step_scaled return it too while one is.
+ *
+ * exdyna_worker_exchange (Alg. 1 lines 11, 13-15, 17 and the next Allocate):
+ *  d_idx_all        the gathered lists, P rows of `stride` indices; row r holds
+ *                   worker r's list in its first min(k_r, capacity, stride)
+ *                   entries, the rest of the row is ignored.  Row `rank` must
+ *                   be this context's own list.
+ *  d_counts_by_rank P uint64, k_{r,t} of worker r (not cut), 8-byte aligned.
+ *  d_val_all        P rows of `stride` floats, written here: this worker's acc
+ *                   at every gathered index (g_{i,t} of line 11), 0 in the
+ *                   unused part of each row, so that a SUM AllReduce over the
+ *                   whole buffer gives g_t.
+ * Every gathered entry of the residual is then cleared (line 17); an index
+ * >= n_g is skipped and counted in exdyna_stats.bad_index.  The counts are
+ * moved from rank order to partition order (Alg. 3 lines 2-7) and drive Alg. 5
+ * and Alg. 3 exactly as in exdyna_step; t advances.  stride may be 0 when
+ * nothing was selected anywhere (the pointers may then be NULL).  Two kernels
+ * in `select`, one in `exchange`; nothing synchronises.  Not for HIP-graph
+ * replay: the owned partition is computed on the host from t. */
+int exdyna_worker_select(exdyna_ctx *ctx, const void *d_grad, int grad_dtype, float eta,
+                         uint32_t rank, void *hip_stream);
+int exdyna_worker_exchange(exdyna_ctx *ctx, const uint32_t *d_idx_all,
+                           const uint64_t *d_counts_by_rank, uint64_t stride, float *d_val_all,
+                           void *hip_stream);
 
 /* Results of the last step.  *d_idx / *d_val: device arrays of k_emitted
  * ascending gradient indices and the accumulated values at them (Alg. 1 lines

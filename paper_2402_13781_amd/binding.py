@@ -20,7 +20,8 @@ EXDYNA_OK, EXDYNA_EINVAL, EXDYNA_ENULL, EXDYNA_EALIGN, EXDYNA_ESTATE, EXDYNA_ENO
 # every symbol include/exdyna.h declares
 SYMBOLS = (
     "exdyna_default_config", "exdyna_block_size_from_nb", "exdyna_workspace_bytes", "exdyna_init",
-    "exdyna_step", "exdyna_step_scaled", "exdyna_get_selected", "exdyna_get_partitions", "exdyna_get_block_counts",
+    "exdyna_step", "exdyna_step_scaled", "exdyna_worker_select", "exdyna_worker_exchange",
+    "exdyna_get_selected", "exdyna_get_partitions", "exdyna_get_block_counts",
     "exdyna_get_part_counts", "exdyna_get_stats", "exdyna_get_dims", "exdyna_set_profiling",
     "exdyna_get_kernel_ms", "exdyna_state_bytes", "exdyna_get_state", "exdyna_set_state",
     "exdyna_strerror", "exdyna_last_hip_error", "exdyna_destroy",
@@ -43,6 +44,7 @@ class Stats(C.Structure):
         ("k_max_part", C.c_uint64), ("density_error", C.c_double), ("traffic_ratio", C.c_double),
         ("err_norm", C.c_double), ("delta_used", C.c_float), ("delta_next", C.c_float),
         ("overflow", C.c_uint32), ("moves", C.c_uint32),
+        ("bad_index", C.c_uint32), ("reserved", C.c_uint32),
     ]
 
 
@@ -72,6 +74,8 @@ def load() -> C.CDLL:
     L.exdyna_init.argtypes = [P(vp), P(Config), vp, vp, C.c_size_t, vp]
     L.exdyna_step.argtypes = [vp, vp, vp]
     L.exdyna_step_scaled.argtypes = [vp, vp, C.c_int, C.c_float, vp]
+    L.exdyna_worker_select.argtypes = [vp, vp, C.c_int, C.c_float, u32, vp]
+    L.exdyna_worker_exchange.argtypes = [vp, vp, vp, u64, vp, vp]
     L.exdyna_get_selected.argtypes = [vp, P(vp), P(vp), P(vp), P(u64), P(u64)]
     L.exdyna_get_partitions.argtypes = [vp, C.c_int, P(u32), P(u32), P(u64), P(u64), P(u32)]
     L.exdyna_get_block_counts.argtypes = [vp, P(u32)]
@@ -206,6 +210,40 @@ class ExDyna:
             raise ValueError("grad must be a contiguous fp32/bf16/fp16 tensor of n_g elements on the context's device")
         self._check(self._L.exdyna_step_scaled(self._h, C.c_void_p(grad.data_ptr()), dt, float(eta),
                                                self._stream_ptr(stream)), "exdyna_step_scaled")
+
+    def _grad_dtype(self, grad):
+        torch = self._torch
+        dt = {torch.float32: EXDYNA_F32, torch.bfloat16: EXDYNA_BF16, torch.float16: EXDYNA_F16}.get(grad.dtype)
+        if dt is None or grad.device != self.device or not grad.is_contiguous() \
+                or grad.numel() != self.cfg.n_g:
+            raise ValueError("grad must be a contiguous fp32/bf16/fp16 tensor of n_g elements on the context's device")
+        return dt
+
+    def worker_select(self, grad, rank: int, eta: float = 1.0, stream=None):
+        """exdyna_worker_select: worker `rank`'s accumulate and selection of its own partition."""
+        self._check(self._L.exdyna_worker_select(self._h, C.c_void_p(grad.data_ptr()), self._grad_dtype(grad),
+                                                 float(eta), int(rank), self._stream_ptr(stream)),
+                    "exdyna_worker_select")
+
+    def worker_exchange(self, idx_all, counts_by_rank, val_all, stream=None):
+        """exdyna_worker_exchange.  idx_all: int32/uint32-bits tensor [P, stride]; counts_by_rank: int64 [P];
+        val_all: float32 [P, stride], written.  All on the context's device, contiguous."""
+        torch = self._torch
+        P = self.P
+        if counts_by_rank.dtype != torch.int64 or counts_by_rank.numel() != P or not counts_by_rank.is_contiguous() \
+                or counts_by_rank.device != self.device:
+            raise ValueError("counts_by_rank must be a contiguous int64 tensor of n_parts entries on the device")
+        if idx_all.dim() != 2 or idx_all.shape[0] != P or idx_all.dtype != torch.int32 or not idx_all.is_contiguous() \
+                or idx_all.device != self.device:
+            raise ValueError("idx_all must be a contiguous int32 tensor [n_parts, stride] on the device")
+        if val_all.shape != idx_all.shape or val_all.dtype != torch.float32 or not val_all.is_contiguous() \
+                or val_all.device != self.device:
+            raise ValueError("val_all must be a contiguous float32 tensor shaped like idx_all on the device")
+        stride = int(idx_all.shape[1])
+        self._check(self._L.exdyna_worker_exchange(
+            self._h, C.c_void_p(idx_all.data_ptr() if stride else None), C.c_void_p(counts_by_rank.data_ptr()),
+            stride, C.c_void_p(val_all.data_ptr() if stride else None), self._stream_ptr(stream)),
+            "exdyna_worker_exchange")
 
     def get_selected(self):
         """exdyna_get_selected: (idx[int32 view of u32], val[fp32], part_off[int64], k_actual, k_emitted)."""

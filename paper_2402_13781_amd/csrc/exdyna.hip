@@ -65,6 +65,7 @@ constexpr uint32_t kMaxParts    = 1024;
 constexpr uint32_t kFinishWG    = 1024;  // k_finish: 16 waves = control, or 16 chunks
 constexpr uint32_t kErrSlots    = 256;
 constexpr uint32_t kFlag        = 0x80000000u;  // tile count flag: pairs not staged
+constexpr uint32_t kAllParts    = 0xFFFFFFFFu;  // selection over every partition (one device plays all workers)
 constexpr uint64_t kMagic       = 0x45784479'6e61'0002ull;
 
 // Device-resident scalar state.  One instance at the start of the workspace.
@@ -81,6 +82,10 @@ struct DevState {
     double   density_error;
     double   traffic_ratio;
     double   err_norm;
+    uint64_t own_actual;   // what the output lists hold: selected / emitted by the last selection pass
+    uint64_t own_emitted;  // (one worker's share in the worker view, everything otherwise)
+    uint32_t bad_index;    // worker view: gathered indices >= n_g that were skipped
+    uint32_t pad;
 };
 
 struct CtrlParams {
@@ -212,7 +217,21 @@ struct StreamArgs {
     uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
     uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
     uint32_t        one_counter;  // a block is exactly one segment: blk_cnt doubles as seg_cnt
+    // worker view (Alg. 1 line 9): compare only inside partition own_part of this
+    // iteration's topology; kAllParts = everywhere
+    uint32_t        own_part;
+    const int32_t  *cur_part;
+    const int32_t  *cur_pos;
 };
+
+// Granule range [lo, hi) of partition p: blocks are whole granules (b % 256 == 0).
+__device__ __forceinline__ void partition_granules(const int32_t *part, const int32_t *pos, uint32_t p,
+                                                   uint32_t gran_per_blk, uint32_t &lo, uint32_t &hi)
+{
+    const uint32_t ps = (uint32_t)pos[p], pn = (uint32_t)part[p];
+    lo = ps * gran_per_blk;
+    hi = (ps + pn) * gran_per_blk;
+}
 
 template <int CMP, bool NORM, int GT, bool SCALE>
 __global__ void __launch_bounds__(kStreamWG)
@@ -228,6 +247,9 @@ k_stream(StreamArgs A)
     const bool     live   = tile < A.n_tiles;            // wave-uniform
     const bool     fast   = gran0 + kTileGran <= n_full;  // wave-uniform: no ragged end inside
     float nrm = 0.f;
+    uint32_t g_lo = 0u, g_hi = 0xFFFFFFFFu;  // granules that are compared at all
+    if (A.own_part != kAllParts)
+        partition_granules(A.cur_part, A.cur_pos, A.own_part, A.gran_per_blk, g_lo, g_hi);
 
     if (live && fast) {
         f32x4    a[kTileGran];
@@ -249,6 +271,7 @@ k_stream(StreamArgs A)
                 a[u].w = accumulate<SCALE>(ev[u].w, gv[u].w, A.eta);
                 nib[u] = sel<CMP>(a[u].x, delta) | (sel<CMP>(a[u].y, delta) << 1) |
                          (sel<CMP>(a[u].z, delta) << 2) | (sel<CMP>(a[u].w, delta) << 3);
+                if (gran0 + u < g_lo || gran0 + u >= g_hi) nib[u] = 0u;  // wave-uniform: another worker's partition
             }
         }
 
@@ -334,12 +357,13 @@ k_stream(StreamArgs A)
         for (uint32_t u = 0; u < kTileGran; ++u) {
             const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
             uint32_t f = 0;
+            const bool mine = gran0 + u >= g_lo && gran0 + u < g_hi;  // wave-uniform
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) {
                 if (base + q < A.n_g) {
                     const float v = accumulate<SCALE>(A.e[base + q], load_grad1<GT>(A.g, base + q), A.eta);
                     A.e[base + q] = v;
-                    const uint32_t hit = sel<CMP>(v, delta);
+                    const uint32_t hit = mine ? sel<CMP>(v, delta) : 0u;
                     f |= hit << q;
                     if (NORM) nrm += hit ? 0.f : v * v;
                 }
@@ -392,6 +416,9 @@ struct FinishArgs {
     double         *err_slots;       // this iteration's norm partials
     double         *err_slots_next;  // cleared here
     uint32_t        n_tiles, n_chunks, n_segs, seg_shift, chunk_shift, slots_min, pool_extra, parity;
+    uint32_t        mode;            // kCtrlFull or kCtrlSelect
+    uint32_t        own_part;        // worker view: the partition that was compared; else kAllParts
+    uint32_t        gran_per_blk;
 };
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
@@ -411,38 +438,40 @@ __device__ __forceinline__ uint32_t compose(uint32_t later, uint32_t earlier)
            (((later >> (2u * ((earlier >> 4) & 3u))) & 3u) << 4);
 }
 
-__device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
+// Shared-memory scratch of the control workgroup.
+struct CtrlShared {
+    uint32_t cnt[kMaxParts];    // selected per partition
+    int32_t  lpos[kMaxParts];   // topology the iteration selected with
+    int32_t  lpart[kMaxParts];
+    uint8_t  flags[kMaxParts];
+    uint32_t wsum[kFinishWG / 64];
+    uint32_t wmax[kFinishWG / 64];
+    uint32_t wfun[kFinishWG / 64];
+    uint32_t wcarry[kFinishWG / 64];
+    uint32_t n_moves;
+    uint64_t k_total;
+};
+
+// What the control workgroup does with the per-partition counts.
+enum : uint32_t {
+    kCtrlFull   = 0,  // one device plays every worker: offsets, Alg. 5, Alg. 3, statistics
+    kCtrlSelect = 1,  // worker view, after the selection pass: output offsets of the own list only
+    kCtrlUpdate = 2   // worker view, after the exchange: Alg. 5, Alg. 3, statistics from the gathered counts
+};
+
+// k_{p,t} from the per-block counters (Sec. 4.2: the workload of a partition).
+// Each wave takes a contiguous run of the counters, 64 at a time; its first
+// slices are requested before anything waits on memory.  Also clears the other
+// parity's block counters and norm partials for the next iteration.
+__device__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S)
 {
     constexpr uint32_t kWaves = kFinishWG / 64;
-    constexpr uint32_t kIdent = 0u | (1u << 2) | (2u << 4);  // s -> s
-    __shared__ uint32_t cnt_s[kMaxParts];
-    __shared__ int32_t  lpos[kMaxParts];
-    __shared__ int32_t  lpart[kMaxParts];
-    __shared__ uint8_t  flags[kMaxParts];
-    __shared__ uint32_t wsum[kWaves];
-    __shared__ uint32_t wmax[kWaves];
-    __shared__ uint32_t wfun[kWaves];
-    __shared__ uint32_t wcarry[kWaves];
-    __shared__ uint32_t n_moves;
-    __shared__ uint64_t k_total;
-
     const uint32_t tid  = threadIdx.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wave = tid >> 6;
     const uint32_t P    = prm.n_parts;
     const uint32_t n_b  = prm.n_b;
 
-    float    delta  = 0.f;
-    uint64_t t_done = 0;
-    if (tid == 0) {
-        delta  = A.st->delta[A.parity];
-        t_done = A.st->t;
-    }
-    const int32_t part = tid < P ? A.cur_part[tid] : 0;
-    const int32_t pos  = tid < P ? A.cur_pos[tid] : 0;
-    // k_{p,t} (Sec. 4.2: the workload of a partition).  Each wave takes a
-    // contiguous run of the block counters, 64 at a time; its first slices are
-    // requested before anything waits on memory.
     const uint32_t per_wave = (n_b + kWaves - 1) / kWaves;
     const uint32_t beg      = wave * per_wave < n_b ? wave * per_wave : n_b;
     const uint32_t end      = beg + per_wave < n_b ? beg + per_wave : n_b;
@@ -454,11 +483,10 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
         cbuf[q] = i < end ? A.blk_cnt[i] : 0u;
     }
     if (tid < P) {
-        cnt_s[tid] = 0u;
-        lpos[tid]  = pos;
-        lpart[tid] = part;
+        S.cnt[tid]   = 0u;
+        S.lpos[tid]  = A.cur_pos[tid];
+        S.lpart[tid] = A.cur_part[tid];
     }
-    if (tid == 0) n_moves = 0u;
     if (tid < kErrSlots) A.err_slots_next[tid] = 0.0;
     __syncthreads();
 
@@ -467,10 +495,10 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
         uint32_t plo = 0, phi = P - 1;
         while (plo < phi) {
             const uint32_t mid = (plo + phi + 1) >> 1;
-            if ((uint32_t)lpos[mid] <= beg) plo = mid; else phi = mid - 1;
+            if ((uint32_t)S.lpos[mid] <= beg) plo = mid; else phi = mid - 1;
         }
         uint32_t pcur       = plo;
-        uint32_t next_start = pcur + 1 < P ? (uint32_t)lpos[pcur + 1] : 0xFFFFFFFFu;
+        uint32_t next_start = pcur + 1 < P ? (uint32_t)S.lpos[pcur + 1] : 0xFFFFFFFFu;
         uint32_t acc        = 0;  // this lane's share of partition pcur so far
         for (uint32_t i0 = beg; i0 < end; i0 += kAhead * 64u) {
             if (i0 != beg) {
@@ -491,22 +519,44 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
                     c = i < next_start ? 0u : c;
 #pragma unroll
                     for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
-                    if (lane == 0 && acc) atomicAdd(&cnt_s[pcur], acc);
+                    if (lane == 0 && acc) atomicAdd(&S.cnt[pcur], acc);
                     acc = 0;
                     ++pcur;
-                    next_start = pcur + 1 < P ? (uint32_t)lpos[pcur + 1] : 0xFFFFFFFFu;
+                    next_start = pcur + 1 < P ? (uint32_t)S.lpos[pcur + 1] : 0xFFFFFFFFu;
                 }
                 acc += c;
             }
         }
 #pragma unroll
         for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
-        if (lane == 0 && acc) atomicAdd(&cnt_s[pcur], acc);
+        if (lane == 0 && acc) atomicAdd(&S.cnt[pcur], acc);
     }
     __syncthreads();
+}
+
+// Everything that follows from the per-partition counts in S.cnt (S.lpos /
+// S.lpart hold the topology they were counted with).
+__device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S, uint32_t mode)
+{
+    constexpr uint32_t kWaves = kFinishWG / 64;
+    constexpr uint32_t kIdent = 0u | (1u << 2) | (2u << 4);  // s -> s
+    const uint32_t tid  = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = tid >> 6;
+    const uint32_t P    = prm.n_parts;
+
+    float    delta  = 0.f;
+    uint64_t t_done = 0;
+    if (tid == 0) {
+        delta  = A.st->delta[A.parity];
+        t_done = A.st->t;
+        S.n_moves = 0u;
+    }
+    const int32_t part = tid < P ? S.lpart[tid] : 0;
+    const int32_t pos  = tid < P ? S.lpos[tid] : 0;
 
     // exclusive scan and maximum of the P counts (P <= 1024 = one value per thread)
-    const uint32_t c    = tid < P ? cnt_s[tid] : 0u;
+    const uint32_t c    = tid < P ? S.cnt[tid] : 0u;
     const uint32_t incl = wave_incl_scan(c, lane);
     uint32_t mx = c;
 #pragma unroll
@@ -514,21 +564,32 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
         const uint32_t o = __shfl_xor(mx, d, 64);
         mx = o > mx ? o : mx;
     }
-    if (lane == 63) wsum[wave] = incl;
-    if (lane == 0) wmax[wave] = mx;
+    if (lane == 63) S.wsum[wave] = incl;
+    if (lane == 0) S.wmax[wave] = mx;
     __syncthreads();
     if (wave == 0) {
-        const uint32_t v  = lane < kWaves ? wsum[lane] : 0u;
+        const uint32_t v  = lane < kWaves ? S.wsum[lane] : 0u;
         const uint32_t vi = wave_incl_scan(v, lane);
-        if (lane < kWaves) wsum[lane] = vi - v;
-        if (lane == kWaves - 1) k_total = vi;  // k' (Alg. 1 line 13)
+        if (lane < kWaves) S.wsum[lane] = vi - v;
+        if (lane == kWaves - 1) S.k_total = vi;  // k' (Alg. 1 line 13)
     }
     __syncthreads();
-    const uint64_t excl     = (uint64_t)wsum[wave] + (incl - c);
-    const uint64_t k_actual = k_total;
+    const uint64_t excl     = (uint64_t)S.wsum[wave] + (incl - c);
+    const uint64_t k_actual = S.k_total;
     if (tid < P) {
         A.part_cnt[tid] = c;
-        A.part_off[tid] = excl < prm.cap ? excl : prm.cap;
+        if (mode != kCtrlUpdate) A.part_off[tid] = excl < prm.cap ? excl : prm.cap;
+    }
+    if (mode == kCtrlSelect) {  // the gathered counts decide the rest, after the exchange
+        if (tid == 0) {
+            DevState *st = A.st;
+            A.part_off[P]   = k_actual < prm.cap ? k_actual : prm.cap;
+            st->own_actual  = k_actual;
+            st->own_emitted = k_actual < prm.cap ? k_actual : prm.cap;
+            st->delta_used  = delta;
+            st->bad_index   = 0u;
+        }
+        return;
     }
 
     // Alg. 3 lines 8-10 and the comparisons of lines 13 / 21.  This iteration's
@@ -552,7 +613,7 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
                 (dp > prm.alpha ? 4u : 0u) | (dp < prm.inv_alpha ? 8u : 0u) |
                 (dm > prm.alpha ? 16u : 0u) | (dm < prm.inv_alpha ? 32u : 0u);
         }
-        flags[tid] = (uint8_t)f;
+        S.flags[tid] = (uint8_t)f;
     }
     __syncthreads();
 
@@ -561,10 +622,10 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     const int64_t min_blk = (int64_t)prm.min_blk;
     uint32_t table = 0;  // beyond the last pair: every state maps to "none"
     if (tid + 1 < P) {
-        const uint32_t f_i     = flags[tid];
-        const uint32_t f_n     = flags[tid + 1];
+        const uint32_t f_i     = S.flags[tid];
+        const uint32_t f_n     = S.flags[tid + 1];
         const bool     det2_hi = f_n & 1u, det2_lo = f_n & 2u;
-        const int64_t  part_n  = lpart[tid + 1];
+        const int64_t  part_n  = S.lpart[tid + 1];
 #pragma unroll
         for (uint32_t st = 0; st < 3; ++st) {
             const uint32_t fi     = f_i >> (2u * st);
@@ -587,22 +648,22 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
         const uint32_t prev = __shfl_up(fun, d, 64);
         if (lane >= d) fun = compose(fun, prev);
     }
-    if (lane == 63) wfun[wave] = fun;
+    if (lane == 63) S.wfun[wave] = fun;
     __syncthreads();
     if (tid == 0) {
         uint32_t stt = 0;  // pair 0 starts untouched
         for (uint32_t w = 0; w < kWaves; ++w) {
-            wcarry[w] = stt;
-            stt = (wfun[w] >> (2u * stt)) & 3u;
+            S.wcarry[w] = stt;
+            stt = (S.wfun[w] >> (2u * stt)) & 3u;
         }
     }
     __syncthreads();
     uint32_t before = __shfl_up(fun, 1, 64);
     if (lane == 0) before = kIdent;
-    const uint32_t st_in = (before >> (2u * wcarry[wave])) & 3u;  // what pair tid-1 did
-    const uint32_t act   = (table >> (2u * st_in)) & 3u;          // what pair tid does
+    const uint32_t st_in = (before >> (2u * S.wcarry[wave])) & 3u;  // what pair tid-1 did
+    const uint32_t act   = (table >> (2u * st_in)) & 3u;            // what pair tid does
     const uint64_t moved = __ballot(act != 0);
-    if (lane == 0 && moved) atomicAdd(&n_moves, (uint32_t)__popcll(moved));
+    if (lane == 0 && moved) atomicAdd(&S.n_moves, (uint32_t)__popcll(moved));
     if (tid < P) {
         const int32_t bmi = (int32_t)prm.blk_move;
         // lines 16-18 / 24-26 as seen from partition tid: it is the right side
@@ -615,10 +676,8 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
     __syncthreads();
 
     if (tid == 0) {
-        A.part_off[P] = k_actual < prm.cap ? k_actual : prm.cap;
-
+        DevState *st = A.st;
         // ---- Alg. 5: online threshold scaling ----
-        DevState   *st   = A.st;
         const double exam = (double)k_actual / prm.k;
         float sf;
         if (exam > prm.beta)
@@ -634,16 +693,33 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 
         // ---- Eq. 2 / 5 / 6 ----
         uint64_t m_t = 0;
-        for (uint32_t w = 0; w < kWaves; ++w) m_t = wmax[w] > m_t ? wmax[w] : m_t;
+        for (uint32_t w = 0; w < kWaves; ++w) m_t = S.wmax[w] > m_t ? S.wmax[w] : m_t;
+        uint64_t emitted = k_actual < prm.cap ? k_actual : prm.cap;
+        if (mode == kCtrlFull) {
+            A.part_off[P]   = emitted;
+            st->own_actual  = k_actual;
+            st->own_emitted = emitted;
+        } else {
+            // every worker's list is cut at the capacity on its own
+            emitted = 0;
+            for (uint32_t p = 0; p < P; ++p) emitted += S.cnt[p] < prm.cap ? S.cnt[p] : prm.cap;
+        }
         st->k_actual      = k_actual;
-        st->k_emitted     = k_actual < prm.cap ? k_actual : prm.cap;
-        st->overflow      = k_actual > prm.cap ? 1u : 0u;
+        st->k_emitted     = emitted;
+        st->overflow      = emitted < k_actual ? 1u : 0u;
         st->k_max_part    = m_t;
         st->density_error = fabs(prm.k - (double)k_actual) / (double)prm.n_g;
         st->traffic_ratio = k_actual ? (double)P * (double)m_t / (double)k_actual : 0.0;
         st->t     = t_done + 1;  // counted on the device so that a captured graph can be replayed
-        st->moves = n_moves;
+        st->moves = S.n_moves;
     }
+}
+
+__device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
+{
+    __shared__ CtrlShared S;
+    control_counts(A, prm, S);
+    control_decide(A, prm, S, A.mode);
 }
 
 // ---- compaction: a workgroup takes 16 consecutive chunks, one wavefront per
@@ -661,7 +737,8 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 template <bool NORM, int CMP>
 __device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32_t tile, uint64_t r0,
                                                      float delta, uint32_t lane, uint32_t n_g,
-                                                     uint64_t cap, float &spill)
+                                                     uint64_t cap, uint32_t g_lo, uint32_t g_hi,
+                                                     float &spill)
 {
     if (!NORM && r0 >= cap) return;  // nothing fits: the tile stays in the residual as it is
     float *__restrict__ e = A.e;
@@ -689,9 +766,11 @@ __device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32
     for (uint32_t u = 0; u < kTileGran; ++u) {
         const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
         nib[u] = 0;
+        if (gran0 + u >= g_lo && gran0 + u < g_hi) {  // the streaming pass compared only these
 #pragma unroll
-        for (uint32_t q = 0; q < 4; ++q)
-            if (base + q < n_g) nib[u] |= sel<CMP>(v[u][q], delta) << q;
+            for (uint32_t q = 0; q < 4; ++q)
+                if (base + q < n_g) nib[u] |= sel<CMP>(v[u][q], delta) << q;
+        }
     }
     uint64_t running = r0;
 #pragma unroll
@@ -855,13 +934,16 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
     }
 
     uint64_t flagged = __ballot((word & kFlag) != 0);
+    uint32_t g_lo = 0u, g_hi = 0xFFFFFFFFu;
+    if (flagged && A.own_part != kAllParts)
+        partition_granules(A.cur_part, A.cur_pos, A.own_part, A.gran_per_blk, g_lo, g_hi);
     while (flagged) {  // wave-uniform
         const uint32_t l = (uint32_t)__ffsll((unsigned long long)flagged) - 1u;
         flagged &= flagged - 1u;
         const uint32_t lo = __shfl((uint32_t)r0, l, 64), hi = __shfl((uint32_t)(r0 >> 32), l, 64);
         const float    dl = __shfl(delta, l, 64);
         compact_flagged_tile<NORM, CMP>(A, (chunk << cs) + l, ((uint64_t)hi << 32) | lo, dl, lane,
-                                        n_g, cap, spill);
+                                        n_g, cap, g_lo, g_hi, spill);
     }
 
     if (NORM) {
@@ -880,6 +962,79 @@ k_finish(FinishArgs A, CtrlParams prm)
         finish_control(A, prm);
     else
         finish_compact<NORM, CMP>(A, (uint32_t)prm.n_g, prm.cap);
+}
+
+// ---------------------------------------------------------------------------
+// Worker view, after the AllGather (Alg. 1 lines 11 and 17, then 13-15): one
+// worker's residual meets the gathered index list of all workers.
+//   blockIdx.y = r < P   rank r's part of the list: read acc at those indices
+//                        into the value buffer (what the AllReduce will sum) and
+//                        clear them.  The worker's own part was cleared by the
+//                        streaming pass already: its values come from its list.
+//   blockIdx.y = P       control: the gathered counts, moved from rank order
+//                        to partition order (Alg. 3 lines 2-7), drive Alg. 5
+//                        and Alg. 3 for the next iteration.
+struct ExchangeArgs {
+    const uint32_t *idx_all;  // P x stride: rank r's indices start at r * stride
+    const uint64_t *counts;   // k_{r,t} by rank, not cut at the capacity
+    float          *val_all;  // same layout as idx_all; 0 beyond each rank's list
+    const float    *own_val;  // values of this worker's own list
+    uint64_t        stride;
+    uint32_t        rank;     // this worker
+    uint32_t        t_mod_p;  // iteration mod P
+};
+
+template <bool NORM>
+__global__ void __launch_bounds__(kFinishWG)
+k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
+{
+    const uint32_t P   = prm.n_parts;
+    const uint32_t tid = threadIdx.x;
+    if (blockIdx.y == P) {
+        if (blockIdx.x != 0) return;
+        __shared__ CtrlShared S;
+        if (tid < P) {
+            S.lpos[tid]  = A.cur_pos[tid];
+            S.lpart[tid] = A.cur_part[tid];
+            // rank tid selected partition (t mod P + tid) mod P (Alg. 3 line 29)
+            const uint64_t k_r = X.counts[tid];
+            S.cnt[(X.t_mod_p + tid) % P] = (uint32_t)(k_r < prm.n_g ? k_r : prm.n_g);
+        }
+        __syncthreads();
+        control_decide(A, prm, S, kCtrlUpdate);
+        return;
+    }
+    const uint32_t r = blockIdx.y;
+    const uint64_t q = (uint64_t)blockIdx.x * kFinishWG + tid;
+    float sq = 0.f;
+    if (q < X.stride) {
+        uint64_t have = X.counts[r];
+        have = have < prm.cap ? have : prm.cap;
+        const uint64_t j = (uint64_t)r * X.stride + q;
+        float v = 0.f;
+        if (q < have) {
+            if (r == X.rank) {
+                v = X.own_val[q];
+            } else {
+                const uint32_t i = X.idx_all[j];
+                if (i < prm.n_g) {
+                    v = A.e[i];
+                    A.e[i] = 0.0f;  // Alg. 1 line 17
+                    if (NORM) sq = v * v;
+                } else {
+                    atomicAdd(&A.st->bad_index, 1u);  // not a gradient index: skipped and reported
+                }
+            }
+        }
+        X.val_all[j] = v;  // Alg. 1 line 11
+    }
+    if (NORM) {
+        // the streaming pass counted these entries as residual: take them out again
+        double s = (double)sq;
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+        if ((tid & 63u) == 0 && s != 0.0) atomicAdd(&A.err_slots[(blockIdx.x + r) % kErrSlots], -s);
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -921,6 +1076,7 @@ __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_
         st->overflow = 0; st->moves = 0; st->t = 0;
         st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
         st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
+        st->own_actual = 0; st->own_emitted = 0; st->bad_index = 0; st->pad = 0;
     }
 }
 
@@ -944,6 +1100,7 @@ __global__ void k_restore_state(DevState *st, uint64_t t, float delta)
     st->overflow = 0; st->moves = 0; st->t = t;
     st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
     st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
+    st->own_actual = 0; st->own_emitted = 0; st->bad_index = 0; st->pad = 0;
 }
 
 __global__ void k_norm_finalize(DevState *st, const double *err_slots)
@@ -955,7 +1112,7 @@ __global__ void k_norm_finalize(DevState *st, const double *err_slots)
         if (threadIdx.x < d) s[threadIdx.x] += s[threadIdx.x + d];
         __syncthreads();
     }
-    if (threadIdx.x == 0) st->err_norm = sqrt(s[0]);
+    if (threadIdx.x == 0) st->err_norm = sqrt(s[0] > 0.0 ? s[0] : s[0] == s[0] ? 0.0 : s[0]);
 }
 
 }  // namespace
@@ -969,7 +1126,10 @@ struct exdyna_ctx {
     CtrlParams    prm;
     Layout        lay;
     uint64_t      n_b, cap;
-    uint64_t      t;  // iterations enqueued
+    uint64_t      t;  // iterations completed (enqueued)
+    uint32_t      phase;     // worker view: 1 between exdyna_worker_select and exdyna_worker_exchange
+    uint32_t      rank;      // worker view: the rank of the pending selection
+    uint32_t      own_part;  // partition the current selection pass compares, or kAllParts
     float        *d_residual;
     char         *ws;
     hipStream_t   stream;  // stream of the most recent call
@@ -1133,12 +1293,14 @@ void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
     for (uint32_t sh = 0; sh < 32; ++sh)
         if ((1u << sh) == A.gran_per_blk) A.gpb_shift = sh;
     A.parity = (uint32_t)(c->t & 1);
+    A.own_part = c->own_part;
+    A.cur_part = slot_part(c, c->t);
+    A.cur_pos = slot_pos(c, c->t);
     const uint32_t grid = (uint32_t)((c->lay.n_tiles + kWavesPerWG - 1) / kWavesPerWG);
     hipLaunchKernelGGL((k_stream<CMP, NORM, GT, SCALE>), dim3(grid), dim3(kStreamWG), 0, s, A);
 }
 
-template <bool NORM, int CMP>
-void launch_finish(exdyna_ctx *c, hipStream_t s)
+FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
 {
     const uint64_t t = c->t;
     FinishArgs A;
@@ -1170,6 +1332,16 @@ void launch_finish(exdyna_ctx *c, hipStream_t s)
     A.slots_min = c->lay.slots;
     A.pool_extra = c->lay.pool_extra;
     A.parity = (uint32_t)(t & 1);
+    A.mode = mode;
+    A.own_part = c->own_part;
+    A.gran_per_blk = c->cfg.block_size / kGran;
+    return A;
+}
+
+template <bool NORM, int CMP>
+void launch_finish(exdyna_ctx *c, uint32_t mode, hipStream_t s)
+{
+    const FinishArgs A = finish_args(c, mode);
     const uint32_t per_wg = kFinishWG / 64;
     const uint32_t grid = 1u + (uint32_t)((c->lay.n_chunks + per_wg - 1) / per_wg);
     hipLaunchKernelGGL((k_finish<NORM, CMP>), dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
@@ -1186,19 +1358,28 @@ void dispatch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
     }
 }
 
-// grad_dtype < 0: the unscaled fp32 path of exdyna_step (one add per gradient)
-int step_impl(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, void *hip_stream)
+// grad_dtype < 0: the unscaled fp32 path of exdyna_step (one add per gradient).
+// worker_rank < 0: one device plays every worker; otherwise only that worker's
+// partition is compared and the control stops at the own list's offsets.
+int step_impl(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, int64_t worker_rank,
+              void *hip_stream)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (!d_grad) return EXDYNA_ENULL;
     if (grad_dtype > EXDYNA_F16) return EXDYNA_EINVAL;
     if (grad_dtype >= 0 && !std::isfinite(eta)) return EXDYNA_EINVAL;
+    if (worker_rank >= (int64_t)c->cfg.n_parts) return EXDYNA_EINVAL;
     if ((uintptr_t)d_grad % 16 != 0) return EXDYNA_EALIGN;
+    if (c->phase != 0) return EXDYNA_ESTATE;  // a worker's selection is waiting for its exchange
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     c->stream = s;
     const bool norm = c->cfg.want_err_norm != 0;
     const bool prof = c->prof_slots != 0;
     hipEvent_t *ev = prof ? c->ev + 3 * (c->t % c->prof_slots) : nullptr;
+    const uint32_t P = c->cfg.n_parts;
+    // Alg. 3 line 29: the partition worker `rank` selects at iteration t
+    c->own_part = worker_rank < 0 ? kAllParts : (uint32_t)((c->t % P + (uint64_t)worker_rank) % P);
+    const uint32_t mode = worker_rank < 0 ? kCtrlFull : kCtrlSelect;
 
     if (prof) HIP_TRY(c, hipEventRecord(ev[0], s));
     switch (grad_dtype) {
@@ -1209,17 +1390,26 @@ int step_impl(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, void
     }
     if (prof) HIP_TRY(c, hipEventRecord(ev[1], s));
 
-    const uint64_t t = c->t;
     if (c->cfg.cmp_mode == 0) {
-        if (norm) launch_finish<true, 0>(c, s); else launch_finish<false, 0>(c, s);
+        if (norm) launch_finish<true, 0>(c, mode, s); else launch_finish<false, 0>(c, mode, s);
     } else {
-        if (norm) launch_finish<true, 1>(c, s); else launch_finish<false, 1>(c, s);
+        if (norm) launch_finish<true, 1>(c, mode, s); else launch_finish<false, 1>(c, mode, s);
     }
     if (prof) HIP_TRY(c, hipEventRecord(ev[2], s));
     HIP_TRY(c, hipGetLastError());
-    c->t = t + 1;
+    if (worker_rank < 0) {
+        c->t += 1;
+    } else {
+        c->rank = (uint32_t)worker_rank;
+        c->phase = 1;  // the iteration ends with exdyna_worker_exchange
+    }
     return EXDYNA_OK;
 }
+
+// Iteration whose selection the getters describe: the last finished one, or the
+// one whose worker-view selection is waiting for its exchange.
+bool have_iteration(const exdyna_ctx *c) { return c->t + c->phase > 0; }
+uint64_t last_iteration(const exdyna_ctx *c) { return c->t + c->phase - 1; }
 
 }  // namespace
 
@@ -1278,6 +1468,9 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
     c->n_b = n_b;
     c->cap = cap;
     c->t = 0;
+    c->phase = 0;
+    c->rank = 0;
+    c->own_part = kAllParts;
     c->d_residual = d_residual;
     c->ws = static_cast<char *>(d_workspace);
     c->stream = static_cast<hipStream_t>(hip_stream);
@@ -1332,13 +1525,56 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
 
 int exdyna_step(exdyna_ctx *c, const float *d_grad, void *hip_stream)
 {
-    return step_impl(c, d_grad, -1, 1.0f, hip_stream);
+    return step_impl(c, d_grad, -1, 1.0f, -1, hip_stream);
 }
 
 int exdyna_step_scaled(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, void *hip_stream)
 {
     if (grad_dtype < EXDYNA_F32) return c ? EXDYNA_EINVAL : EXDYNA_ENULL;
-    return step_impl(c, d_grad, grad_dtype, eta, hip_stream);
+    return step_impl(c, d_grad, grad_dtype, eta, -1, hip_stream);
+}
+
+int exdyna_worker_select(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, uint32_t rank,
+                         void *hip_stream)
+{
+    if (grad_dtype < EXDYNA_F32) return c ? EXDYNA_EINVAL : EXDYNA_ENULL;
+    return step_impl(c, d_grad, grad_dtype, eta, (int64_t)rank, hip_stream);
+}
+
+int exdyna_worker_exchange(exdyna_ctx *c, const uint32_t *d_idx_all, const uint64_t *d_counts_by_rank,
+                           uint64_t stride, float *d_val_all, void *hip_stream)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!d_counts_by_rank) return EXDYNA_ENULL;
+    if (stride > 0 && (!d_idx_all || !d_val_all)) return EXDYNA_ENULL;
+    if (stride > c->cfg.n_g) return EXDYNA_EINVAL;
+    if ((uintptr_t)d_counts_by_rank % 8 != 0 || (uintptr_t)d_idx_all % 4 != 0 ||
+        (uintptr_t)d_val_all % 4 != 0)
+        return EXDYNA_EALIGN;
+    if (c->phase != 1) return EXDYNA_ESTATE;  // no selection is waiting
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    c->stream = s;
+    const uint32_t P = c->cfg.n_parts;
+    const FinishArgs A = finish_args(c, kCtrlUpdate);
+    ExchangeArgs X;
+    X.idx_all = d_idx_all;
+    X.counts = d_counts_by_rank;
+    X.val_all = d_val_all;
+    X.own_val = at<float>(c, c->lay.out_val);
+    X.stride = stride;
+    X.rank = c->rank;
+    X.t_mod_p = (uint32_t)(c->t % P);
+    const uint64_t gx = (stride + kFinishWG - 1) / kFinishWG;
+    const dim3 grid((uint32_t)(gx ? gx : 1), P + 1);
+    if (c->cfg.want_err_norm)
+        hipLaunchKernelGGL((k_exchange<true>), grid, dim3(kFinishWG), 0, s, A, c->prm, X);
+    else
+        hipLaunchKernelGGL((k_exchange<false>), grid, dim3(kFinishWG), 0, s, A, c->prm, X);
+    HIP_TRY(c, hipGetLastError());
+    c->t += 1;
+    c->phase = 0;
+    c->own_part = kAllParts;
+    return EXDYNA_OK;
 }
 
 int exdyna_get_selected(exdyna_ctx *c, const uint32_t **d_idx, const float **d_val,
@@ -1353,8 +1589,8 @@ int exdyna_get_selected(exdyna_ctx *c, const uint32_t **d_idx, const float **d_v
         HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st,
                                   hipMemcpyDeviceToHost, c->stream));
         HIP_TRY(c, hipStreamSynchronize(c->stream));
-        if (h_k_actual) *h_k_actual = st.k_actual;
-        if (h_k_emitted) *h_k_emitted = st.k_emitted;
+        if (h_k_actual) *h_k_actual = st.own_actual;
+        if (h_k_emitted) *h_k_emitted = st.own_emitted;
     }
     return EXDYNA_OK;
 }
@@ -1364,10 +1600,11 @@ int exdyna_get_partitions(exdyna_ctx *c, int which, uint32_t *h_blk_pos, uint32_
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (which != 0 && which != 1) return EXDYNA_EINVAL;
-    if (which == 0 && c->t == 0) return EXDYNA_ESTATE;  // no step has selected yet
+    if (which == 0 && !have_iteration(c)) return EXDYNA_ESTATE;  // no step has selected yet
+    if (which == 1 && c->phase) return EXDYNA_ESTATE;  // the pending exchange computes it
     const uint32_t P = c->cfg.n_parts;
     // iteration whose topology is asked for
-    const uint64_t it = which == 0 ? c->t - 1 : c->t;
+    const uint64_t it = which == 0 ? last_iteration(c) : c->t;
     int32_t *tmp = static_cast<int32_t *>(malloc(2 * (size_t)P * sizeof(int32_t)));
     if (!tmp) return EXDYNA_ENOMEM;
     hipError_t e = hipMemcpyAsync(tmp, slot_part(c, it), 2 * (size_t)P * sizeof(int32_t),
@@ -1399,8 +1636,8 @@ int exdyna_get_block_counts(exdyna_ctx *c, uint32_t *h_counts)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (!h_counts) return EXDYNA_ENULL;
-    if (c->t == 0) return EXDYNA_ESTATE;
-    HIP_TRY(c, hipMemcpyAsync(h_counts, blk_cnt_of(c, c->t - 1), c->n_b * sizeof(uint32_t),
+    if (!have_iteration(c)) return EXDYNA_ESTATE;
+    HIP_TRY(c, hipMemcpyAsync(h_counts, blk_cnt_of(c, last_iteration(c)), c->n_b * sizeof(uint32_t),
                               hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return EXDYNA_OK;
@@ -1410,7 +1647,7 @@ int exdyna_get_part_counts(exdyna_ctx *c, uint64_t *h_counts)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (!h_counts) return EXDYNA_ENULL;
-    if (c->t == 0) return EXDYNA_ESTATE;
+    if (!have_iteration(c)) return EXDYNA_ESTATE;
     HIP_TRY(c, hipMemcpyAsync(h_counts, at<uint64_t>(c, c->lay.part_cnt),
                               c->cfg.n_parts * sizeof(uint64_t), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
@@ -1421,9 +1658,9 @@ int exdyna_get_stats(exdyna_ctx *c, exdyna_stats *h_out)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (!h_out) return EXDYNA_ENULL;
-    if (c->cfg.want_err_norm && c->t > 0)
+    if (c->cfg.want_err_norm && have_iteration(c))
         hipLaunchKernelGGL(k_norm_finalize, dim3(1), dim3(kErrSlots), 0, c->stream,
-                           at<DevState>(c, c->lay.state), err_slots_of(c, c->t - 1));
+                           at<DevState>(c, c->lay.state), err_slots_of(c, last_iteration(c)));
     DevState st;
     HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st, hipMemcpyDeviceToHost,
                               c->stream));
@@ -1434,11 +1671,13 @@ int exdyna_get_stats(exdyna_ctx *c, exdyna_stats *h_out)
     h_out->k_max_part = st.k_max_part;
     h_out->density_error = st.density_error;
     h_out->traffic_ratio = st.traffic_ratio;
-    h_out->err_norm = (c->cfg.want_err_norm && c->t > 0) ? st.err_norm : -1.0;
+    h_out->err_norm = (c->cfg.want_err_norm && have_iteration(c)) ? st.err_norm : -1.0;
     h_out->delta_used = st.delta_used;
     h_out->delta_next = st.delta_next;
     h_out->overflow = st.overflow;
     h_out->moves = st.moves;
+    h_out->bad_index = st.bad_index;
+    h_out->reserved = 0;
     return EXDYNA_OK;
 }
 
@@ -1476,6 +1715,7 @@ int exdyna_get_state(exdyna_ctx *c, void *h_state, size_t bytes)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (!h_state) return EXDYNA_ENULL;
+    if (c->phase) return EXDYNA_ESTATE;  // in the middle of a worker-view iteration
     const size_t P = c->cfg.n_parts;
     if (bytes < sizeof(StateHeader) + 2 * P * sizeof(int32_t)) return EXDYNA_ENOMEM;
     DevState st;
@@ -1524,6 +1764,8 @@ int exdyna_set_state(exdyna_ctx *c, const void *h_state, size_t bytes, void *hip
         drop_events_fwd(c);
     }
     c->t = h.t;
+    c->phase = 0;  // a selection waiting for its exchange is dropped
+    c->own_part = kAllParts;
     const Layout &L = c->lay;
     HIP_TRY(c, hipMemcpyAsync(slot_part(c, c->t), part, 2 * P * sizeof(int32_t),
                               hipMemcpyHostToDevice, s));

@@ -88,6 +88,8 @@ def test_init_and_step_argument_errors_without_a_gpu():
     assert not h.value
     assert L.exdyna_step(None, fake_res, None) == binding.EXDYNA_ENULL
     assert L.exdyna_step_scaled(None, fake_res, binding.EXDYNA_BF16, 1.0, None) == binding.EXDYNA_ENULL
+    assert L.exdyna_worker_select(None, fake_res, binding.EXDYNA_F32, 1.0, 0, None) == binding.EXDYNA_ENULL
+    assert L.exdyna_worker_exchange(None, fake_res, fake_res, 4, fake_res, None) == binding.EXDYNA_ENULL
     assert L.exdyna_get_stats(None, None) == binding.EXDYNA_ENULL
     assert L.exdyna_destroy(None) == binding.EXDYNA_ENULL
     assert L.exdyna_state_bytes(None, None) == binding.EXDYNA_ENULL
