@@ -49,6 +49,12 @@ def main() -> int:
                          "gradients with the learning rate fused in (10 instead of 12 B/gradient)")
     ap.add_argument("--eta", type=float, default=1.0 / 1024.0,
                     help="learning rate of the --grad-dtype bf16/f16 variant")
+    ap.add_argument("--worker-view", action="store_true",
+                    help="time one worker's iteration instead (exdyna_worker_select + "
+                         "exdyna_worker_exchange for rank 0).  All P workers are given the same "
+                         "gradient, so the gathered lists are the partitions' lists of a whole-step "
+                         "reference run, prepared before the clock starts; the worker's residual and "
+                         "threshold must end bit-equal to the reference's")
     ap.add_argument("--hbm-budget-gb", type=float, default=160.0,
                     help="HBM to spend on pre-generated gradient vectors")
     args = ap.parse_args()
@@ -146,6 +152,55 @@ def main() -> int:
         torch.cuda.synchronize()
         del ref
 
+    # ---- worker view: what the AllGather would deliver, for every iteration ----
+    gathered = None
+    if args.worker_view:
+        P = w.n_parts
+        ref_cfg = binding.default_config(n_g=w.n_g, block_size=w.block_size, n_parts=P,
+                                         density=w.density, threshold0=thr, max_selected=w.n_g)
+        ref = binding.ExDyna(ref_cfg, dev)
+        probe = binding.ExDyna(cfg, dev)
+        worker_cap = probe.capacity
+        probe.close()
+        del probe
+        gathered = []
+        max_elems = 0
+        for t in range(W + K):
+            gpu_step(ref, grads[t % n_vec])
+            idx, _, off, ka, ke = ref.get_selected()
+            assert ka == ke
+            offs = off.cpu().numpy()
+            lens = np.diff(offs)
+            if lens.max() > worker_cap:
+                print("bench.py: a worker's list exceeds the capacity; the reference run cannot "
+                      "stand in for the gather", file=sys.stderr)
+                return 1
+            stride = int(lens.max())
+            idx_all = torch.zeros((P, stride), dtype=torch.int32, device=dev)
+            counts = np.empty(P, np.int64)
+            for r in range(P):
+                p = (t % P + r) % P                      # Alg. 3 line 29
+                idx_all[r, :lens[p]] = idx[offs[p]:offs[p + 1]]
+                counts[r] = lens[p]
+            gathered.append((idx_all, torch.from_numpy(counts).to(dev)))
+            max_elems = max(max_elems, P * stride)
+        val_buf = torch.empty(max(max_elems, 1), dtype=torch.float32, device=dev)
+        ref_residual = ref.residual.clone()
+        ref_delta = ref.get_stats().delta_next
+        ref.close()
+        del ref
+        torch.cuda.empty_cache()
+
+        def gpu_step(ctx, g, _t=[0]):                    # noqa: F811 -- one worker's iteration
+            idx_all, counts = gathered[_t[0]]
+            _t[0] += 1
+            if scaled:
+                ctx.worker_select(g, 0, eta)
+            else:
+                ctx.worker_select(g, 0)
+            n = idx_all.numel()
+            ctx.worker_exchange(idx_all, counts, val_buf[:n].view(idx_all.shape))
+
     # ---- timed region ---------------------------------------------------------
     x = binding.ExDyna(cfg, dev)
     for t in range(W):
@@ -161,6 +216,12 @@ def main() -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
+    if args.worker_view:
+        same = (torch.equal(x.residual.view(torch.int32), ref_residual.view(torch.int32))
+                and x.get_stats().delta_next == ref_delta)
+        if not same:
+            print("bench.py: the worker's trajectory left the reference's", file=sys.stderr)
+            return 1
     ms_events = None
     if prof:
         ms_events = np.array([x.get_kernel_ms(t) for t in range(W, W + K)], dtype=np.float64)
@@ -177,7 +238,7 @@ def main() -> int:
         achieved = alg_bytes_per_elem * w.n_g / (ms[:, 0].mean() * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": None if scaled else MEASURED_TRAFFIC_BYTES.get(args.config),
+                    "traffic": None if (scaled or args.worker_view) else MEASURED_TRAFFIC_BYTES.get(args.config),
                     "alg_bytes_per_launch": alg_bytes_per_elem * w.n_g}
     out = {
         "metric": "gradient elements sparsified/sec",
@@ -196,6 +257,7 @@ def main() -> int:
                    "n_parts": w.n_parts, "density": w.density, "threshold0": thr,
                    "gradient_vectors_in_hbm": n_vec, "recycled": recycled,
                    "cmp": ">=", "grad_dtype": args.grad_dtype, "eta_fused": eta if scaled else None,
+                   "view": "worker rank 0: select + exchange" if args.worker_view else "whole step",
                    "parallelism": "1 GPU, P partitions as index ranges"},
         "hbm_roofline_pct_per_step": round(100.0 * step_bytes / (elapsed / K) / (HBM_PEAK_GBS * 1e9), 2),
         "step_alg_gb_per_s": round(step_bytes / (elapsed / K) / 1e9, 1),
