@@ -711,7 +711,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
         st->density_error = fabs(prm.k - (double)k_actual) / (double)prm.n_g;
         st->traffic_ratio = k_actual ? (double)P * (double)m_t / (double)k_actual : 0.0;
         st->t     = t_done + 1;  // counted on the device so that a captured graph can be replayed
-        st->moves = S.n_moves;
+        st->moves = prm.blk_move ? S.n_moves : 0u;  // blk_move = 0: the pairs decide, nothing moves
     }
 }
 

@@ -1,0 +1,87 @@
+#!/usr/bin/env python3
+"""Per-iteration trace of the sparsifier's own metrics on a synthetic workload.
+
+Runs the HIP library (never a CPU substitute) over a workload of
+paper_2402_13781_amd.synthetic and prints one CSV line per iteration:
+the actual density k'/n_g against the target d (Sec. 5.2's density plots), the
+density error of Eq. 6, the traffic ratio f(t) of Eq. 5, the threshold, and
+the number of boundary moves Alg. 3 made.  Two switches turn the paper's
+ablations on:
+
+  --static-partitions   blk_move = 0: coarse-grained, never rebalanced (Sec. 4.1)
+  --fixed-threshold     gamma = 0: the hard-threshold sparsifier of Sec. 3
+
+    python -m paper_2402_13781_amd.trace --config 5 --n-g 20000000 --steps 200
+"""
+from __future__ import annotations
+
+import argparse
+import sys
+
+
+def run_trace(workload, steps, device="cuda:0", static_partitions=False, fixed_threshold=False,
+              gamma=None, blk_move=None, out=None):
+    """Returns a list of dicts, one per iteration; also writes CSV lines to `out` if given."""
+    from . import binding, synthetic
+
+    src = synthetic.GradientSource(workload, device)
+    g = src.grad(0)
+    thr = synthetic.initial_threshold(g, workload.density)
+    kw = {}
+    if static_partitions:
+        kw["blk_move"] = 0
+    elif blk_move is not None:
+        kw["blk_move"] = blk_move
+    if fixed_threshold:
+        kw["gamma"] = 0.0
+    elif gamma is not None:
+        kw["gamma"] = gamma
+    cfg = binding.default_config(n_g=workload.n_g, block_size=workload.block_size,
+                                 n_parts=workload.n_parts, density=workload.density,
+                                 threshold0=thr, **kw)
+    x = binding.ExDyna(cfg, device)
+    rows = []
+    cols = ("t", "k_actual", "density", "density_error", "traffic_ratio", "delta_used", "moves",
+            "overflow")
+    if out is not None:
+        print(",".join(cols), file=out)
+    for t in range(steps):
+        if t:
+            g = src.grad(t, out=g)
+        x.step(g)
+        s = x.get_stats()
+        row = dict(t=t, k_actual=s.k_actual, density=s.k_actual / workload.n_g,
+                   density_error=s.density_error, traffic_ratio=s.traffic_ratio,
+                   delta_used=s.delta_used, moves=s.moves, overflow=s.overflow)
+        rows.append(row)
+        if out is not None:
+            print(",".join(f"{row[c]:.6g}" if isinstance(row[c], float) else str(row[c]) for c in cols),
+                  file=out, flush=True)
+    x.close()
+    return rows
+
+
+def main(argv=None) -> int:
+    from . import synthetic
+
+    ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
+    ap.add_argument("--config", type=int, default=5, choices=sorted(synthetic.WORKLOADS))
+    ap.add_argument("--n-g", type=int, default=0, help="scale the workload down to this many gradients")
+    ap.add_argument("--block-size", type=int, default=0)
+    ap.add_argument("--n-parts", type=int, default=0)
+    ap.add_argument("--steps", type=int, default=0, help="default: the workload's own iteration count")
+    ap.add_argument("--static-partitions", action="store_true")
+    ap.add_argument("--fixed-threshold", action="store_true")
+    ap.add_argument("--gamma", type=float, default=None)
+    ap.add_argument("--blk-move", type=int, default=None)
+    a = ap.parse_args(argv)
+    w = synthetic.WORKLOADS[a.config]
+    if a.n_g or a.block_size or a.n_parts:
+        w = w.scaled(a.n_g or w.n_g, a.block_size or None, a.n_parts or None)
+    run_trace(w, a.steps or w.iters, static_partitions=a.static_partitions,
+              fixed_threshold=a.fixed_threshold, gamma=a.gamma, blk_move=a.blk_move, out=sys.stdout)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
