@@ -228,14 +228,17 @@ int exdyna_state_bytes(const exdyna_ctx *ctx, size_t *h_bytes);
 int exdyna_get_state(exdyna_ctx *ctx, void *h_state, size_t bytes);
 int exdyna_set_state(exdyna_ctx *ctx, const void *h_state, size_t bytes, void *hip_stream);
 
-/* Per-kernel timing for benchmarks.  exdyna_set_profiling(ctx, n_slots) with
- * n_slots > 0 makes every later exdyna_step record HIP events around its two
- * kernels on the step's stream, into a ring of n_slots (<= 65536) event sets;
- * 0 turns it off.  exdyna_get_kernel_ms waits for iteration `iteration`
- * (0-based, one of the last n_slots enqueued since profiling was turned on)
- * and returns its durations in milliseconds: [0] the streaming pass, [1] the
- * finishing kernel (control + compaction). */
-int exdyna_set_profiling(exdyna_ctx *ctx, uint32_t n_slots);
+/* Per-kernel timing for benchmarks.  exdyna_set_profiling(ctx, n_slots, every)
+ * with n_slots > 0 makes later steps record HIP events around their two
+ * kernels on the step's stream: the iteration it is called before and every
+ * `every`-th (>= 1) after it, into a ring of n_slots (<= 65536) event sets;
+ * n_slots = 0 turns it off.  Recording costs a few microseconds per step (the
+ * event markers keep consecutive launches from overlapping), which is why a
+ * benchmark samples.  exdyna_get_kernel_ms waits for iteration `iteration`
+ * (0-based, a recorded one among the last n_slots recorded) and returns its
+ * durations in milliseconds: [0] the streaming pass, [1] the finishing kernel
+ * (control + compaction). */
+int exdyna_set_profiling(exdyna_ctx *ctx, uint32_t n_slots, uint32_t every);
 int exdyna_get_kernel_ms(exdyna_ctx *ctx, uint64_t iteration, float *h_ms2);
 
 const char *exdyna_strerror(int code);

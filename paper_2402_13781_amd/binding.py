@@ -82,7 +82,7 @@ def load() -> C.CDLL:
     L.exdyna_get_part_counts.argtypes = [vp, P(u64)]
     L.exdyna_get_stats.argtypes = [vp, P(Stats)]
     L.exdyna_get_dims.argtypes = [vp, P(u64), P(u64)]
-    L.exdyna_set_profiling.argtypes = [vp, u32]
+    L.exdyna_set_profiling.argtypes = [vp, u32, u32]
     L.exdyna_get_kernel_ms.argtypes = [vp, u64, P(C.c_float)]
     L.exdyna_state_bytes.argtypes = [vp, P(C.c_size_t)]
     L.exdyna_get_state.argtypes = [vp, vp, C.c_size_t]
@@ -303,8 +303,8 @@ class ExDyna:
         self._check(self._L.exdyna_set_state(self._h, buf, len(state), self._stream_ptr(stream)),
                     "exdyna_set_state")
 
-    def set_profiling(self, n_slots: int):
-        self._check(self._L.exdyna_set_profiling(self._h, int(n_slots)), "exdyna_set_profiling")
+    def set_profiling(self, n_slots: int, every: int = 1):
+        self._check(self._L.exdyna_set_profiling(self._h, int(n_slots), int(every)), "exdyna_set_profiling")
 
     def get_kernel_ms(self, iteration: int):
         """[streaming pass, finishing kernel] milliseconds of a profiled iteration."""

@@ -1135,6 +1135,7 @@ struct exdyna_ctx {
     hipStream_t   stream;  // stream of the most recent call
     uint32_t      prof_slots;  // 0 = profiling off
     uint64_t      prof_since;  // first iteration recorded with the current events
+    uint32_t      prof_every;  // every how many iterations events are recorded
     hipEvent_t   *ev;          // prof_slots x 3 events, slot = iteration % prof_slots
     char          hip_err[256];
 };
@@ -1374,8 +1375,8 @@ int step_impl(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, int6
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     c->stream = s;
     const bool norm = c->cfg.want_err_norm != 0;
-    const bool prof = c->prof_slots != 0;
-    hipEvent_t *ev = prof ? c->ev + 3 * (c->t % c->prof_slots) : nullptr;
+    const bool prof = c->prof_slots != 0 && (c->t - c->prof_since) % c->prof_every == 0;
+    hipEvent_t *ev = prof ? c->ev + 3 * (((c->t - c->prof_since) / c->prof_every) % c->prof_slots) : nullptr;
     const uint32_t P = c->cfg.n_parts;
     // Alg. 3 line 29: the partition worker `rank` selects at iteration t
     c->own_part = worker_rank < 0 ? kAllParts : (uint32_t)((c->t % P + (uint64_t)worker_rank) % P);
@@ -1475,6 +1476,7 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
     c->ws = static_cast<char *>(d_workspace);
     c->stream = static_cast<hipStream_t>(hip_stream);
     c->prof_slots = 0;
+    c->prof_every = 1;
     c->ev = nullptr;
     c->hip_err[0] = 0;
 
@@ -1801,10 +1803,10 @@ namespace {
 void drop_events_fwd(exdyna_ctx *c) { drop_events(c); }
 }  // namespace
 
-int exdyna_set_profiling(exdyna_ctx *c, uint32_t n_slots)
+int exdyna_set_profiling(exdyna_ctx *c, uint32_t n_slots, uint32_t every)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
-    if (n_slots > 65536) return EXDYNA_EINVAL;
+    if (n_slots > 65536 || (n_slots && every == 0)) return EXDYNA_EINVAL;
     if (c->prof_slots) {
         HIP_TRY(c, hipStreamSynchronize(c->stream));
         drop_events(c);
@@ -1822,6 +1824,7 @@ int exdyna_set_profiling(exdyna_ctx *c, uint32_t n_slots)
         }
     }
     c->prof_slots = n_slots;
+    c->prof_every = every;
     c->prof_since = c->t;
     return EXDYNA_OK;
 }
@@ -1831,10 +1834,13 @@ int exdyna_get_kernel_ms(exdyna_ctx *c, uint64_t iteration, float *h_ms2)
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (!h_ms2) return EXDYNA_ENULL;
     if (!c->prof_slots) return EXDYNA_ESTATE;
-    // only iterations enqueued while profiling was on and not yet overwritten
-    if (iteration >= c->t || iteration < c->prof_since || c->t - iteration > c->prof_slots)
-        return EXDYNA_EINVAL;
-    hipEvent_t *ev = c->ev + 3 * (iteration % c->prof_slots);
+    // only recorded iterations, enqueued while profiling was on and not yet overwritten
+    if (iteration >= c->t || iteration < c->prof_since) return EXDYNA_EINVAL;
+    if ((iteration - c->prof_since) % c->prof_every != 0) return EXDYNA_EINVAL;
+    const uint64_t sample = (iteration - c->prof_since) / c->prof_every;
+    const uint64_t latest = (c->t - 1 - c->prof_since) / c->prof_every;
+    if (latest - sample >= c->prof_slots) return EXDYNA_EINVAL;
+    hipEvent_t *ev = c->ev + 3 * (sample % c->prof_slots);
     HIP_TRY(c, hipEventSynchronize(ev[2]));
     for (int i = 0; i < 2; ++i) HIP_TRY(c, hipEventElapsedTime(&h_ms2[i], ev[i], ev[i + 1]));
     return EXDYNA_OK;
