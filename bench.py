@@ -58,6 +58,9 @@ def main() -> int:
                          "gradient, so the gathered lists are the partitions' lists of a whole-step "
                          "reference run, prepared before the clock starts; the worker's residual and "
                          "threshold must end bit-equal to the reference's")
+    ap.add_argument("--block-size", type=int, default=0,
+                    help="override the workload's block size b (any multiple of 32; multiples "
+                         "of 256 take the faster kernel variant)")
     ap.add_argument("--hbm-budget-gb", type=float, default=160.0,
                     help="HBM to spend on pre-generated gradient vectors")
     args = ap.parse_args()
@@ -77,6 +80,8 @@ def main() -> int:
     binding.load()   # fails loudly if the HIP library has not been built
     dev = torch.device("cuda:0")
     w = synthetic.WORKLOADS[args.config]
+    if args.block_size:
+        w = w.scaled(w.n_g, args.block_size)
     K, W = args.steps, args.warmup
     src = synthetic.GradientSource(w, dev)
 

@@ -56,8 +56,9 @@ typedef struct exdyna_ctx exdyna_ctx; /* opaque, host memory, library-owned */
  * fills this build's defaults. */
 typedef struct {
     uint64_t n_g;          /* number of gradients, 1 <= n_g < 2^32 (indices are u32)        */
-    uint32_t block_size;   /* b: gradients per block, > 0 and a multiple of 256 (Sec. 4.1;
-                              the paper's granularity is 32, one wavefront x float4 is 256)  */
+    uint32_t block_size;   /* b: gradients per block, > 0 and a multiple of 32 (Sec. 4.1,
+                              Alg. 2 line 2).  Multiples of 256 (one wavefront x float4)
+                              take the kernel variant with fewer counter updates           */
     uint32_t n_parts;      /* P = number of workers n, 1 <= P <= min(n_b, 1024)             */
     double   density;      /* d in (0, 1]; k = d * n_g is kept in fp64 (Sec. 1)             */
     float    threshold0;   /* delta_0 > 0, finite (Alg. 1 line 5)                           */
@@ -97,8 +98,8 @@ typedef struct {
 int exdyna_default_config(exdyna_config *cfg);
 
 /* Alg. 2 lines 1-2, for callers that think in a block count n_b: floor(n_g /
- * n_b) rounded down to the granularity `multiple` (the paper uses 32; this
- * library's kernels need 256).  Writes 0 when fewer than `multiple` gradients
+ * n_b) rounded down to the granularity `multiple` (the paper uses 32, which
+ * this library accepts; 256 selects its leaner kernel variant).  Writes 0 when fewer than `multiple` gradients
  * would fall in a block.  Host only. */
 int exdyna_block_size_from_nb(uint64_t n_g, uint64_t n_b, uint32_t multiple, uint32_t *h_block_size);
 

@@ -222,7 +222,18 @@ struct StreamArgs {
     uint32_t        own_part;
     const int32_t  *cur_part;
     const int32_t  *cur_pos;
+    uint32_t        block_size;  // b (the generic variant counts and masks by element index)
 };
+
+// Gradient range [lo, hi) of partition p, cut at n_g (Alg. 3 lines 30-31).
+__device__ __forceinline__ void partition_elems(const int32_t *part, const int32_t *pos, uint32_t p,
+                                                uint32_t block_size, uint32_t n_g, uint32_t &lo, uint32_t &hi)
+{
+    const uint64_t a = (uint64_t)(uint32_t)pos[p] * block_size;
+    const uint64_t b = (uint64_t)((uint32_t)pos[p] + (uint32_t)part[p]) * block_size;
+    lo = (uint32_t)(a < n_g ? a : n_g);
+    hi = (uint32_t)(b < n_g ? b : n_g);
+}
 
 // Granule range [lo, hi) of partition p: blocks are whole granules (b % 256 == 0).
 __device__ __forceinline__ void partition_granules(const int32_t *part, const int32_t *pos, uint32_t p,
@@ -233,7 +244,11 @@ __device__ __forceinline__ void partition_granules(const int32_t *part, const in
     hi = (ps + pn) * gran_per_blk;
 }
 
-template <int CMP, bool NORM, int GT, bool SCALE>
+// GEN: block sizes that are multiples of 32 but not of 256.  Block and partition
+// boundaries then fall inside granules (always between lanes: a lane's four
+// gradients share a 32-aligned group), so the comparison is masked per lane
+// and every lane adds its own selected gradients to its block's counter.
+template <int CMP, bool NORM, int GT, bool SCALE, bool GEN>
 __global__ void __launch_bounds__(kStreamWG)
 k_stream(StreamArgs A)
 {
@@ -248,8 +263,13 @@ k_stream(StreamArgs A)
     const bool     fast   = gran0 + kTileGran <= n_full;  // wave-uniform: no ragged end inside
     float nrm = 0.f;
     uint32_t g_lo = 0u, g_hi = 0xFFFFFFFFu;  // granules that are compared at all
-    if (A.own_part != kAllParts)
-        partition_granules(A.cur_part, A.cur_pos, A.own_part, A.gran_per_blk, g_lo, g_hi);
+    uint32_t e_lo = 0u, e_hi = 0xFFFFFFFFu;  // GEN: the same as a gradient range
+    if (A.own_part != kAllParts) {
+        if (GEN)
+            partition_elems(A.cur_part, A.cur_pos, A.own_part, A.block_size, A.n_g, e_lo, e_hi);
+        else
+            partition_granules(A.cur_part, A.cur_pos, A.own_part, A.gran_per_blk, g_lo, g_hi);
+    }
 
     if (live && fast) {
         f32x4    a[kTileGran];
@@ -271,7 +291,12 @@ k_stream(StreamArgs A)
                 a[u].w = accumulate<SCALE>(ev[u].w, gv[u].w, A.eta);
                 nib[u] = sel<CMP>(a[u].x, delta) | (sel<CMP>(a[u].y, delta) << 1) |
                          (sel<CMP>(a[u].z, delta) << 2) | (sel<CMP>(a[u].w, delta) << 3);
-                if (gran0 + u < g_lo || gran0 + u >= g_hi) nib[u] = 0u;  // wave-uniform: another worker's partition
+                if (GEN) {
+                    const uint32_t i0 = ((gran0 + u) << 8) + lane * 4u;
+                    if (i0 < e_lo || i0 >= e_hi) nib[u] = 0u;
+                } else if (gran0 + u < g_lo || gran0 + u >= g_hi) {
+                    nib[u] = 0u;  // wave-uniform: another worker's partition
+                }
             }
         }
 
@@ -315,7 +340,14 @@ k_stream(StreamArgs A)
             } else {
                 word = total | kFlag;  // too many for the slots: compaction re-reads this tile
             }
-            if (lane == 0) {
+            if (GEN) {
+#pragma unroll
+                for (uint32_t u = 0; u < kTileGran; ++u)
+                    if (nib[u])
+                        atomicAdd(&A.blk_cnt[(((gran0 + u) << 8) + lane * 4u) / A.block_size],
+                                  (uint32_t)__popc(nib[u]));
+                if (lane == 0) atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
+            } else if (lane == 0) {
                 // One counter per block / segment keeps same-address atomics rare (they
                 // serialise at roughly 150 ns each across the dies).
                 if (A.one_counter) {
@@ -357,7 +389,8 @@ k_stream(StreamArgs A)
         for (uint32_t u = 0; u < kTileGran; ++u) {
             const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
             uint32_t f = 0;
-            const bool mine = gran0 + u >= g_lo && gran0 + u < g_hi;  // wave-uniform
+            const bool mine = GEN ? (base >= e_lo && base < e_hi)
+                                  : (gran0 + u >= g_lo && gran0 + u < g_hi);  // wave-uniform unless GEN
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q) {
                 if (base + q < A.n_g) {
@@ -370,7 +403,11 @@ k_stream(StreamArgs A)
             }
             uint32_t cu, below;
             granule_ranks(f, cu, below);
-            if (cu && lane == 0) atomicAdd(&A.blk_cnt[(gran0 + u) / A.gran_per_blk], cu);  // = its segment if one_counter
+            if (GEN) {
+                if (f) atomicAdd(&A.blk_cnt[(uint32_t)base / A.block_size], (uint32_t)__popc(f));
+            } else if (cu && lane == 0) {
+                atomicAdd(&A.blk_cnt[(gran0 + u) / A.gran_per_blk], cu);  // = its segment if one_counter
+            }
             total += cu;
         }
         if (lane == 0) {
@@ -418,7 +455,7 @@ struct FinishArgs {
     uint32_t        n_tiles, n_chunks, n_segs, seg_shift, chunk_shift, slots_min, pool_extra, parity;
     uint32_t        mode;            // kCtrlFull or kCtrlSelect
     uint32_t        own_part;        // worker view: the partition that was compared; else kAllParts
-    uint32_t        gran_per_blk;
+    uint32_t        block_size;
 };
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
@@ -737,7 +774,7 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 template <bool NORM, int CMP>
 __device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32_t tile, uint64_t r0,
                                                      float delta, uint32_t lane, uint32_t n_g,
-                                                     uint64_t cap, uint32_t g_lo, uint32_t g_hi,
+                                                     uint64_t cap, uint32_t e_lo, uint32_t e_hi,
                                                      float &spill)
 {
     if (!NORM && r0 >= cap) return;  // nothing fits: the tile stays in the residual as it is
@@ -766,7 +803,7 @@ __device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32
     for (uint32_t u = 0; u < kTileGran; ++u) {
         const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
         nib[u] = 0;
-        if (gran0 + u >= g_lo && gran0 + u < g_hi) {  // the streaming pass compared only these
+        if (base >= e_lo && base < e_hi) {  // the streaming pass compared only these (a lane's four share a block)
 #pragma unroll
             for (uint32_t q = 0; q < 4; ++q)
                 if (base + q < n_g) nib[u] |= sel<CMP>(v[u][q], delta) << q;
@@ -934,16 +971,16 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
     }
 
     uint64_t flagged = __ballot((word & kFlag) != 0);
-    uint32_t g_lo = 0u, g_hi = 0xFFFFFFFFu;
+    uint32_t e_lo = 0u, e_hi = 0xFFFFFFFFu;
     if (flagged && A.own_part != kAllParts)
-        partition_granules(A.cur_part, A.cur_pos, A.own_part, A.gran_per_blk, g_lo, g_hi);
+        partition_elems(A.cur_part, A.cur_pos, A.own_part, A.block_size, n_g, e_lo, e_hi);
     while (flagged) {  // wave-uniform
         const uint32_t l = (uint32_t)__ffsll((unsigned long long)flagged) - 1u;
         flagged &= flagged - 1u;
         const uint32_t lo = __shfl((uint32_t)r0, l, 64), hi = __shfl((uint32_t)(r0 >> 32), l, 64);
         const float    dl = __shfl(delta, l, 64);
         compact_flagged_tile<NORM, CMP>(A, (chunk << cs) + l, ((uint64_t)hi << 32) | lo, dl, lane,
-                                        n_g, cap, g_lo, g_hi, spill);
+                                        n_g, cap, e_lo, e_hi, spill);
     }
 
     if (NORM) {
@@ -1145,7 +1182,7 @@ namespace {
 int validate_config(const exdyna_config *c, uint64_t *n_b_out, uint64_t *cap_out)
 {
     if (c->n_g == 0 || c->n_g > 0xFFFFFFFFull) return EXDYNA_EINVAL;
-    if (c->block_size == 0 || c->block_size % kGran != 0) return EXDYNA_EINVAL;
+    if (c->block_size == 0 || c->block_size % 32 != 0) return EXDYNA_EINVAL;
     const uint64_t n_b = (c->n_g + c->block_size - 1) / c->block_size;
     if (c->n_parts == 0 || c->n_parts > n_b || c->n_parts > kMaxParts) return EXDYNA_EINVAL;
     if (!(c->density > 0.0 && c->density <= 1.0)) return EXDYNA_EINVAL;
@@ -1271,7 +1308,7 @@ double *err_slots_of(exdyna_ctx *c, uint64_t t) { return at<double>(c, c->lay.er
 uint2 *slot_tab_of(exdyna_ctx *c, uint64_t t) { return at<uint2>(c, c->lay.slot_tab) + (t & 1) * c->lay.n_tiles; }
 uint32_t *seg_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.seg_cnt) + (t & 1) * c->lay.n_segs; }
 
-template <int CMP, bool NORM, int GT, bool SCALE>
+template <int CMP, bool NORM, int GT, bool SCALE, bool GEN>
 void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
 {
     StreamArgs A;
@@ -1297,8 +1334,9 @@ void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
     A.own_part = c->own_part;
     A.cur_part = slot_part(c, c->t);
     A.cur_pos = slot_pos(c, c->t);
+    A.block_size = c->cfg.block_size;
     const uint32_t grid = (uint32_t)((c->lay.n_tiles + kWavesPerWG - 1) / kWavesPerWG);
-    hipLaunchKernelGGL((k_stream<CMP, NORM, GT, SCALE>), dim3(grid), dim3(kStreamWG), 0, s, A);
+    hipLaunchKernelGGL((k_stream<CMP, NORM, GT, SCALE, GEN>), dim3(grid), dim3(kStreamWG), 0, s, A);
 }
 
 FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
@@ -1335,7 +1373,7 @@ FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
     A.parity = (uint32_t)(t & 1);
     A.mode = mode;
     A.own_part = c->own_part;
-    A.gran_per_blk = c->cfg.block_size / kGran;
+    A.block_size = c->cfg.block_size;
     return A;
 }
 
@@ -1348,15 +1386,24 @@ void launch_finish(exdyna_ctx *c, uint32_t mode, hipStream_t s)
     hipLaunchKernelGGL((k_finish<NORM, CMP>), dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
 }
 
-template <int GT, bool SCALE>
-void dispatch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
+template <int GT, bool SCALE, bool GEN>
+void dispatch_stream2(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
 {
     const bool norm = c->cfg.want_err_norm != 0;
     if (c->cfg.cmp_mode == 0) {
-        if (norm) launch_stream<0, true, GT, SCALE>(c, g, eta, s); else launch_stream<0, false, GT, SCALE>(c, g, eta, s);
+        if (norm) launch_stream<0, true, GT, SCALE, GEN>(c, g, eta, s); else launch_stream<0, false, GT, SCALE, GEN>(c, g, eta, s);
     } else {
-        if (norm) launch_stream<1, true, GT, SCALE>(c, g, eta, s); else launch_stream<1, false, GT, SCALE>(c, g, eta, s);
+        if (norm) launch_stream<1, true, GT, SCALE, GEN>(c, g, eta, s); else launch_stream<1, false, GT, SCALE, GEN>(c, g, eta, s);
     }
+}
+
+template <int GT, bool SCALE>
+void dispatch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
+{
+    if (c->cfg.block_size % kGran != 0)
+        dispatch_stream2<GT, SCALE, true>(c, g, eta, s);   // blocks are not whole granules
+    else
+        dispatch_stream2<GT, SCALE, false>(c, g, eta, s);
 }
 
 // grad_dtype < 0: the unscaled fp32 path of exdyna_step (one add per gradient).

@@ -54,7 +54,7 @@ def test_workspace_bytes_accepts_the_five_configurations():
 
 
 @pytest.mark.parametrize("bad", [
-    dict(n_g=0), dict(n_g=1 << 32), dict(block_size=0), dict(block_size=32), dict(block_size=300),
+    dict(n_g=0), dict(n_g=1 << 32), dict(block_size=0), dict(block_size=48), dict(block_size=300),
     dict(n_parts=0), dict(n_parts=4097), dict(n_g=1 << 22, n_parts=1025), dict(density=0.0),
     dict(density=1.01), dict(density=float("nan")), dict(threshold0=0.0), dict(threshold0=-1.0),
     dict(threshold0=float("inf")), dict(threshold0=float("nan")), dict(cmp_mode=2),
