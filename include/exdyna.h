@@ -195,6 +195,16 @@ int exdyna_worker_exchange(exdyna_ctx *ctx, const uint32_t *d_idx_all,
 int exdyna_get_selected(exdyna_ctx *ctx, const uint32_t **d_idx, const float **d_val,
                         const uint64_t **d_part_off, uint64_t *h_k_actual, uint64_t *h_k_emitted);
 
+/* Device addresses of the two counts exdyna_get_selected copies to the host
+ * (k_actual: gradients that passed the comparison in the last selection pass,
+ * k_emitted: pairs written), for callers that feed them to a collective or a
+ * kernel without a host round trip -- in the worker view k_actual is the
+ * k_{i,t} the AllGather of Alg. 1 line 10 carries.  The pointers stay valid for
+ * the life of the context; the values are rewritten by every selection pass.
+ * Host only, does not synchronise. */
+int exdyna_get_count_pointers(exdyna_ctx *ctx, const uint64_t **d_k_actual,
+                              const uint64_t **d_k_emitted);
+
 /* Topology (Alg. 2 / Alg. 3): which = 0 is what the last step selected with,
  * which = 1 what the next step will select with.  Host arrays of P entries
  * each; any may be NULL.  h_elem_end is clamped to n_g (the last block may be

@@ -21,7 +21,7 @@ EXDYNA_OK, EXDYNA_EINVAL, EXDYNA_ENULL, EXDYNA_EALIGN, EXDYNA_ESTATE, EXDYNA_ENO
 SYMBOLS = (
     "exdyna_default_config", "exdyna_block_size_from_nb", "exdyna_workspace_bytes", "exdyna_init",
     "exdyna_step", "exdyna_step_scaled", "exdyna_worker_select", "exdyna_worker_exchange",
-    "exdyna_get_selected", "exdyna_get_partitions", "exdyna_get_block_counts",
+    "exdyna_get_selected", "exdyna_get_count_pointers", "exdyna_get_partitions", "exdyna_get_block_counts",
     "exdyna_get_part_counts", "exdyna_get_stats", "exdyna_get_dims", "exdyna_set_profiling",
     "exdyna_get_kernel_ms", "exdyna_state_bytes", "exdyna_get_state", "exdyna_set_state",
     "exdyna_strerror", "exdyna_last_hip_error", "exdyna_destroy",
@@ -77,6 +77,7 @@ def load() -> C.CDLL:
     L.exdyna_worker_select.argtypes = [vp, vp, C.c_int, C.c_float, u32, vp]
     L.exdyna_worker_exchange.argtypes = [vp, vp, vp, u64, vp, vp]
     L.exdyna_get_selected.argtypes = [vp, P(vp), P(vp), P(vp), P(u64), P(u64)]
+    L.exdyna_get_count_pointers.argtypes = [vp, P(vp), P(vp)]
     L.exdyna_get_partitions.argtypes = [vp, C.c_int, P(u32), P(u32), P(u64), P(u64), P(u32)]
     L.exdyna_get_block_counts.argtypes = [vp, P(u32)]
     L.exdyna_get_part_counts.argtypes = [vp, P(u64)]
@@ -256,6 +257,15 @@ class ExDyna:
         val = self._view(pv.value, ke.value, torch.float32)
         off = self._view(po.value, self.P + 1, torch.int64)
         return idx, val, off, ka.value, ke.value
+
+    def count_tensors(self):
+        """exdyna_get_count_pointers as two 1-element int64 views of the workspace: (k_actual, k_emitted)
+        of the last selection pass, readable on the device without a host round trip."""
+        torch = self._torch
+        pa, pe = C.c_void_p(), C.c_void_p()
+        self._check(self._L.exdyna_get_count_pointers(self._h, C.byref(pa), C.byref(pe)),
+                    "exdyna_get_count_pointers")
+        return self._view(pa.value, 1, torch.int64), self._view(pe.value, 1, torch.int64)
 
     def get_partitions(self, which: int = 0):
         """exdyna_get_partitions: dict of numpy arrays (blk_pos, blk_part, elem_start, elem_end, owner_rank)."""

@@ -31,6 +31,21 @@
 //              Control and compaction read the same finished counters and do
 //              not depend on each other, so they overlap inside one launch.
 //
+// Variants of the same two kernels: gradients stored as fp32, bf16 or fp16 with
+// the learning rate applied inside the accumulate (Alg. 1 line 7 as printed);
+// block sizes that are multiples of 32 but not of 256 (per-lane masks and
+// counters instead of per-granule ones); and the "worker view", in which one
+// context is one worker of Alg. 1: k_stream compares only inside the partition
+// that worker owns at this iteration (Alg. 3 lines 29-31), k_finish stops at
+// the offsets of the worker's own list, and after the caller's AllGather a
+// third kernel finishes the iteration:
+//
+//   k_exchange rows r < P: read this worker's acc at rank r's gathered indices
+//              into the value buffer the AllReduce will sum, and clear them
+//              (Alg. 1 lines 11 and 17).  Row P: the control workgroup on the
+//              gathered counts, moved from rank to partition order (Alg. 3
+//              lines 2-7) -- the same Alg. 5 / Alg. 3 code as in k_finish.
+//
 // Partitions are contiguous and ascending (Sec. 4.1), so the concatenation of
 // the per-partition index lists in partition order is the global ascending
 // list: a pair's output position is the number of selected gradients in front
@@ -1641,6 +1656,15 @@ int exdyna_get_selected(exdyna_ctx *c, const uint32_t **d_idx, const float **d_v
         if (h_k_actual) *h_k_actual = st.own_actual;
         if (h_k_emitted) *h_k_emitted = st.own_emitted;
     }
+    return EXDYNA_OK;
+}
+
+int exdyna_get_count_pointers(exdyna_ctx *c, const uint64_t **d_k_actual, const uint64_t **d_k_emitted)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    DevState *st = at<DevState>(c, c->lay.state);
+    if (d_k_actual) *d_k_actual = &st->own_actual;
+    if (d_k_emitted) *d_k_emitted = &st->own_emitted;
     return EXDYNA_OK;
 }
 

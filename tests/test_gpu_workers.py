@@ -38,7 +38,10 @@ def _iteration(ctxs, w, grads, t, tag, check_norm=False):
     idx_all = torch.full((n, stride), -1, dtype=torch.int32, device=DEV)
     for r, (idx, _, ke) in enumerate(lists):
         idx_all[r, :ke] = idx
-    counts_dev = torch.tensor(counts, dtype=torch.int64, device=DEV)
+    # the counts as a collective would see them: straight from device memory
+    counts_dev = torch.cat([x.count_tensors()[0] for x in ctxs]).contiguous()
+    assert counts_dev.tolist() == counts
+    assert [int(x.count_tensors()[1]) for x in ctxs] == [ke for _, _, ke in lists]
     vals = []
     for x in ctxs:
         val_all = torch.full((n, stride), float("nan"), dtype=torch.float32, device=DEV)
@@ -135,6 +138,21 @@ def test_workers_dense_tiles_and_capacity():
     # d = 0.05: many tiles select more than their staging slots hold (re-read path, also on
     # partition boundaries); a small capacity cuts every worker's list
     _run(120_000 + 5, 256, 5, 0.05, 7, "workers dense", max_selected=700)
+
+
+def test_workers_at_the_full_size_of_a_configuration():
+    # cfg 2 as it stands (n_g = 11,689,512, b = 4096, 8 workers), each worker its own gradient
+    wl = synthetic.WORKLOADS[2]
+    src = synthetic.GradientSource(wl, DEV)
+    n = wl.n_parts
+    thr = synthetic.initial_threshold(src.grad(0), wl.density)
+    ctxs, w = _make(wl.n_g, wl.block_size, n, wl.density, thr)
+    for t in range(3):
+        grads = [src.grad(t * n + i) for i in range(n)]
+        counts = _iteration(ctxs, w, grads, t, "workers cfg2")
+        log(f"  [workers cfg2] t={t} k_i={counts} ok")
+    for x in ctxs:
+        x.close()
 
 
 def test_one_worker_view_equals_the_whole_step():
