@@ -947,28 +947,40 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
         const uint32_t *__restrict__ incl_w  = s_incl[wave];
         const uint32_t *__restrict__ off_w = s_off[wave];
         const uint32_t *__restrict__ rel_w = s_rel[wave];
-        // four pairs per lane and trip, so that four independent loads are in flight
-        for (uint32_t j0 = lane; j0 < tots; j0 += 256u) {
-            uint2    pr[4];
-            uint32_t rr[4];
+        // kCopy pairs per lane and trip.  The searches of one trip run side by side,
+        // step by step (six LDS reads each, one after the other), and so do the loads
+        // of the pairs they find.
+        constexpr uint32_t kCopy = 8;
+        for (uint32_t j0 = lane; j0 < tots; j0 += 64u * kCopy) {
+            uint32_t pos[kCopy];
 #pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) {
+            for (uint32_t q = 0; q < kCopy; ++q) pos[q] = 0u;
+            // first tile with incl_w[tile] > j: incl_w is non-decreasing over all 64
+            // entries and incl_w[63] = tots > j, so the answer is in [0, 63]
+#pragma unroll
+            for (uint32_t step = 32u; step >= 1u; step >>= 1) {
+#pragma unroll
+                for (uint32_t q = 0; q < kCopy; ++q) {
+                    const uint32_t j = j0 + q * 64u;
+                    if (incl_w[pos[q] + step - 1u] <= j) pos[q] += step;
+                }
+            }
+            uint2    pr[kCopy];
+            uint32_t rr[kCopy];
+#pragma unroll
+            for (uint32_t q = 0; q < kCopy; ++q) {
                 const uint32_t j = j0 + q * 64u;
                 pr[q] = make_uint2(0u, 0u);
                 rr[q] = 0;
                 if (j < tots) {
-                    uint32_t lo = 0, hi = 63;
-                    while (lo < hi) {  // first tile with incl_w[tile] > j
-                        const uint32_t mid = (lo + hi) >> 1;
-                        if (incl_w[mid] > j) hi = mid; else lo = mid + 1;
-                    }
-                    const uint32_t within = j - (lo ? incl_w[lo - 1] : 0u);
-                    pr[q] = stage[off_w[lo] + within];
-                    rr[q] = rel_w[lo] + within;
+                    const uint32_t t      = pos[q];
+                    const uint32_t within = j - (t ? incl_w[t - 1u] : 0u);
+                    pr[q] = stage[off_w[t] + within];
+                    rr[q] = rel_w[t] + within;
                 }
             }
 #pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) {
+            for (uint32_t q = 0; q < kCopy; ++q) {
                 if (j0 + q * 64u < tots) {
                     const uint64_t r = base + rr[q];
                     if (r < cap) {
