@@ -9,8 +9,9 @@
  *   residual = acc with the emitted entries zeroed (Alg. 1 lines 17-18)
  *   delta   <- online threshold scaling           (Alg. 5, Sec. 4.4)
  *   topology <- adjacent-partition rebalancing    (Alg. 3 lines 8-28, Sec. 4.2)
- * The collectives of Alg. 1 (lines 10, 12) and the model update (line 16) are
- * not part of this library.  The "worker view" calls further down split the
+ * The collectives of Alg. 1 (lines 10, 12) are not part of this library; the
+ * model update of line 16 is available for the selected entries as
+ * exdyna_apply_update.  The "worker view" calls further down split the
  * iteration at those collectives for callers that have one context per worker.
  *
  * Conventions
@@ -184,6 +185,21 @@ int exdyna_worker_select(exdyna_ctx *ctx, const void *d_grad, int grad_dtype, fl
 int exdyna_worker_exchange(exdyna_ctx *ctx, const uint32_t *d_idx_all,
                            const uint64_t *d_counts_by_rank, uint64_t stride, float *d_val_all,
                            void *hip_stream);
+
+/* Alg. 1 line 16 restricted to the selected entries: for every listed index i,
+ * d_model[i] <- fl(d_model[i] - fl(scale * value)), scale = 1/n in the paper
+ * (two fp32 roundings, no fused multiply-add).  d_idx / d_val: n_rows rows of
+ * `stride` entries each (indices and the values to apply, e.g. the gathered
+ * list and the all-reduced buffer of the worker view, or, with n_rows = 1 and
+ * stride = capacity, the whole step's own output); row r uses its first
+ * min(d_counts[r], capacity, stride) entries.  d_counts: n_rows uint64 in device
+ * memory (exdyna_get_count_pointers gives one for the context's own list).
+ * d_model: n_g floats.  Indices must not repeat (they do not in the library's
+ * own lists: partitions are disjoint); an index >= n_g is skipped and counted
+ * in exdyna_stats.bad_index.  One kernel, asynchronous.  1 <= n_rows <= 1024. */
+int exdyna_apply_update(exdyna_ctx *ctx, float *d_model, const uint32_t *d_idx, const float *d_val,
+                        const uint64_t *d_counts, uint32_t n_rows, uint64_t stride, float scale,
+                        void *hip_stream);
 
 /* Results of the last step.  *d_idx / *d_val: device arrays of k_emitted
  * ascending gradient indices and the accumulated values at them (Alg. 1 lines

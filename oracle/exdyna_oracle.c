@@ -595,3 +595,15 @@ double exo_workers_traffic_ratio(const exo_workers *s)
         if (s->k_rank[i] > m) m = s->k_rank[i];
     return (double)s->n * (double)m / (double)s->k_actual;
 }
+
+/* Alg. 1 line 16 on the entries that were sent: x[idx_t] <- x[idx_t] - (1/n) g_t.
+ * `scale` is the 1/n of the paper as an fp32 number; the product is rounded
+ * to fp32, then the difference is. */
+void exo_apply_update(float *x, const uint32_t *idx_t, const float *g_t, uint64_t len, float scale)
+{
+    for (uint64_t j = 0; j < len; ++j) {
+        float p = scale * g_t[j];
+        float v = x[idx_t[j]] - p;
+        x[idx_t[j]] = v;
+    }
+}

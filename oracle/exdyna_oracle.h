@@ -144,6 +144,10 @@ const int64_t  *exo_workers_blk_pos(const exo_workers *s, int which);
 double          exo_workers_err_norm(const exo_workers *s, uint32_t i); /* Eq. 1; i == n: the mean */
 double          exo_workers_traffic_ratio(const exo_workers *s);        /* Eq. 5 */
 
+/* Alg. 1 line 16 restricted to the sent entries: x[idx_t[j]] -= scale * g_t[j]
+ * (scale = 1/n; fp32 product, then fp32 difference). */
+void exo_apply_update(float *x, const uint32_t *idx_t, const float *g_t, uint64_t len, float scale);
+
 #ifdef __cplusplus
 }
 #endif

@@ -77,6 +77,8 @@ def _load():
         fn = getattr(L, name)
         fn.restype = P(i64)
         fn.argtypes = [vp, C.c_int]
+    L.exo_apply_update.restype = None
+    L.exo_apply_update.argtypes = [P(f32), P(u32), P(f32), u64, f32]
     L.exo_reindex.restype = None
     L.exo_reindex.argtypes = [P(f64), u32, u64, P(f64)]
     L.exo_workers_create.restype = vp
@@ -147,6 +149,16 @@ def scale_factor(k, k_actual, beta, gamma) -> float:
 
 def estimate(k, k_actual, delta, beta, gamma) -> float:
     return float(_load().exo_estimate(k, k_actual, np.float32(delta), beta, gamma))
+
+
+def apply_update(x: np.ndarray, idx_t: np.ndarray, g_t: np.ndarray, scale: float):
+    """Alg. 1 line 16 on the sent entries, in place on the float32 array x."""
+    assert x.dtype == np.float32 and x.flags.c_contiguous
+    idx = np.ascontiguousarray(idx_t, np.uint32)
+    g = np.ascontiguousarray(g_t, np.float32)
+    assert idx.size == g.size
+    _load().exo_apply_update(_ptr(x, C.c_float), _ptr(idx, C.c_uint32), _ptr(g, C.c_float), idx.size,
+                             np.float32(scale))
 
 
 def reindex(k_rank, t: int):

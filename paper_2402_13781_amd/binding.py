@@ -21,7 +21,7 @@ EXDYNA_OK, EXDYNA_EINVAL, EXDYNA_ENULL, EXDYNA_EALIGN, EXDYNA_ESTATE, EXDYNA_ENO
 SYMBOLS = (
     "exdyna_default_config", "exdyna_block_size_from_nb", "exdyna_workspace_bytes", "exdyna_init",
     "exdyna_step", "exdyna_step_scaled", "exdyna_worker_select", "exdyna_worker_exchange",
-    "exdyna_get_selected", "exdyna_get_count_pointers", "exdyna_get_partitions", "exdyna_get_block_counts",
+    "exdyna_apply_update", "exdyna_get_selected", "exdyna_get_count_pointers", "exdyna_get_partitions", "exdyna_get_block_counts",
     "exdyna_get_part_counts", "exdyna_get_stats", "exdyna_get_dims", "exdyna_set_profiling",
     "exdyna_get_kernel_ms", "exdyna_state_bytes", "exdyna_get_state", "exdyna_set_state",
     "exdyna_strerror", "exdyna_last_hip_error", "exdyna_destroy",
@@ -77,6 +77,7 @@ def load() -> C.CDLL:
     L.exdyna_worker_select.argtypes = [vp, vp, C.c_int, C.c_float, u32, vp]
     L.exdyna_worker_exchange.argtypes = [vp, vp, vp, u64, vp, vp]
     L.exdyna_get_selected.argtypes = [vp, P(vp), P(vp), P(vp), P(u64), P(u64)]
+    L.exdyna_apply_update.argtypes = [vp, vp, vp, vp, vp, u32, u64, C.c_float, vp]
     L.exdyna_get_count_pointers.argtypes = [vp, P(vp), P(vp)]
     L.exdyna_get_partitions.argtypes = [vp, C.c_int, P(u32), P(u32), P(u64), P(u64), P(u32)]
     L.exdyna_get_block_counts.argtypes = [vp, P(u32)]
@@ -257,6 +258,23 @@ class ExDyna:
         val = self._view(pv.value, ke.value, torch.float32)
         off = self._view(po.value, self.P + 1, torch.int64)
         return idx, val, off, ka.value, ke.value
+
+    def apply_update(self, model, idx, val, counts, scale: float, stream=None):
+        """exdyna_apply_update: model[idx] -= scale * val for the first counts[r] entries of every row.
+        idx int32 [rows, stride], val float32 [rows, stride], counts int64 [rows], all on the device."""
+        torch = self._torch
+        if model.dtype != torch.float32 or model.numel() != self.cfg.n_g or not model.is_contiguous() \
+                or model.device != self.device:
+            raise ValueError("model must be a contiguous fp32 tensor of n_g elements on the context's device")
+        if idx.dim() != 2 or idx.dtype != torch.int32 or not idx.is_contiguous() or val.shape != idx.shape \
+                or val.dtype != torch.float32 or not val.is_contiguous() or counts.dtype != torch.int64 \
+                or counts.numel() != idx.shape[0] or not counts.is_contiguous():
+            raise ValueError("idx int32 [rows, stride], val float32 [rows, stride], counts int64 [rows], contiguous")
+        rows, stride = int(idx.shape[0]), int(idx.shape[1])
+        self._check(self._L.exdyna_apply_update(
+            self._h, C.c_void_p(model.data_ptr()), C.c_void_p(idx.data_ptr() if stride else None),
+            C.c_void_p(val.data_ptr() if stride else None), C.c_void_p(counts.data_ptr()), rows, stride,
+            float(scale), self._stream_ptr(stream)), "exdyna_apply_update")
 
     def count_tensors(self):
         """exdyna_get_count_pointers as two 1-element int64 views of the workspace: (k_actual, k_emitted)

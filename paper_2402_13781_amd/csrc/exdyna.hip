@@ -1102,6 +1102,30 @@ k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
 }
 
 // ---------------------------------------------------------------------------
+// Alg. 1 line 16 on the selected entries only: x[idx] <- x[idx] - scale * g_t,
+// one thread per entry of a rows x stride list (the layout of the exchange).
+__global__ void __launch_bounds__(256)
+k_apply(float *x, const uint32_t *idx, const float *val, const uint64_t *counts, uint64_t stride,
+        uint64_t cap, uint32_t n_g, float scale, DevState *st)
+{
+#pragma clang fp contract(off)
+    const uint32_t r = blockIdx.y;
+    const uint64_t q = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= stride) return;
+    uint64_t have = counts[r];
+    have = have < cap ? have : cap;
+    if (q >= have) return;
+    const uint64_t j = (uint64_t)r * stride + q;
+    const uint32_t i = idx[j];
+    if (i >= n_g) {
+        atomicAdd(&st->bad_index, 1u);
+        return;
+    }
+    const float p = scale * val[j];  // rounded before the subtraction
+    x[i] = x[i] - p;
+}
+
+// ---------------------------------------------------------------------------
 // small set-up / read-out kernels
 
 __global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n)
@@ -1650,6 +1674,27 @@ int exdyna_worker_exchange(exdyna_ctx *c, const uint32_t *d_idx_all, const uint6
     c->t += 1;
     c->phase = 0;
     c->own_part = kAllParts;
+    return EXDYNA_OK;
+}
+
+int exdyna_apply_update(exdyna_ctx *c, float *d_model, const uint32_t *d_idx, const float *d_val,
+                        const uint64_t *d_counts, uint32_t n_rows, uint64_t stride, float scale,
+                        void *hip_stream)
+{
+    if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
+    if (!d_model || !d_counts) return EXDYNA_ENULL;
+    if (stride > 0 && (!d_idx || !d_val)) return EXDYNA_ENULL;
+    if (n_rows == 0 || n_rows > kMaxParts || stride > c->cfg.n_g || !std::isfinite(scale)) return EXDYNA_EINVAL;
+    if ((uintptr_t)d_model % 4 != 0 || (uintptr_t)d_idx % 4 != 0 || (uintptr_t)d_val % 4 != 0 ||
+        (uintptr_t)d_counts % 8 != 0)
+        return EXDYNA_EALIGN;
+    if (stride == 0) return EXDYNA_OK;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    c->stream = s;
+    const dim3 grid((uint32_t)((stride + 255) / 256), n_rows);
+    hipLaunchKernelGGL(k_apply, grid, dim3(256), 0, s, d_model, d_idx, d_val, d_counts, stride,
+                       (uint64_t)c->cap, (uint32_t)c->cfg.n_g, scale, at<DevState>(c, c->lay.state));
+    HIP_TRY(c, hipGetLastError());
     return EXDYNA_OK;
 }
 

@@ -92,6 +92,7 @@ def test_init_and_step_argument_errors_without_a_gpu():
     assert L.exdyna_worker_exchange(None, fake_res, fake_res, 4, fake_res, None) == binding.EXDYNA_ENULL
     assert L.exdyna_get_stats(None, None) == binding.EXDYNA_ENULL
     assert L.exdyna_get_count_pointers(None, None, None) == binding.EXDYNA_ENULL
+    assert L.exdyna_apply_update(None, fake_res, fake_res, fake_res, fake_res, 1, 4, 1.0, None) == binding.EXDYNA_ENULL
     assert L.exdyna_destroy(None) == binding.EXDYNA_ENULL
     assert L.exdyna_state_bytes(None, None) == binding.EXDYNA_ENULL
     assert L.exdyna_get_state(None, None, 0) == binding.EXDYNA_ENULL

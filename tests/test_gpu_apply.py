@@ -1,0 +1,121 @@
+"""exdyna_apply_update (Alg. 1 line 16 on the selected entries) against the oracle."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2402_13781_amd import binding, synthetic
+from tests.parity import bits, log
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def test_whole_step_output_applied_to_a_model():
+    """One device: the step's own list and values, its count read from device memory."""
+    n_g, b, P, d = 400_000 + 9, 1024, 8, 0.01
+    wl = synthetic.WORKLOADS[3].scaled(n_g, b, P)
+    src = synthetic.GradientSource(wl, DEV)
+    thr = synthetic.initial_threshold(src.grad(0), d)
+    x = binding.ExDyna(binding.default_config(n_g=n_g, block_size=b, n_parts=P, density=d, threshold0=thr), DEV)
+    o = oracle.Oracle(n_g, b, P, d, thr)
+    model = torch.randn(n_g, device=DEV)
+    ref = model.cpu().numpy().copy()
+    scale = 0.125
+    for t in range(4):
+        g = src.grad(t)
+        x.step(g)
+        idx, val, _, ka, ke = x.get_selected()
+        cap = x.capacity
+        # the full-capacity views of the output arrays, as a caller without the host count has them
+        idx_all = x._view(idx.data_ptr(), cap, torch.int32).view(1, cap)
+        val_all = x._view(val.data_ptr(), cap, torch.float32).view(1, cap)
+        x.apply_update(model, idx_all, val_all, x.count_tensors()[1], scale)
+        o.step(g.cpu().numpy())
+        oracle.apply_update(ref, o.out_idx(), o.out_val(), scale)
+        assert np.array_equal(bits(model.cpu().numpy()), bits(ref)), t
+        log(f"  [apply whole-step] t={t} k={ke} ok")
+    assert x.get_stats().bad_index == 0
+    x.close()
+
+
+def test_gathered_list_applied_and_argument_checks():
+    n_g, n = 100_000, 3
+    x = binding.ExDyna(binding.default_config(n_g=n_g, block_size=256, n_parts=n, density=0.01,
+                                              threshold0=1.0), DEV)
+    rng = np.random.default_rng(6)
+    stride = 500
+    counts = np.array([500, 0, 123], np.int64)
+    idx = np.full((n, stride), 0xFFFFFFFF, np.uint32)          # padding must not be dereferenced
+    val = rng.normal(0, 2, (n, stride)).astype(np.float32)
+    picks = rng.choice(n_g, 623, replace=False).astype(np.uint32)
+    idx[0, :500] = picks[:500]
+    idx[2, :123] = picks[500:]
+    idx[2, 7] = n_g                                             # one bad index inside a row
+    model = torch.randn(n_g, device=DEV)
+    ref = model.cpu().numpy().copy()
+    x.apply_update(model, torch.from_numpy(idx.view(np.int32)).to(DEV), torch.from_numpy(val).to(DEV),
+                   torch.from_numpy(counts).to(DEV), -0.3)
+    good0 = np.arange(500)
+    good2 = np.array([j for j in range(123) if j != 7])
+    oracle.apply_update(ref, idx[0, good0], val[0, good0], -0.3)
+    oracle.apply_update(ref, idx[2, good2], val[2, good2], -0.3)
+    assert np.array_equal(bits(model.cpu().numpy()), bits(ref))
+    assert x.get_stats().bad_index == 1
+
+    L = binding.load()
+    m, i, v, c = (C.c_void_p(p) for p in (model.data_ptr(), 0x1000, 0x2000, 0x3000))
+    assert L.exdyna_apply_update(None, m, i, v, c, 1, 4, 1.0, None) == binding.EXDYNA_ENULL
+    assert L.exdyna_apply_update(x._h, None, i, v, c, 1, 4, 1.0, None) == binding.EXDYNA_ENULL
+    assert L.exdyna_apply_update(x._h, m, None, v, c, 1, 4, 1.0, None) == binding.EXDYNA_ENULL
+    assert L.exdyna_apply_update(x._h, m, i, v, None, 1, 4, 1.0, None) == binding.EXDYNA_ENULL
+    assert L.exdyna_apply_update(x._h, m, i, v, c, 0, 4, 1.0, None) == binding.EXDYNA_EINVAL
+    assert L.exdyna_apply_update(x._h, m, i, v, c, 1025, 4, 1.0, None) == binding.EXDYNA_EINVAL
+    assert L.exdyna_apply_update(x._h, m, i, v, c, 1, n_g + 1, 1.0, None) == binding.EXDYNA_EINVAL
+    assert L.exdyna_apply_update(x._h, m, i, v, c, 1, 4, float("nan"), None) == binding.EXDYNA_EINVAL
+    assert L.exdyna_apply_update(x._h, m, C.c_void_p(0x1002), v, c, 1, 4, 1.0, None) == binding.EXDYNA_EALIGN
+    assert L.exdyna_apply_update(x._h, m, None, None, c, 1, 0, 1.0, None) == binding.EXDYNA_OK   # nothing to do
+    x.close()
+
+
+def test_all_of_algorithm_1_with_three_workers():
+    """Lines 7-18 in order, the test standing in for the two collectives: select, gather,
+    exchange, reduce, model update; the three model replicas stay bit-equal to the oracle's."""
+    n_g, b, n, d = 180_000 + 11, 512, 3, 0.01
+    wl = synthetic.WORKLOADS[4].scaled(n_g, b, n)
+    src = synthetic.GradientSource(wl, DEV)
+    thr = synthetic.initial_threshold(src.grad(0), d)
+    cfg = binding.default_config(n_g=n_g, block_size=b, n_parts=n, density=d, threshold0=thr)
+    ctxs = [binding.ExDyna(cfg, DEV) for _ in range(n)]
+    w = oracle.Workers(n_g, b, n, d, thr)
+    x0 = torch.randn(n_g, device=DEV)
+    models = [x0.clone() for _ in range(n)]
+    ref = x0.cpu().numpy().copy()
+    scale = float(np.float32(1.0 / n))
+    for t in range(6):
+        grads = [src.grad(t * n + i) for i in range(n)]
+        for i, c in enumerate(ctxs):
+            c.worker_select(grads[i], i)                                   # lines 7-9
+        counts = torch.cat([c.count_tensors()[0] for c in ctxs]).contiguous()
+        emitted = [int(c.count_tensors()[1]) for c in ctxs]
+        stride = max(emitted)
+        idx_all = torch.zeros((n, stride), dtype=torch.int32, device=DEV)  # line 10
+        for r, c in enumerate(ctxs):
+            idx_all[r, :emitted[r]] = c.get_selected()[0]
+        total = torch.zeros((n, stride), dtype=torch.float32, device=DEV)
+        for c in ctxs:
+            v = torch.empty((n, stride), dtype=torch.float32, device=DEV)
+            c.worker_exchange(idx_all, counts, v)                          # lines 11, 13-15, 17-18
+            total += v                                                     # line 12, rank order
+        for c, m in zip(ctxs, models):
+            c.apply_update(m, idx_all, total, counts, scale)               # line 16
+        w.step([g.cpu().numpy() for g in grads])
+        oracle.apply_update(ref, w.idx(), w.sum(), scale)
+        for i, m in enumerate(models):
+            assert np.array_equal(bits(m.cpu().numpy()), bits(ref)), (t, i)
+            assert np.array_equal(bits(ctxs[i].residual.cpu().numpy()), bits(w.residual(i, copy=False))), (t, i)
+        log(f"  [algorithm 1] t={t} k'={w.k_actual} ok")
+    for c in ctxs:
+        c.close()

@@ -193,3 +193,57 @@ def test_per_worker_capacity_keeps_the_rest_in_that_workers_residual():
     assert np.array_equal(w.idx()[:50], own0[:50])
     e0 = w.residual(0)
     assert np.array_equal(e0[own0[50:]], g[0][own0[50:]])       # not sent: kept
+
+
+def test_apply_update_equals_the_dense_update_with_zeros_elsewhere():
+    """Alg. 1 line 16, x <- x - (1/n) g_t, where g_t is zero except at idx_t: the dense numpy
+    expression and the sparse routine must agree bit for bit, and untouched entries stay."""
+    rng = np.random.default_rng(4)
+    n_g, n = 5000, 4
+    x = rng.normal(0, 1, n_g).astype(np.float32)
+    idx = rng.choice(n_g, 300, replace=False).astype(np.uint32)
+    g = rng.normal(0, 3, 300).astype(np.float32)
+    scale = np.float32(1.0 / n)
+    dense = np.zeros(n_g, np.float32)
+    dense[idx] = g
+    want = (x - scale * dense).astype(np.float32)
+    got = x.copy()
+    oracle.apply_update(got, idx, g, scale)
+    assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+    untouched = np.setdiff1d(np.arange(n_g), idx)
+    assert np.array_equal(got[untouched].view(np.uint32), x[untouched].view(np.uint32))
+    # scale 1 and g = x[idx]: the entries cancel exactly
+    z = x.copy()
+    oracle.apply_update(z, idx, x[idx], 1.0)
+    assert not z[idx].any() and not np.signbit(z[idx]).any()
+
+
+def test_apply_update_rounds_the_product_before_the_difference():
+    scale, g, x0 = np.float32(1.4099537), np.float32(1.5942448), np.float32(1.3154374)
+    fused = np.float32(float(x0) - float(scale) * float(g))      # what an FMA would round
+    two_step = np.float32(x0 - np.float32(scale * g))
+    assert fused != two_step
+    x = np.full(8, x0, np.float32)
+    oracle.apply_update(x, np.array([2, 5], np.uint32), np.array([g, g], np.float32), scale)
+    assert x[2] == two_step and x[5] == two_step and x[0] == x0
+
+
+def test_model_update_over_a_workers_iteration():
+    """Lines 12 and 16 together on a small case: x - (1/n) * sum_i acc_i[idx_t], dense in numpy."""
+    n_g, b, n = 2048, 128, 4
+    rng = np.random.default_rng(8)
+    grads = _grads(rng, n, n_g, 1.0)
+    w = oracle.Workers(n_g, b, n, 0.02, 2.5)
+    w.step(grads)
+    idx = w.idx()
+    assert idx.size > 0 and np.unique(idx).size == idx.size      # partitions are disjoint: no repeats
+    total = np.zeros(n_g, np.float32)
+    sent = np.zeros(n_g, bool)
+    sent[idx] = True
+    for i in range(n):                                             # rank-order sum of acc_i = g_i at t = 0
+        total = np.where(sent, (total + grads[i]).astype(np.float32) if i else grads[i], 0).astype(np.float32)
+    x0 = rng.normal(0, 1, n_g).astype(np.float32)
+    want = (x0 - np.float32(1.0 / n) * total).astype(np.float32)
+    x = x0.copy()
+    oracle.apply_update(x, idx, w.sum(), 1.0 / n)
+    assert np.array_equal(x.view(np.uint32), want.view(np.uint32))
