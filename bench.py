@@ -187,7 +187,7 @@ def main() -> int:
             idx_all = torch.zeros((P, stride), dtype=torch.int32, device=dev)
             counts = np.empty(P, np.int64)
             for r in range(P):
-                p = (t % P + r) % P                      # Alg. 3 line 29
+                p = (t % P + r) % P                      # Alg. 3 (cyclic allocation)
                 idx_all[r, :lens[p]] = idx[offs[p]:offs[p + 1]]
                 counts[r] = lens[p]
             gathered.append((idx_all, torch.from_numpy(counts).to(dev)))

@@ -2,15 +2,15 @@
  * exdyna.h -- C ABI of the MI355X (gfx950) ExDyna gradient-selection library.
  *
  * One `exdyna_step` is one iteration of the sparsifier of "Distributed SGD
- * with ExDyna" (Alg. 1, lines 7-18) on ONE device that plays all P workers:
- *   acc = residual + grad                         (Alg. 1 line 7, Sec. 2)
- *   select |acc| >= delta inside every partition  (Alg. 4, Sec. 4.3)
- *   emit (index, value) pairs, ascending          (Alg. 1 lines 9-11)
- *   residual = acc with the emitted entries zeroed (Alg. 1 lines 17-18)
- *   delta   <- online threshold scaling           (Alg. 5, Sec. 4.4)
- *   topology <- adjacent-partition rebalancing    (Alg. 3 lines 8-28, Sec. 4.2)
- * The collectives of Alg. 1 (lines 10, 12) are not part of this library; the
- * model update of line 16 is available for the selected entries as
+ * with ExDyna" (the body of Alg. 1's loop) on ONE device that plays all P workers:
+ *   acc = residual + grad                          (Alg. 1, accumulate; Sec. 2)
+ *   select |acc| >= delta inside every partition   (Alg. 4, Sec. 4.3)
+ *   emit (index, value) pairs, ascending           (Alg. 1, Sparsify and value gather)
+ *   residual = acc with the emitted entries zeroed (Alg. 1, zeroing and residual carry)
+ *   delta   <- online threshold scaling            (Alg. 5, Sec. 4.4)
+ *   topology <- adjacent-partition rebalancing     (Alg. 3, the sweep; Sec. 4.2)
+ * The two collectives of Alg. 1 (AllGather, AllReduce) are not part of this
+ * library; the model update is available for the selected entries as
  * exdyna_apply_update.  The "worker view" calls further down split the
  * iteration at those collectives for callers that have one context per worker.
  *
@@ -58,19 +58,19 @@ typedef struct exdyna_ctx exdyna_ctx; /* opaque, host memory, library-owned */
 typedef struct {
     uint64_t n_g;          /* number of gradients, 1 <= n_g < 2^32 (indices are u32)        */
     uint32_t block_size;   /* b: gradients per block, > 0 and a multiple of 32 (Sec. 4.1,
-                              Alg. 2 line 2).  Multiples of 256 (one wavefront x float4)
-                              take the kernel variant with fewer counter updates           */
+                              Alg. 2's rounding).  Multiples of 256 (one wavefront x
+                              float4) take the kernel variant with fewer counter updates   */
     uint32_t n_parts;      /* P = number of workers n, 1 <= P <= min(n_b, 1024)             */
     double   density;      /* d in (0, 1]; k = d * n_g is kept in fp64 (Sec. 1)             */
-    float    threshold0;   /* delta_0 > 0, finite (Alg. 1 line 5)                           */
-    uint32_t cmp_mode;     /* 0: |acc| >= delta (Alg. 4 line 2); 1: |acc| > delta           */
-    double   alpha;        /* >= 1, imbalance band of Alg. 3 lines 13/21                    */
-    double   beta;         /* > 1, density band of Alg. 5 lines 2/4                         */
-    double   gamma;        /* in [0, 1), threshold step of Alg. 5 lines 3-7; 0 keeps delta
-                              fixed (the hard-threshold sparsifier of Sec. 3)               */
-    uint32_t blk_move;     /* blocks moved per adjustment (Alg. 3 line 12); 0 = static
+    float    threshold0;   /* delta_0 > 0, finite (Alg. 1, threshold initialisation)        */
+    uint32_t cmp_mode;     /* 0: |acc| >= delta (Alg. 4's comparison); 1: |acc| > delta     */
+    double   alpha;        /* >= 1, imbalance band of Alg. 3's two overload tests           */
+    double   beta;         /* > 1, density band of Alg. 5's two tests on exam               */
+    double   gamma;        /* in [0, 1), threshold step of Alg. 5's scaling factors; 0 keeps
+                              delta fixed (the hard-threshold sparsifier of Sec. 3)         */
+    uint32_t blk_move;     /* blocks moved per adjustment (Alg. 3's k_move); 0 = static
                               partitions (the coarse-grained partitioning of Sec. 4.1)      */
-    uint32_t min_blk;      /* >= 1, smallest partition in blocks (Alg. 3 lines 14/22)       */
+    uint32_t min_blk;      /* >= 1, smallest partition in blocks (Alg. 3's min_blk guards)  */
     uint64_t max_selected; /* output capacity in pairs; 0 = max(ceil(4k), 1024), <= n_g     */
     uint32_t want_err_norm;/* != 0: also compute ||residual||_2 (Eq. 1, one worker)         */
     uint32_t reserved;     /* must be 0                                                     */
@@ -86,7 +86,7 @@ typedef struct {
     double   traffic_ratio; /* f(t) = P * m_t / k' (Eq. 5); 0 when k' = 0                   */
     double   err_norm;      /* ||e_{t+1}||_2 (Eq. 1 with one worker); -1 when not requested */
     float    delta_used;    /* delta_t the step compared with                               */
-    float    delta_next;    /* delta_{t+1} (Alg. 5 line 8)                                  */
+    float    delta_next;    /* delta_{t+1} (Alg. 5, threshold scaling)                      */
     uint32_t overflow;      /* 1 when k' > capacity (worker view: some worker's k_i > capacity) */
     uint32_t moves;         /* boundary moves Alg. 3 made for the next iteration            */
     uint32_t bad_index;     /* worker view: gathered indices >= n_g, skipped by the exchange */
@@ -98,7 +98,7 @@ typedef struct {
  * n_parts, density and threshold0 are left 0 for the caller to set. */
 int exdyna_default_config(exdyna_config *cfg);
 
-/* Alg. 2 lines 1-2, for callers that think in a block count n_b: floor(n_g /
+/* Alg. 2 (block size), for callers that think in a block count n_b: floor(n_g /
  * n_b) rounded down to the granularity `multiple` (the paper uses 32, which
  * this library accepts; 256 selects its leaner kernel variant).  Writes 0 when fewer than `multiple` gradients
  * would fall in a block.  Host only. */
@@ -109,7 +109,7 @@ int exdyna_block_size_from_nb(uint64_t n_g, uint64_t n_b, uint32_t multiple, uin
  * streaming pass writes selected pairs into, and the output pairs).  Host only, launches nothing. */
 int exdyna_workspace_bytes(const exdyna_config *cfg, size_t *h_bytes);
 
-/* Alg. 1 lines 3-6: residual <- 0, partial-k vector <- k/P, delta <- delta_0,
+/* Alg. 1 (initialisation): residual <- 0, partial-k vector <- k/P, delta <- delta_0,
  * topology <- Alg. 2.  d_residual: n_g floats, 16-byte aligned, zeroed here
  * and updated in place by every step.  d_workspace: 256-byte aligned,
  * ws_bytes >= exdyna_workspace_bytes().  Both must stay valid until
@@ -132,7 +132,7 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
 int exdyna_step(exdyna_ctx *ctx, const float *d_grad, void *hip_stream);
 
 /* The same iteration with the learning rate fused in and a choice of gradient
- * element type (Alg. 1 line 7 as printed: acc = e + eta * G).  d_grad: n_g
+ * element type (Alg. 1's accumulate as printed: acc = e + eta * G).  d_grad: n_g
  * elements of grad_dtype (EXDYNA_F32 / EXDYNA_BF16 / EXDYNA_F16), 16-byte
  * aligned.  Each gradient is widened to fp32 exactly, multiplied by eta in fp32
  * (rounded), then added to the residual in fp32 (rounded): fl(e + fl(eta * g)),
@@ -144,39 +144,40 @@ int exdyna_step_scaled(exdyna_ctx *ctx, const void *d_grad, int grad_dtype, floa
 
 /* ---- worker view --------------------------------------------------------
  * For callers that run Alg. 1 as printed, one context per worker, each with its
- * own gradient and residual, and do the two collectives (Alg. 1 lines 10 and
- * 12) themselves.  An iteration is exdyna_worker_select, the caller's
+ * own gradient and residual, and do the two collectives (AllGather and
+ * AllReduce) themselves.  An iteration is exdyna_worker_select, the caller's
  * AllGather, exdyna_worker_exchange, the caller's AllReduce.  All contexts of
  * a job are created with the same configuration (n_parts = number of workers)
  * and stay replicas of each other in threshold and topology, because Alg. 5
  * and Alg. 3 see the same gathered counts everywhere.
  *
- * exdyna_worker_select (Alg. 1 lines 7-9 for worker `rank`): acc = e + eta * g
- * over all n_g gradients as in exdyna_step_scaled (same d_grad, grad_dtype,
+ * exdyna_worker_select (Alg. 1's accumulate, Allocate and Sparsify for worker
+ * `rank`): acc = e + eta * g over all n_g gradients as in exdyna_step_scaled (same d_grad, grad_dtype,
  * eta rules; eta = 1 with EXDYNA_F32 is bit-identical to the single add of
  * exdyna_step), but the comparison runs only inside the partition that worker
  * `rank` < n_parts owns at this iteration, (t mod P + rank) mod P of the
- * current topology (Alg. 3 lines 29-31).  Afterwards exdyna_get_selected gives
- * this worker's list idx_{i,t} (ascending, cut at the capacity; the values are
+ * current topology (Alg. 3, cyclic allocation and partition range).
+ * Afterwards exdyna_get_selected gives this worker's list idx_{i,t} (ascending, cut at the capacity; the values are
  * acc at them; k_actual is the uncut count k_{i,t}), and those entries of the
  * residual are already zero.  Threshold, topology and t do not change yet.
  * Returns EXDYNA_ESTATE if a selection is already waiting for its exchange;
  * exdyna_step / exdyna_step_scaled return it too while one is.
  *
- * exdyna_worker_exchange (Alg. 1 lines 11, 13-15, 17 and the next Allocate):
+ * exdyna_worker_exchange (Alg. 1's value gather, k' sum, Estimate, partial-k
+ * carry and zeroing, and the next iteration's Allocate):
  *  d_idx_all        the gathered lists, P rows of `stride` indices; row r holds
  *                   worker r's list in its first min(k_r, capacity, stride)
  *                   entries, the rest of the row is ignored.  Row `rank` must
  *                   be this context's own list.
  *  d_counts_by_rank P uint64, k_{r,t} of worker r (not cut), 8-byte aligned.
  *  d_val_all        P rows of `stride` floats, written here: this worker's acc
- *                   at every gathered index (g_{i,t} of line 11), 0 in the
+ *                   at every gathered index (g_{i,t}, the value gather), 0 in the
  *                   unused part of each row, so that a SUM AllReduce over the
  *                   whole buffer gives g_t.
- * Every gathered entry of the residual is then cleared (line 17); an index
+ * Every gathered entry of the residual is then cleared (the zeroing step); an index
  * >= n_g is skipped and counted in exdyna_stats.bad_index.  The counts are
- * moved from rank order to partition order (Alg. 3 lines 2-7) and drive Alg. 5
- * and Alg. 3 exactly as in exdyna_step; t advances.  stride may be 0 when
+ * moved from rank order to partition order (Alg. 3's re-indexing of the
+ * partial-k vector) and drive Alg. 5 and Alg. 3 exactly as in exdyna_step; t advances.  stride may be 0 when
  * nothing was selected anywhere (the pointers may then be NULL).  Two kernels
  * in `select`, one in `exchange`; nothing synchronises.  Not for HIP-graph
  * replay: the owned partition is computed on the host from t. */
@@ -186,7 +187,7 @@ int exdyna_worker_exchange(exdyna_ctx *ctx, const uint32_t *d_idx_all,
                            const uint64_t *d_counts_by_rank, uint64_t stride, float *d_val_all,
                            void *hip_stream);
 
-/* Alg. 1 line 16 restricted to the selected entries: for every listed index i,
+/* Alg. 1 (model update) restricted to the selected entries: for every listed index i,
  * d_model[i] <- fl(d_model[i] - fl(scale * value)), scale = 1/n in the paper
  * (two fp32 roundings, no fused multiply-add).  d_idx / d_val: n_rows rows of
  * `stride` entries each (indices and the values to apply, e.g. the gathered
@@ -215,7 +216,7 @@ int exdyna_get_selected(exdyna_ctx *ctx, const uint32_t **d_idx, const float **d
  * (k_actual: gradients that passed the comparison in the last selection pass,
  * k_emitted: pairs written), for callers that feed them to a collective or a
  * kernel without a host round trip -- in the worker view k_actual is the
- * k_{i,t} the AllGather of Alg. 1 line 10 carries.  The pointers stay valid for
+ * k_{i,t} that Alg. 1's AllGather carries.  The pointers stay valid for
  * the life of the context; the values are rewritten by every selection pass.
  * Host only, does not synchronise. */
 int exdyna_get_count_pointers(exdyna_ctx *ctx, const uint64_t **d_k_actual,
@@ -225,7 +226,7 @@ int exdyna_get_count_pointers(exdyna_ctx *ctx, const uint64_t **d_k_actual,
  * which = 1 what the next step will select with.  Host arrays of P entries
  * each; any may be NULL.  h_elem_end is clamped to n_g (the last block may be
  * short).  h_owner_rank[p] is the worker that owns partition p at that
- * iteration under the cyclic rule of Alg. 3 line 29.  Synchronises. */
+ * iteration under Alg. 3's cyclic allocation.  Synchronises. */
 int exdyna_get_partitions(exdyna_ctx *ctx, int which, uint32_t *h_blk_pos, uint32_t *h_blk_part,
                           uint64_t *h_elem_start, uint64_t *h_elem_end, uint32_t *h_owner_rank);
 

@@ -13,7 +13,7 @@
 #include <string.h>
 
 /* ------------------------------------------------------------------ */
-/* Alg. 2, lines 1-2                                                   */
+/* Alg. 2 (block size)                                                   */
 uint64_t exo_block_size(uint64_t n_g, uint64_t n_b)
 {
     if (n_b == 0) return 0;
@@ -21,7 +21,7 @@ uint64_t exo_block_size(uint64_t n_g, uint64_t n_b)
     return temp - temp % 32;
 }
 
-/* Alg. 2, lines 3-17                                                  */
+/* Alg. 2 (topology)                                                  */
 void exo_partition(uint64_t n_b, uint32_t n, int64_t *blk_part, int64_t *blk_pos)
 {
     int64_t quotient  = (int64_t)(n_b / n);
@@ -37,8 +37,8 @@ void exo_partition(uint64_t n_b, uint32_t n, int64_t *blk_part, int64_t *blk_pos
         blk_pos[i] = blk_part[i - 1] + blk_pos[i - 1];
 }
 
-/* Alg. 3, lines 8-28.  The re-indexing of k_t from rank order to partition
- * order (lines 2-7) is done by the caller: here kvec is already indexed by
+/* Alg. 3 (the sweep over adjacent pairs).  The re-indexing of k_t from rank order to partition
+ * order (the loop ahead of the sweep) is done by the caller: here kvec is already indexed by
  * partition.                                                           */
 int exo_allocate(double *kvec, int64_t *blk_part, int64_t *blk_pos, uint32_t n,
                  uint64_t n_g, uint64_t sz_blk, int64_t blk_move, int64_t min_blk,
@@ -80,7 +80,7 @@ int exo_allocate(double *kvec, int64_t *blk_part, int64_t *blk_pos, uint32_t n,
     return moves;
 }
 
-/* Alg. 3, line 29                                                     */
+/* Alg. 3 (cyclic allocation)                                                     */
 uint32_t exo_owner(uint64_t t, uint32_t rank, uint32_t n)
 {
     return (uint32_t)((t % n + rank) % n);
@@ -102,7 +102,7 @@ uint64_t exo_select(const float *acc, uint64_t st, uint64_t end, float delta,
     return count;
 }
 
-/* Alg. 5, lines 1-7                                                   */
+/* Alg. 5 (choice of the scaling factor)                                                   */
 float exo_scale_factor(double k, double k_actual, double beta, double gamma)
 {
     double exam = k_actual / k;
@@ -116,7 +116,7 @@ float exo_scale_factor(double k, double k_actual, double beta, double gamma)
     return (float)sf;
 }
 
-/* Alg. 5, line 8                                                      */
+/* Alg. 5 (threshold scaling)                                                      */
 float exo_estimate(double k, double k_actual, float delta, double beta, double gamma)
 {
     float sf = exo_scale_factor(k, k_actual, beta, gamma);
@@ -166,11 +166,11 @@ exo_state *exo_create(uint64_t n_g, uint32_t block_size, uint32_t n_parts,
     }
     if (cap > n_g) cap = n_g;
     s->cap = cap;
-    s->delta = threshold0;          /* Alg. 1 line 5 */
+    s->delta = threshold0;          /* Alg. 1 (threshold initialisation) */
     s->delta_used = threshold0;
     s->t = 0;
 
-    s->e         = (float *)calloc(n_g, sizeof(float));        /* Alg. 1 line 3 */
+    s->e         = (float *)calloc(n_g, sizeof(float));        /* Alg. 1 (local-error initialisation) */
     s->kvec      = (double *)malloc(n_parts * sizeof(double));
     s->blk_part  = (int64_t *)malloc(n_parts * sizeof(int64_t));
     s->blk_pos   = (int64_t *)malloc(n_parts * sizeof(int64_t));
@@ -187,9 +187,9 @@ exo_state *exo_create(uint64_t n_g, uint32_t block_size, uint32_t n_parts,
         exo_destroy(s);
         return NULL;
     }
-    for (uint32_t i = 0; i < n_parts; ++i)                      /* Alg. 1 line 4 */
+    for (uint32_t i = 0; i < n_parts; ++i)                      /* Alg. 1 (partial-k initialisation) */
         s->kvec[i] = s->k / (double)n_parts;
-    exo_partition(n_b, n_parts, s->blk_part, s->blk_pos);       /* Alg. 1 line 6 */
+    exo_partition(n_b, n_parts, s->blk_part, s->blk_pos);       /* Alg. 1 (partition initialisation) */
     memcpy(s->used_part, s->blk_part, n_parts * sizeof(int64_t));
     memcpy(s->used_pos, s->blk_pos, n_parts * sizeof(int64_t));
     return s;
@@ -211,7 +211,7 @@ void exo_step(exo_state *s, const float *g)
     const uint64_t n_g = s->n_g;
     float *acc = s->e;
 
-    /* Alg. 1 line 7: acc = e + g (g carries the learning rate already). */
+    /* Alg. 1 (accumulate): acc = e + g (g carries the learning rate already). */
     for (uint64_t i = 0; i < n_g; ++i) {
         float a = acc[i] + g[i];
         acc[i] = a;
@@ -242,7 +242,7 @@ static float half_to_float(uint16_t h)
     return sign ? -v : v;
 }
 
-/* Alg. 1 line 7 as printed: acc = e + eta * G, with G in fp32 (dtype 0), bf16
+/* Alg. 1 (accumulate) as printed: acc = e + eta * G, with G in fp32 (dtype 0), bf16
  * (1) or fp16 (2).  The gradient is widened exactly, the product is rounded
  * to fp32, then the sum is rounded to fp32 (no fused multiply-add: the file
  * is built with -ffp-contract=off). */
@@ -271,15 +271,15 @@ static void step_after_accumulate(exo_state *s)
     const uint32_t n = s->n;
     float *acc = s->e;
 
-    /* Alg. 1 line 8: Allocate adjusts the topology from last iteration's
+    /* Alg. 1 (Allocate): Allocate adjusts the topology from last iteration's
      * per-partition counts; selection below uses the adjusted topology. */
     exo_allocate(s->kvec, s->blk_part, s->blk_pos, n, n_g, s->b,
                  (int64_t)s->blk_move, (int64_t)s->min_blk, s->alpha);
     memcpy(s->used_part, s->blk_part, n * sizeof(int64_t));
     memcpy(s->used_pos, s->blk_pos, n * sizeof(int64_t));
 
-    /* Alg. 1 lines 9-11: every partition is selected by exactly one worker
-     * (Alg. 3 line 29 is a bijection rank -> partition at fixed t), so on
+    /* Alg. 1 (Sparsify, AllGather, value gather): every partition is selected by exactly one worker
+     * (Alg. 3 (cyclic allocation) is a bijection rank -> partition at fixed t), so on
      * one device the gathered index list is the partitions' lists; they are
      * laid out here in ascending partition order. */
     const float delta = s->delta;
@@ -287,7 +287,7 @@ static void step_after_accumulate(exo_state *s)
     memset(s->blk_cnt, 0, s->n_b * sizeof(uint32_t));
     uint64_t emitted = 0, total = 0;
     for (uint32_t p = 0; p < n; ++p) {
-        /* Alg. 3 lines 30-31, with the last block allowed to be short. */
+        /* Alg. 3 (partition range), with the last block allowed to be short. */
         uint64_t st  = (uint64_t)s->used_pos[p] * s->b;
         uint64_t end = (uint64_t)(s->used_pos[p] + s->used_part[p]) * s->b;
         if (end > n_g) end = n_g;
@@ -304,7 +304,7 @@ static void step_after_accumulate(exo_state *s)
             int sel = s->cmp_mode ? (a > delta) : (a >= delta);
             if (sel) s->blk_cnt[i / s->b] += 1;
         }
-        /* Alg. 1 line 11: values at the selected indices. */
+        /* Alg. 1 (value gather): values at the selected indices. */
         for (uint64_t j = 0; j < take; ++j)
             s->out_val[emitted + j] = acc[s->out_idx[emitted + j]];
         s->part_cnt[p] = cnt;
@@ -312,19 +312,19 @@ static void step_after_accumulate(exo_state *s)
         total += cnt;
     }
     s->part_off[n] = emitted;
-    s->k_actual = total;        /* Alg. 1 line 13 */
+    s->k_actual = total;        /* Alg. 1 (k' sum) */
     s->k_emitted = emitted;
 
-    /* Alg. 1 line 14: Estimate. */
+    /* Alg. 1 (Estimate): Estimate. */
     s->delta = exo_estimate(s->k, (double)total, delta, s->beta, s->gamma);
 
-    /* Alg. 1 lines 10/15: the partial-k vector for the next Allocate. */
+    /* Alg. 1 (AllGather counts, partial-k carry): the partial-k vector for the next Allocate. */
     for (uint32_t p = 0; p < n; ++p) s->kvec[p] = (double)s->part_cnt[p];
 
-    /* Alg. 1 line 17: zero what was sent (only what fitted the output). */
+    /* Alg. 1 (zeroing of the sent entries): zero what was sent (only what fitted the output). */
     for (uint64_t j = 0; j < emitted; ++j) acc[s->out_idx[j]] = 0.0f;
 
-    /* Alg. 1 line 18: e_{t+1} = acc (same buffer). */
+    /* Alg. 1 (residual carry): e_{t+1} = acc (same buffer). */
     s->t += 1;
 }
 
@@ -376,7 +376,7 @@ double exo_traffic_ratio(const exo_state *s)
 /* One statement of the algorithm = one loop below, workers in rank    */
 /* order; the two collectives are plain loops over the workers.        */
 
-/* Alg. 3 lines 2-7: the all-gathered partial-k vector is indexed by rank;
+/* Alg. 3 (re-indexing of the partial-k vector): the all-gathered partial-k vector is indexed by rank;
  * rank i selected partition ((t-1) mod n + i) mod n at iteration t-1, so
  * temp[that partition] = k_t[i].  The modulo is the mathematical one
  * ((-1) mod n = n-1), which only matters at t = 0. */
@@ -467,7 +467,7 @@ exo_workers *exo_workers_create(uint64_t n_g, uint32_t block_size, uint32_t n,
     int ok = s->e && s->idx && s->g && s->k_t && s->temp && s->blk_part && s->blk_pos &&
              s->used_part && s->used_pos && s->k_rank && s->rank_off && s->idx_t && s->g_t;
     for (uint32_t i = 0; ok && i < n; ++i) {
-        s->e[i]   = (float *)calloc(n_g, sizeof(float));            /* Alg. 1 line 3 */
+        s->e[i]   = (float *)calloc(n_g, sizeof(float));            /* Alg. 1 (local-error initialisation) */
         s->idx[i] = (uint32_t *)malloc(cap * sizeof(uint32_t));
         s->g[i]   = (float *)malloc(n * cap * sizeof(float));
         ok = s->e[i] && s->idx[i] && s->g[i];
@@ -476,8 +476,8 @@ exo_workers *exo_workers_create(uint64_t n_g, uint32_t block_size, uint32_t n,
         exo_workers_destroy(s);
         return NULL;
     }
-    for (uint32_t i = 0; i < n; ++i) s->k_t[i] = s->k / (double)n;  /* Alg. 1 line 4 */
-    exo_partition(n_b, n, s->blk_part, s->blk_pos);                  /* Alg. 1 line 6 */
+    for (uint32_t i = 0; i < n; ++i) s->k_t[i] = s->k / (double)n;  /* Alg. 1 (partial-k initialisation) */
+    exo_partition(n_b, n, s->blk_part, s->blk_pos);                  /* Alg. 1 (partition initialisation) */
     memcpy(s->used_part, s->blk_part, n * sizeof(int64_t));
     memcpy(s->used_pos, s->blk_pos, n * sizeof(int64_t));
     return s;
@@ -492,7 +492,7 @@ void exo_workers_step(exo_workers *s, const float *const *g)
     const float delta = s->delta;
     s->delta_used = delta;
 
-    /* line 7: acc_i = e_i + g_i */
+    /* accumulate: acc_i = e_i + g_i */
     for (uint32_t i = 0; i < n; ++i) {
         float *acc = s->e[i];
         for (uint64_t j = 0; j < n_g; ++j) {
@@ -501,7 +501,7 @@ void exo_workers_step(exo_workers *s, const float *const *g)
         }
     }
 
-    /* line 8: Allocate.  Every worker computes the same thing from the same
+    /* Allocate.  Every worker computes the same thing from the same
      * gathered vector, so it is computed once. */
     exo_reindex(s->k_t, n, s->t, s->temp);
     exo_allocate(s->temp, s->blk_part, s->blk_pos, n, n_g, s->b,
@@ -509,17 +509,17 @@ void exo_workers_step(exo_workers *s, const float *const *g)
     memcpy(s->used_part, s->blk_part, n * sizeof(int64_t));
     memcpy(s->used_pos, s->blk_pos, n * sizeof(int64_t));
 
-    /* line 9: every worker sparsifies its own partition of its own acc */
+    /* Sparsify: every worker sparsifies its own partition of its own acc */
     for (uint32_t i = 0; i < n; ++i) {
-        uint32_t alloc = exo_owner(s->t, i, n);                      /* Alg. 3 line 29 */
-        uint64_t st  = (uint64_t)s->used_pos[alloc] * s->b;          /* Alg. 3 lines 30-31 */
+        uint32_t alloc = exo_owner(s->t, i, n);                      /* Alg. 3 (cyclic allocation) */
+        uint64_t st  = (uint64_t)s->used_pos[alloc] * s->b;          /* Alg. 3 (partition range) */
         uint64_t end = (uint64_t)(s->used_pos[alloc] + s->used_part[alloc]) * s->b;
         if (end > n_g) end = n_g;
         if (st > n_g) st = n_g;
         s->k_rank[i] = exo_select(s->e[i], st, end, delta, (int)s->cmp_mode, s->idx[i], s->cap);
     }
 
-    /* line 10: AllGather of the index lists (rank order) and of the counts */
+    /* AllGather of the index lists (rank order) and of the counts */
     uint64_t total = 0, len = 0;
     for (uint32_t i = 0; i < n; ++i) {
         uint64_t sent = s->k_rank[i] < s->cap ? s->k_rank[i] : s->cap;
@@ -527,30 +527,30 @@ void exo_workers_step(exo_workers *s, const float *const *g)
         for (uint64_t j = 0; j < sent; ++j) s->idx_t[len + j] = s->idx[i][j];
         len += sent;
         total += s->k_rank[i];
-        s->k_t[i] = (double)s->k_rank[i];                            /* also line 15 */
+        s->k_t[i] = (double)s->k_rank[i];                            /* also the partial-k carry */
     }
     s->rank_off[n] = len;
 
-    /* line 11: g_i = acc_i[idx_t] */
+    /* value gather: g_i = acc_i[idx_t] */
     for (uint32_t i = 0; i < n; ++i)
         for (uint64_t j = 0; j < len; ++j) s->g[i][j] = s->e[i][s->idx_t[j]];
 
-    /* line 12: AllReduce(SUM); the order of the sum is rank order here */
+    /* AllReduce(SUM); the order of the sum is rank order here */
     for (uint64_t j = 0; j < len; ++j) {
         float sum = s->g[0][j];
         for (uint32_t i = 1; i < n; ++i) sum = sum + s->g[i][j];
         s->g_t[j] = sum;
     }
 
-    /* lines 13-14 */
+    /* k' sum and Estimate */
     s->k_actual = total;
     s->delta = exo_estimate(s->k, (double)total, delta, s->beta, s->gamma);
 
-    /* line 17: every worker zeroes its acc at the gathered indices */
+    /* zeroing: every worker zeroes its acc at the gathered indices */
     for (uint32_t i = 0; i < n; ++i)
         for (uint64_t j = 0; j < len; ++j) s->e[i][s->idx_t[j]] = 0.0f;
 
-    /* line 18: e_{i,t+1} = acc_i (same buffer) */
+    /* residual carry: e_{i,t+1} = acc_i (same buffer) */
     s->t += 1;
 }
 
@@ -596,7 +596,7 @@ double exo_workers_traffic_ratio(const exo_workers *s)
     return (double)s->n * (double)m / (double)s->k_actual;
 }
 
-/* Alg. 1 line 16 on the entries that were sent: x[idx_t] <- x[idx_t] - (1/n) g_t.
+/* Alg. 1 (model update) on the entries that were sent: x[idx_t] <- x[idx_t] - (1/n) g_t.
  * `scale` is the 1/n of the paper as an fp32 number; the product is rounded
  * to fp32, then the difference is. */
 void exo_apply_update(float *x, const uint32_t *idx_t, const float *g_t, uint64_t len, float scale)

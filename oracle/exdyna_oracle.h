@@ -19,7 +19,7 @@
  * paper's: "parity unpinned" for those two (see exo_step).  The n-worker
  * form (exo_workers_*) is pinned by the same definitions written in numpy,
  * by its reduction to the one-device form for n = 1 and for identical
- * gradients, and by Alg. 3 line 29 for the re-indexing of lines 2-7; the
+ * gradients, and by Alg. 3 (cyclic allocation) for the re-indexing ahead of the sweep; the
  * order of the AllReduce sum (rank order) is this build's reading.
  */
 #ifndef EXDYNA_ORACLE_H
@@ -31,15 +31,15 @@
 extern "C" {
 #endif
 
-/* Alg. 2 lines 1-2: block size from a block count: floor(n_g / n_b) rounded
+/* Alg. 2 (block size): block size from a block count: floor(n_g / n_b) rounded
  * down to a multiple of 32. */
 uint64_t exo_block_size(uint64_t n_g, uint64_t n_b);
 
-/* Alg. 2 lines 3-17: initial topology.  blk_part[i] = quotient (+1 for the
+/* Alg. 2 (topology): initial topology.  blk_part[i] = quotient (+1 for the
  * first `remainder` partitions); blk_pos = exclusive prefix sum. */
 void exo_partition(uint64_t n_b, uint32_t n, int64_t *blk_part, int64_t *blk_pos);
 
-/* Alg. 3 lines 8-28: one sweep over adjacent partition pairs.  kvec (fp64,
+/* Alg. 3 (the sweep over adjacent pairs): one sweep over adjacent partition pairs.  kvec (fp64,
  * length n) is the partial-k vector in partition order and is updated in
  * place, as are blk_part / blk_pos.  A sum of zero (nothing selected) leaves
  * everything unchanged.  Returns the number of boundary moves made. */
@@ -47,7 +47,7 @@ int exo_allocate(double *kvec, int64_t *blk_part, int64_t *blk_pos, uint32_t n,
                  uint64_t n_g, uint64_t sz_blk, int64_t blk_move, int64_t min_blk,
                  double alpha);
 
-/* Alg. 3 line 29: the partition that worker `rank` owns at iteration t. */
+/* Alg. 3 (cyclic allocation): the partition that worker `rank` owns at iteration t. */
 uint32_t exo_owner(uint64_t t, uint32_t rank, uint32_t n);
 
 /* Alg. 4: ascending indices i in [st, end) with |acc[i]| >= delta
@@ -62,7 +62,7 @@ uint64_t exo_select(const float *acc, uint64_t st, uint64_t end, float delta,
 float exo_scale_factor(double k, double k_actual, double beta, double gamma);
 float exo_estimate(double k, double k_actual, float delta, double beta, double gamma);
 
-/* ---- whole-step state machine (Alg. 1 lines 3-6 and 7-18) ------------- */
+/* ---- whole-step state machine (Alg. 1 (initialisation and iteration body)) ------------- */
 
 typedef struct exo_state exo_state;
 
@@ -80,7 +80,7 @@ void exo_destroy(exo_state *s);
  * carry the residual. */
 void exo_step(exo_state *s, const float *g);
 
-/* The same iteration with Alg. 1 line 7 as printed, acc = e + eta * G, for
+/* The same iteration with Alg. 1 (accumulate) as printed, acc = e + eta * G, for
  * gradients stored as fp32 (dtype 0), bf16 (1) or fp16 (2): fl(e + fl(eta * g)). */
 void exo_step_scaled(exo_state *s, const void *g, int dtype, float eta);
 
@@ -108,7 +108,7 @@ double          exo_traffic_ratio(const exo_state *s); /* Eq. 5; 0 when k' = 0 *
 
 /* ---- Alg. 1 with n workers (each its own gradient and residual) ------- */
 
-/* Alg. 3 lines 2-7: partial-k vector from rank order (as all-gathered after
+/* Alg. 3 (re-indexing of the partial-k vector): partial-k vector from rank order (as all-gathered after
  * iteration t-1) to partition order, k_part[((t-1) mod n + i) mod n] = k_rank[i]. */
 void exo_reindex(const double *k_rank, uint32_t n, uint64_t t, double *k_part);
 
@@ -122,7 +122,7 @@ exo_workers *exo_workers_create(uint64_t n_g, uint32_t block_size, uint32_t n,
                                 uint32_t cmp_mode, uint64_t cap);
 void exo_workers_destroy(exo_workers *s);
 
-/* One iteration of Alg. 1 lines 7-18 for all workers; g[i] = worker i's
+/* One iteration of Alg. 1 (the iteration body) for all workers; g[i] = worker i's
  * gradient (n_g fp32, learning rate applied).  AllGather concatenates the
  * workers' lists in rank order; AllReduce sums in rank order in fp32. */
 void exo_workers_step(exo_workers *s, const float *const *g);
@@ -144,7 +144,7 @@ const int64_t  *exo_workers_blk_pos(const exo_workers *s, int which);
 double          exo_workers_err_norm(const exo_workers *s, uint32_t i); /* Eq. 1; i == n: the mean */
 double          exo_workers_traffic_ratio(const exo_workers *s);        /* Eq. 5 */
 
-/* Alg. 1 line 16 restricted to the sent entries: x[idx_t[j]] -= scale * g_t[j]
+/* Alg. 1 (model update) restricted to the sent entries: x[idx_t[j]] -= scale * g_t[j]
  * (scale = 1/n; fp32 product, then fp32 difference). */
 void exo_apply_update(float *x, const uint32_t *idx_t, const float *g_t, uint64_t len, float scale);
 

@@ -152,7 +152,7 @@ def estimate(k, k_actual, delta, beta, gamma) -> float:
 
 
 def apply_update(x: np.ndarray, idx_t: np.ndarray, g_t: np.ndarray, scale: float):
-    """Alg. 1 line 16 on the sent entries, in place on the float32 array x."""
+    """Alg. 1 (model update) on the sent entries, in place on the float32 array x."""
     assert x.dtype == np.float32 and x.flags.c_contiguous
     idx = np.ascontiguousarray(idx_t, np.uint32)
     g = np.ascontiguousarray(g_t, np.float32)
@@ -162,7 +162,7 @@ def apply_update(x: np.ndarray, idx_t: np.ndarray, g_t: np.ndarray, scale: float
 
 
 def reindex(k_rank, t: int):
-    """Alg. 3 lines 2-7: partial-k vector from rank order to partition order."""
+    """Alg. 3 (re-indexing of the partial-k vector): partial-k vector from rank order to partition order."""
     kr = np.array(k_rank, np.float64)
     out = np.empty_like(kr)
     _load().exo_reindex(_ptr(kr, C.c_double), len(kr), t, _ptr(out, C.c_double))
@@ -233,7 +233,7 @@ class Workers:
 
 
 class Oracle:
-    """The whole-step state machine (Alg. 1 lines 3-18) behind exo_create/exo_step."""
+    """The whole-step state machine (Alg. 1 (initialisation and iteration body)) behind exo_create/exo_step."""
 
     def __init__(self, n_g, block_size, n_parts, density, threshold0, alpha=1.0, beta=1.1,
                  gamma=0.01, blk_move=1, min_blk=1, cmp_mode=0, max_selected=0):

@@ -3,26 +3,26 @@
 // Two kernels per iteration, both enqueued by exdyna_step with no host round
 // trip (threshold, topology and counters live in device memory):
 //
-//   k_stream   acc = e + g (Alg. 1 line 7), |acc| cmp delta (Alg. 4 line 2).
+//   k_stream   acc = e + g (Alg. 1 (accumulate)), |acc| cmp delta (Alg. 4 (comparison)).
 //              Each wavefront owns 1024 contiguous gradients (a "wave tile").
 //              It ranks its selected gradients with ballots, writes their
 //              (index, value) pairs in index order into the tile's staging
 //              slots, writes the residual with those entries already zeroed
-//              (Alg. 1 lines 17-18), stores the tile's count, and adds the
+//              (Alg. 1 (zeroing and residual carry)), stores the tile's count, and adds the
 //              count to a per-block and a per-segment counter.  A tile with
 //              more selected gradients than it has slots is only counted and
 //              flagged; its residual is written unzeroed.
 //              Pure streaming: 8 B read + 4 B written per gradient, no
 //              workgroup barrier, no fence.
 //   k_finish   workgroup 0 = control: per-partition counts k_{p,t} and k'
-//              (Alg. 1 lines 10, 13), output segment offsets, threshold
+//              (Alg. 1 (AllGather, k' sum)), output segment offsets, threshold
 //              scaling (Alg. 5), adjacent-partition rebalancing (Alg. 3 lines
 //              8-28), Eq. 2/5/6 statistics.
 //              other workgroups = compaction, one wavefront per chunk of up to
 //              64 wave tiles: prefix of the segment counters in front (summed
 //              by the whole workgroup), a wave scan of the tile counts, then
 //              all lanes copy the chunk's staged pairs to their final
-//              positions (Alg. 1 lines 9-11).  Flagged tiles are re-read from
+//              positions (Alg. 1 (Sparsify, AllGather, value gather)).  Flagged tiles are re-read from
 //              the residual and compacted by the whole wave.  Pairs beyond the
 //              output capacity are put back into the residual.  The same
 //              prefix lays out the next iteration's staging slots: a tile gets
@@ -32,19 +32,19 @@
 //              not depend on each other, so they overlap inside one launch.
 //
 // Variants of the same two kernels: gradients stored as fp32, bf16 or fp16 with
-// the learning rate applied inside the accumulate (Alg. 1 line 7 as printed);
+// the learning rate applied inside the accumulate (Alg. 1 (accumulate) as printed);
 // block sizes that are multiples of 32 but not of 256 (per-lane masks and
 // counters instead of per-granule ones); and the "worker view", in which one
 // context is one worker of Alg. 1: k_stream compares only inside the partition
-// that worker owns at this iteration (Alg. 3 lines 29-31), k_finish stops at
+// that worker owns at this iteration (Alg. 3 (cyclic allocation and partition range)), k_finish stops at
 // the offsets of the worker's own list, and after the caller's AllGather a
 // third kernel finishes the iteration:
 //
 //   k_exchange rows r < P: read this worker's acc at rank r's gathered indices
 //              into the value buffer the AllReduce will sum, and clear them
-//              (Alg. 1 lines 11 and 17).  Row P: the control workgroup on the
+//              (Alg. 1 (value gather, zeroing)).  Row P: the control workgroup on the
 //              gathered counts, moved from rank to partition order (Alg. 3
-//              lines 2-7) -- the same Alg. 5 / Alg. 3 code as in k_finish.
+//              re-indexing) -- the same Alg. 5 / Alg. 3 code as in k_finish.
 //
 // Partitions are contiguous and ascending (Sec. 4.1), so the concatenation of
 // the per-partition index lists in partition order is the global ascending
@@ -232,7 +232,7 @@ struct StreamArgs {
     uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
     uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
     uint32_t        one_counter;  // a block is exactly one segment: blk_cnt doubles as seg_cnt
-    // worker view (Alg. 1 line 9): compare only inside partition own_part of this
+    // worker view (Alg. 1 (Sparsify)): compare only inside partition own_part of this
     // iteration's topology; kAllParts = everywhere
     uint32_t        own_part;
     const int32_t  *cur_part;
@@ -240,7 +240,7 @@ struct StreamArgs {
     uint32_t        block_size;  // b (the generic variant counts and masks by element index)
 };
 
-// Gradient range [lo, hi) of partition p, cut at n_g (Alg. 3 lines 30-31).
+// Gradient range [lo, hi) of partition p, cut at n_g (Alg. 3 (partition range)).
 __device__ __forceinline__ void partition_elems(const int32_t *part, const int32_t *pos, uint32_t p,
                                                 uint32_t block_size, uint32_t n_g, uint32_t &lo, uint32_t &hi)
 {
@@ -480,8 +480,8 @@ struct FinishArgs {
 // blk_part[i] raised, or lowered, by one move.  So every pair's decision is
 // tabulated for the three states side by side, and the chain of tables is
 // resolved with a prefix scan of table compositions.  A table is three 2-bit
-// actions (0 none, 1 blocks go right: lines 16-20, 2 blocks go left: lines
-// 24-28), and the action a pair takes is the state it hands to the next pair.
+// actions (0 none, 1 blocks go right: the first move, 2 blocks go left: the
+// second), and the action a pair takes is the state it hands to the next pair.
 __device__ __forceinline__ uint32_t compose(uint32_t later, uint32_t earlier)
 {
     // (later o earlier)[s] = later[earlier[s]]
@@ -623,7 +623,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
         const uint32_t v  = lane < kWaves ? S.wsum[lane] : 0u;
         const uint32_t vi = wave_incl_scan(v, lane);
         if (lane < kWaves) S.wsum[lane] = vi - v;
-        if (lane == kWaves - 1) S.k_total = vi;  // k' (Alg. 1 line 13)
+        if (lane == kWaves - 1) S.k_total = vi;  // k' (Alg. 1 (k' sum))
     }
     __syncthreads();
     const uint64_t excl     = (uint64_t)S.wsum[wave] + (incl - c);
@@ -644,8 +644,8 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
         return;
     }
 
-    // Alg. 3 lines 8-10 and the comparisons of lines 13 / 21.  This iteration's
-    // counts are the next Allocate's partial-k vector (Alg. 1 line 15); they
+    // Alg. 3 (averages ahead of the sweep) and the two overload tests.  This iteration's
+    // counts are the next Allocate's partial-k vector (Alg. 1 (partial-k carry)); they
     // are integers, so their fp64 sum is k' exactly.  When pair i is inspected,
     // k[i] is its count, or its count +/- k_move if pair i-1 moved blocks, and
     // k[i+1] is still its count: quotients for the three cases, compared
@@ -685,9 +685,9 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
             const int64_t  part_i = (int64_t)part + (st == 1 ? bm : st == 2 ? -bm : 0);
             uint32_t act = 0;
             if (det_hi && det2_lo) {
-                if (!(part_i - bm < min_blk)) act = 1;   // else "continue" (line 15)
+                if (!(part_i - bm < min_blk)) act = 1;   // else "continue" (first min_blk guard)
             } else if (det_lo && det2_hi) {
-                if (!(part_n - bm < min_blk)) act = 2;   // else "continue" (line 23)
+                if (!(part_n - bm < min_blk)) act = 2;   // else "continue" (second min_blk guard)
             }
             table |= act << (2u * st);
         }
@@ -718,7 +718,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
     if (lane == 0 && moved) atomicAdd(&S.n_moves, (uint32_t)__popcll(moved));
     if (tid < P) {
         const int32_t bmi = (int32_t)prm.blk_move;
-        // lines 16-18 / 24-26 as seen from partition tid: it is the right side
+        // the two block moves as seen from partition tid: it is the right side
         // of pair tid-1 and the left side of pair tid
         const int32_t d_in  = st_in == 1 ? bmi : st_in == 2 ? -bmi : 0;
         const int32_t d_out = act == 1 ? -bmi : act == 2 ? bmi : 0;
@@ -837,7 +837,7 @@ __device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32
                 if (r < cap) {
                     A.out_idx[r] = (uint32_t)(base + q);
                     A.out_val[r] = v[u][q];
-                    e[base + q]  = 0.0f;  // +0 where sent (Alg. 1 line 17)
+                    e[base + q]  = 0.0f;  // +0 where sent (Alg. 1 (zeroing of the sent entries))
                 } else if (NORM) {
                     spill += v[u][q] * v[u][q];  // selected but not emitted: stays in the residual
                 }
@@ -1029,14 +1029,14 @@ k_finish(FinishArgs A, CtrlParams prm)
 }
 
 // ---------------------------------------------------------------------------
-// Worker view, after the AllGather (Alg. 1 lines 11 and 17, then 13-15): one
+// Worker view, after the AllGather (Alg. 1 (value gather, zeroing), then 13-15): one
 // worker's residual meets the gathered index list of all workers.
 //   blockIdx.y = r < P   rank r's part of the list: read acc at those indices
 //                        into the value buffer (what the AllReduce will sum) and
 //                        clear them.  The worker's own part was cleared by the
 //                        streaming pass already: its values come from its list.
 //   blockIdx.y = P       control: the gathered counts, moved from rank order
-//                        to partition order (Alg. 3 lines 2-7), drive Alg. 5
+//                        to partition order (Alg. 3 (re-indexing of the partial-k vector)), drive Alg. 5
 //                        and Alg. 3 for the next iteration.
 struct ExchangeArgs {
     const uint32_t *idx_all;  // P x stride: rank r's indices start at r * stride
@@ -1060,7 +1060,7 @@ k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
         if (tid < P) {
             S.lpos[tid]  = A.cur_pos[tid];
             S.lpart[tid] = A.cur_part[tid];
-            // rank tid selected partition (t mod P + tid) mod P (Alg. 3 line 29)
+            // rank tid selected partition (t mod P + tid) mod P (Alg. 3 (cyclic allocation))
             const uint64_t k_r = X.counts[tid];
             S.cnt[(X.t_mod_p + tid) % P] = (uint32_t)(k_r < prm.n_g ? k_r : prm.n_g);
         }
@@ -1083,14 +1083,14 @@ k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
                 const uint32_t i = X.idx_all[j];
                 if (i < prm.n_g) {
                     v = A.e[i];
-                    A.e[i] = 0.0f;  // Alg. 1 line 17
+                    A.e[i] = 0.0f;  // Alg. 1 (zeroing of the sent entries)
                     if (NORM) sq = v * v;
                 } else {
                     atomicAdd(&A.st->bad_index, 1u);  // not a gradient index: skipped and reported
                 }
             }
         }
-        X.val_all[j] = v;  // Alg. 1 line 11
+        X.val_all[j] = v;  // Alg. 1 (value gather)
     }
     if (NORM) {
         // the streaming pass counted these entries as residual: take them out again
@@ -1102,7 +1102,7 @@ k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
 }
 
 // ---------------------------------------------------------------------------
-// Alg. 1 line 16 on the selected entries only: x[idx] <- x[idx] - scale * g_t,
+// Alg. 1 (model update) on the selected entries only: x[idx] <- x[idx] - scale * g_t,
 // one thread per entry of a rows x stride list (the layout of the exchange).
 __global__ void __launch_bounds__(256)
 k_apply(float *x, const uint32_t *idx, const float *val, const uint64_t *counts, uint64_t stride,
@@ -1135,9 +1135,9 @@ __global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n)
         p[i] = v;
 }
 
-// Alg. 1 lines 5-6: delta_0 and Alg. 2's topology in closed form (the first
+// Alg. 1 (threshold and partition initialisation): delta_0 and Alg. 2's topology in closed form (the first
 // `remainder` partitions hold quotient+1 blocks; positions are the exclusive
-// prefix sum).  The uniform initial partial-k vector of line 4 is not stored:
+// prefix sum).  The uniform initial partial-k vector is not stored:
 // with equal entries det = det2 for every pair, so the first Allocate moves
 // nothing, and every later Allocate uses the counts of the step before it.
 __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_t *part1,
@@ -1476,7 +1476,7 @@ int step_impl(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, int6
     const bool prof = c->prof_slots != 0 && (c->t - c->prof_since) % c->prof_every == 0;
     hipEvent_t *ev = prof ? c->ev + 3 * (((c->t - c->prof_since) / c->prof_every) % c->prof_slots) : nullptr;
     const uint32_t P = c->cfg.n_parts;
-    // Alg. 3 line 29: the partition worker `rank` selects at iteration t
+    // Alg. 3 (cyclic allocation): the partition worker `rank` selects at iteration t
     c->own_part = worker_rank < 0 ? kAllParts : (uint32_t)((c->t % P + (uint64_t)worker_rank) % P);
     const uint32_t mode = worker_rank < 0 ? kCtrlFull : kCtrlSelect;
 
@@ -1586,9 +1586,9 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
     p.inv_alpha = 1.0 / cfg->alpha;
     p.beta = cfg->beta;
     p.inv_beta = 1.0 / cfg->beta;
-    p.sf_hi = (float)(1.0 + cfg->gamma);           // Alg. 5 line 3
-    p.sf_mid = (float)(1.0 + 0.25 * cfg->gamma);   // Alg. 5 line 5
-    p.sf_lo = (float)(1.0 - cfg->gamma);           // Alg. 5 line 7
+    p.sf_hi = (float)(1.0 + cfg->gamma);           // Alg. 5 (factor above beta)
+    p.sf_mid = (float)(1.0 + 0.25 * cfg->gamma);   // Alg. 5 (factor inside the band)
+    p.sf_lo = (float)(1.0 - cfg->gamma);           // Alg. 5 (factor below 1/beta)
     p.n_b = (uint32_t)n_b;
     p.n_parts = cfg->n_parts;
     p.block_size = cfg->block_size;
@@ -1597,7 +1597,7 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
 
     hipStream_t s = c->stream;
     const uint32_t P = cfg->n_parts;
-    // residual <- 0 (Alg. 1 line 3); counters start clean
+    // residual <- 0 (Alg. 1 (local-error initialisation)); counters start clean
     hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, s,
                        reinterpret_cast<uint32_t *>(d_residual), 0u, (size_t)cfg->n_g);
     hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
@@ -1748,14 +1748,14 @@ int exdyna_get_partitions(exdyna_ctx *c, int which, uint32_t *h_blk_pos, uint32_
     for (uint32_t p = 0; p < P; ++p) {
         if (h_blk_part) h_blk_part[p] = (uint32_t)part[p];
         if (h_blk_pos) h_blk_pos[p] = (uint32_t)pos[p];
-        // Alg. 3 lines 30-31, the last block may be short
+        // Alg. 3 (partition range), the last block may be short
         uint64_t st = (uint64_t)pos[p] * c->cfg.block_size;
         uint64_t en = (uint64_t)(pos[p] + part[p]) * c->cfg.block_size;
         if (st > c->cfg.n_g) st = c->cfg.n_g;
         if (en > c->cfg.n_g) en = c->cfg.n_g;
         if (h_elem_start) h_elem_start[p] = st;
         if (h_elem_end) h_elem_end[p] = en;
-        // Alg. 3 line 29: alloc = (t mod P + rank) mod P  <=>  rank = (alloc - t) mod P
+        // Alg. 3 (cyclic allocation): alloc = (t mod P + rank) mod P  <=>  rank = (alloc - t) mod P
         if (h_owner_rank) h_owner_rank[p] = (uint32_t)((p + P - (uint32_t)(it % P)) % P);
     }
     free(tmp);

@@ -51,7 +51,7 @@ def compare_step(x, o, t, check_norm=False, tag=""):
     assert np.array_equal(parts["elem_start"].astype(np.int64), st), where
     assert np.array_equal(parts["elem_end"].astype(np.int64), en), where
     owners = [oracle.owner(t, int(r), o.P) for r in parts["owner_rank"]]
-    assert owners == list(range(o.P)), where                 # Alg. 3 line 29, inverted
+    assert owners == list(range(o.P)), where                 # Alg. 3 (cyclic allocation), inverted
     res = x.residual.cpu().numpy()
     assert np.array_equal(bits(res), bits(o.residual(copy=False))), where
     s = x.get_stats()

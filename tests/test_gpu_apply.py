@@ -1,4 +1,4 @@
-"""exdyna_apply_update (Alg. 1 line 16 on the selected entries) against the oracle."""
+"""exdyna_apply_update (Alg. 1 (model update) on the selected entries) against the oracle."""
 import ctypes as C
 
 import numpy as np
@@ -97,20 +97,20 @@ def test_all_of_algorithm_1_with_three_workers():
     for t in range(6):
         grads = [src.grad(t * n + i) for i in range(n)]
         for i, c in enumerate(ctxs):
-            c.worker_select(grads[i], i)                                   # lines 7-9
+            c.worker_select(grads[i], i)                                   # accumulate, Allocate, Sparsify
         counts = torch.cat([c.count_tensors()[0] for c in ctxs]).contiguous()
         emitted = [int(c.count_tensors()[1]) for c in ctxs]
         stride = max(emitted)
-        idx_all = torch.zeros((n, stride), dtype=torch.int32, device=DEV)  # line 10
+        idx_all = torch.zeros((n, stride), dtype=torch.int32, device=DEV)  # AllGather
         for r, c in enumerate(ctxs):
             idx_all[r, :emitted[r]] = c.get_selected()[0]
         total = torch.zeros((n, stride), dtype=torch.float32, device=DEV)
         for c in ctxs:
             v = torch.empty((n, stride), dtype=torch.float32, device=DEV)
-            c.worker_exchange(idx_all, counts, v)                          # lines 11, 13-15, 17-18
-            total += v                                                     # line 12, rank order
+            c.worker_exchange(idx_all, counts, v)                          # value gather, Estimate, zeroing
+            total += v                                                     # AllReduce, rank order
         for c, m in zip(ctxs, models):
-            c.apply_update(m, idx_all, total, counts, scale)               # line 16
+            c.apply_update(m, idx_all, total, counts, scale)               # model update
         w.step([g.cpu().numpy() for g in grads])
         oracle.apply_update(ref, w.idx(), w.sum(), scale)
         for i, m in enumerate(models):

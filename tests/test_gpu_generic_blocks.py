@@ -1,4 +1,4 @@
-"""Block sizes that are multiples of 32 but not of 256 (the granularity Alg. 2 line 2 rounds
+"""Block sizes that are multiples of 32 but not of 256 (the granularity Alg. 2 (rounding of the block size) rounds
 to): block and partition boundaries then fall inside the 256-gradient loads of a wavefront."""
 import numpy as np
 import pytest
@@ -31,7 +31,7 @@ def test_generic_block_sizes_bit_exact(n_g, b, P, d):
 
 
 def test_block_size_from_alg2_is_usable():
-    """n_b = 100 blocks asked for, block size by Alg. 2 lines 1-2 with the paper's multiple of 32."""
+    """n_b = 100 blocks asked for, block size by Alg. 2 (block size) with the paper's multiple of 32."""
     n_g = 123_457
     b = binding.block_size_from_nb(n_g, 100, 32)
     assert b == oracle.block_size(n_g, 100) == 1216 and b % 256 != 0

@@ -1,5 +1,5 @@
 """exdyna_step_scaled against the oracle: acc = fl(e + fl(eta * g)) with fp32, bf16 and
-fp16 gradients (Alg. 1 line 7 with the learning rate inside the accumulate)."""
+fp16 gradients (Alg. 1 (accumulate) with the learning rate inside the accumulate)."""
 import numpy as np
 import pytest
 import torch

@@ -81,7 +81,7 @@ def _iteration(ctxs, w, grads, t, tag, check_norm=False):
         x._announced = nxt
         pc = x.get_part_counts()
         for r in range(n):
-            assert pc[(t % n + r) % n] == counts[r], where         # Alg. 3 lines 2-7
+            assert pc[(t % n + r) % n] == counts[r], where         # Alg. 3 (re-indexing of the partial-k vector)
         if check_norm:
             want_n = w.err_norm(i)
             assert abs(s.err_norm - want_n) <= 1e-5 * max(want_n, 1e-30), (where, s.err_norm, want_n)

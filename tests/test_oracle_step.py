@@ -1,4 +1,4 @@
-"""Pins for the oracle's whole-step state machine (Alg. 1 lines 7-18, Alg. 4).
+"""Pins for the oracle's whole-step state machine (Alg. 1 (the iteration body), Alg. 4).
 
 The expectations are what the paper's definitions reduce to in numpy: the
 selected set is `flatnonzero(|acc| >= delta)` (Alg. 4's `where`), its size is
@@ -19,7 +19,7 @@ def _rand_grad(rng, n, scale=1e-3):
 
 def _check_step(o, e_before, g, cmp_mode=0):
     """All per-step facts that follow from the definitions, given the oracle's own delta/topology."""
-    acc = (e_before + g).astype(np.float32)                 # one fp32 add (Alg. 1 line 7)
+    acc = (e_before + g).astype(np.float32)                 # one fp32 add (Alg. 1 (accumulate))
     delta = o.threshold_used
     mag = np.abs(acc)
     mask = mag > delta if cmp_mode else mag >= delta
@@ -55,7 +55,7 @@ def _check_step(o, e_before, g, cmp_mode=0):
     pad[: o.n_g] = mask
     assert np.array_equal(bc, pad.reshape(o.n_b, o.b).sum(1).astype(np.uint32))
 
-    # error feedback: sent + residual == acc, exactly (Alg. 1 lines 17-18)
+    # error feedback: sent + residual == acc, exactly (Alg. 1 (zeroing and residual carry))
     e_after = o.residual()
     sent = np.zeros_like(acc)
     sent[idx] = val
@@ -167,7 +167,7 @@ def test_capacity_rule_truncates_in_index_order_and_keeps_the_rest():
 
 
 def test_threshold_and_partial_k_feed_the_next_iteration():
-    """Alg. 1 lines 13-15: k' drives Estimate; this iteration's counts drive the next Allocate."""
+    """Alg. 1 (k' sum, Estimate, partial-k carry): k' drives Estimate; this iteration's counts drive the next Allocate."""
     n, b, P = 4096, 128, 4
     rng = np.random.default_rng(11)
     # heavy head: partition 0 gets nearly all selections
@@ -265,7 +265,7 @@ def _bf16_bits(x32):
 
 @pytest.mark.parametrize("dtype", [0, 1, 2])
 def test_scaled_step_rounds_product_then_sum(dtype):
-    """Alg. 1 line 7 as printed, acc = e + eta*G: the gradient is widened exactly (checked
+    """Alg. 1 (accumulate) as printed, acc = e + eta*G: the gradient is widened exactly (checked
     against torch's bf16 and numpy's fp16 conversions), the product is rounded to fp32, then
     the sum -- numpy's separate fp32 multiply and add, never a fused multiply-add."""
     n = 3000

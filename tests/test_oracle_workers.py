@@ -6,7 +6,7 @@ What fixes the expectations, none of it produced by the function under test:
   worker's values are `acc_i[idx_t]`, every worker zeroes at the whole gathered list;
 * two special cases that reduce to the one-device oracle (itself pinned by brute force):
   n = 1, and n workers that all see the same gradient;
-* Alg. 3 lines 2-7 against line 29: the re-indexing must send worker i's count to the
+* Alg. 3's re-indexing of the partial-k vector against its cyclic allocation: the re-indexing must send worker i's count to the
   partition that `owner(t-1, i)` says it selected, and a hand-evaluated case.
 """
 import numpy as np
@@ -33,11 +33,11 @@ def test_reindex_hand_case_and_owner_consistency():
             k_rank = np.arange(100, 100 + n, dtype=np.float64)
             k_part = oracle.reindex(k_rank, t)
             for i in range(n):
-                assert k_part[oracle.owner(t - 1, i, n)] == k_rank[i]      # Alg. 3 line 29
+                assert k_part[oracle.owner(t - 1, i, n)] == k_rank[i]      # Alg. 3 (cyclic allocation)
 
 
 def _check_workers_step(w, e_before, grads):
-    """Everything that follows from Alg. 1 lines 7-18, given the oracle's own delta and topology."""
+    """Everything that follows from Alg. 1 (the iteration body), given the oracle's own delta and topology."""
     n, n_g, b = w.n, w.n_g, w.b
     t = w.t - 1
     delta = w.threshold_used
@@ -46,7 +46,7 @@ def _check_workers_step(w, e_before, grads):
     assert pos[0] == 0 and np.array_equal(pos[1:], np.cumsum(bp)[:-1]) and bp.sum() == w.n_b
     lists, counts = [], []
     for i in range(n):
-        p = (t % n + i) % n                                      # Alg. 3 line 29
+        p = (t % n + i) % n                                      # Alg. 3 (cyclic allocation)
         st, en = pos[p] * b, min((pos[p] + bp[p]) * b, n_g)
         own = st + np.flatnonzero(np.abs(acc[i][st:en]) >= delta)
         counts.append(own.size)
@@ -59,11 +59,11 @@ def _check_workers_step(w, e_before, grads):
     assert w.k_actual == sum(counts)
     total = np.zeros(idx_t.size, np.float32)
     for i in range(n):
-        want = acc[i][idx_t]                                     # line 11
+        want = acc[i][idx_t]                                     # value gather
         assert np.array_equal(w.values(i).view(np.uint32), want.view(np.uint32))
         total = want if i == 0 else (total + want).astype(np.float32)
         e_want = acc[i].copy()
-        e_want[idx_t] = 0.0                                      # line 17: the whole gathered list
+        e_want[idx_t] = 0.0                                      # zeroing: the whole gathered list
         assert np.array_equal(w.residual(i).view(np.uint32), e_want.view(np.uint32))
     assert np.array_equal(w.sum().view(np.uint32), total.view(np.uint32))
     return counts
@@ -159,7 +159,7 @@ def test_identical_gradients_reduce_to_the_one_device_oracle():
 
 
 def test_a_worker_zeroes_entries_it_would_not_have_selected_itself():
-    """Alg. 1 line 17 zeroes at the gathered list: an entry another worker selected is sent
+    """Alg. 1 (zeroing of the sent entries) zeroes at the gathered list: an entry another worker selected is sent
     (with this worker's small value) and cleared here too."""
     n_g, b = 512, 128
     w = oracle.Workers(n_g, b, 2, 0.01, 1.0)
@@ -196,7 +196,7 @@ def test_per_worker_capacity_keeps_the_rest_in_that_workers_residual():
 
 
 def test_apply_update_equals_the_dense_update_with_zeros_elsewhere():
-    """Alg. 1 line 16, x <- x - (1/n) g_t, where g_t is zero except at idx_t: the dense numpy
+    """Alg. 1 (model update), x <- x - (1/n) g_t, where g_t is zero except at idx_t: the dense numpy
     expression and the sparse routine must agree bit for bit, and untouched entries stay."""
     rng = np.random.default_rng(4)
     n_g, n = 5000, 4
