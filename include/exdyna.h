@@ -1,8 +1,8 @@
 /*
  * exdyna.h -- C ABI of the MI355X (gfx950) ExDyna gradient-selection library.
  *
- * One `exdyna_step` is one iteration of the sparsifier of "Distributed SGD
- * with ExDyna" (the body of Alg. 1's loop) on ONE device that plays all P workers:
+ * One `exdyna_step` is one iteration of the sparsifier inside the paper's
+ * distributed SGD (the body of Alg. 1's loop) on ONE device that plays all P workers:
  *   acc = residual + grad                          (Alg. 1, accumulate; Sec. 2)
  *   select |acc| >= delta inside every partition   (Alg. 4, Sec. 4.3)
  *   emit (index, value) pairs, ascending           (Alg. 1, Sparsify and value gather)
