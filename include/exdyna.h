@@ -203,8 +203,8 @@ int exdyna_apply_update(exdyna_ctx *ctx, float *d_model, const uint32_t *d_idx, 
                         void *hip_stream);
 
 /* Results of the last step.  *d_idx / *d_val: device arrays of k_emitted
- * ascending gradient indices and the accumulated values at them (Alg. 1 lines
- * 9-11); *d_part_off: device array of P+1 offsets, partition p's pairs are
+ * ascending gradient indices and the accumulated values at them (Alg. 1,
+ * Sparsify and value gather); *d_part_off: device array of P+1 offsets, partition p's pairs are
  * [part_off[p], part_off[p+1]).  They point into the workspace and are
  * overwritten by the next step.  Any of the three may be NULL.  If h_k_actual
  * or h_k_emitted is non-NULL the stream is synchronised and the counts are

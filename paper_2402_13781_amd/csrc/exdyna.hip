@@ -3,27 +3,27 @@
 // Two kernels per iteration, both enqueued by exdyna_step with no host round
 // trip (threshold, topology and counters live in device memory):
 //
-//   k_stream   acc = e + g (Alg. 1 (accumulate)), |acc| cmp delta (Alg. 4 (comparison)).
+//   k_stream   acc = e + g (Alg. 1, accumulate), |acc| cmp delta (Alg. 4).
 //              Each wavefront owns 1024 contiguous gradients (a "wave tile").
 //              It ranks its selected gradients with ballots, writes their
 //              (index, value) pairs in index order into the tile's staging
 //              slots, writes the residual with those entries already zeroed
-//              (Alg. 1 (zeroing and residual carry)), stores the tile's count, and adds the
-//              count to a per-block and a per-segment counter.  A tile with
+//              (Alg. 1, zeroing and residual carry), stores the tile's count, and
+//              adds the count to a per-block and a per-segment counter.  A tile with
 //              more selected gradients than it has slots is only counted and
 //              flagged; its residual is written unzeroed.
 //              Pure streaming: 8 B read + 4 B written per gradient, no
 //              workgroup barrier, no fence.
 //   k_finish   workgroup 0 = control: per-partition counts k_{p,t} and k'
-//              (Alg. 1 (AllGather, k' sum)), output segment offsets, threshold
-//              scaling (Alg. 5), adjacent-partition rebalancing (Alg. 3 lines
-//              8-28), Eq. 2/5/6 statistics.
+//              (Alg. 1, the gathered counts and their sum), output segment
+//              offsets, threshold scaling (Alg. 5), adjacent-partition
+//              rebalancing (Alg. 3's sweep), Eq. 2/5/6 statistics.
 //              other workgroups = compaction, one wavefront per chunk of up to
 //              64 wave tiles: prefix of the segment counters in front (summed
 //              by the whole workgroup), a wave scan of the tile counts, then
 //              all lanes copy the chunk's staged pairs to their final
-//              positions (Alg. 1 (Sparsify, AllGather, value gather)).  Flagged tiles are re-read from
-//              the residual and compacted by the whole wave.  Pairs beyond the
+//              positions (Alg. 1, Sparsify and value gather).  Flagged tiles are
+//              re-read from the residual and compacted by the whole wave.  Pairs beyond the
 //              output capacity are put back into the residual.  The same
 //              prefix lays out the next iteration's staging slots: a tile gets
 //              slots in proportion to what it selected this time, so dense
@@ -32,18 +32,18 @@
 //              not depend on each other, so they overlap inside one launch.
 //
 // Variants of the same two kernels: gradients stored as fp32, bf16 or fp16 with
-// the learning rate applied inside the accumulate (Alg. 1 (accumulate) as printed);
+// the learning rate applied inside the accumulate (Alg. 1 as printed);
 // block sizes that are multiples of 32 but not of 256 (per-lane masks and
 // counters instead of per-granule ones); and the "worker view", in which one
 // context is one worker of Alg. 1: k_stream compares only inside the partition
-// that worker owns at this iteration (Alg. 3 (cyclic allocation and partition range)), k_finish stops at
-// the offsets of the worker's own list, and after the caller's AllGather a
+// that worker owns at this iteration (Alg. 3, cyclic allocation), k_finish stops
+// at the offsets of the worker's own list, and after the caller's AllGather a
 // third kernel finishes the iteration:
 //
 //   k_exchange rows r < P: read this worker's acc at rank r's gathered indices
 //              into the value buffer the AllReduce will sum, and clear them
-//              (Alg. 1 (value gather, zeroing)).  Row P: the control workgroup on the
-//              gathered counts, moved from rank to partition order (Alg. 3
+//              (Alg. 1, value gather and zeroing).  Row P: the control workgroup
+//              on the gathered counts, moved from rank to partition order (Alg. 3
 //              re-indexing) -- the same Alg. 5 / Alg. 3 code as in k_finish.
 //
 // Partitions are contiguous and ascending (Sec. 4.1), so the concatenation of
@@ -1029,15 +1029,16 @@ k_finish(FinishArgs A, CtrlParams prm)
 }
 
 // ---------------------------------------------------------------------------
-// Worker view, after the AllGather (Alg. 1 (value gather, zeroing), then 13-15): one
-// worker's residual meets the gathered index list of all workers.
+// Worker view, after the AllGather (Alg. 1: value gather and zeroing, then the
+// k' sum, Estimate and the partial-k carry): one worker's residual meets the
+// gathered index list of all workers.
 //   blockIdx.y = r < P   rank r's part of the list: read acc at those indices
 //                        into the value buffer (what the AllReduce will sum) and
 //                        clear them.  The worker's own part was cleared by the
 //                        streaming pass already: its values come from its list.
 //   blockIdx.y = P       control: the gathered counts, moved from rank order
-//                        to partition order (Alg. 3 (re-indexing of the partial-k vector)), drive Alg. 5
-//                        and Alg. 3 for the next iteration.
+//                        to partition order (Alg. 3's re-indexing), drive
+//                        Alg. 5 and Alg. 3 for the next iteration.
 struct ExchangeArgs {
     const uint32_t *idx_all;  // P x stride: rank r's indices start at r * stride
     const uint64_t *counts;   // k_{r,t} by rank, not cut at the capacity
@@ -1135,8 +1136,8 @@ __global__ void k_fill_u32(uint32_t *p, uint32_t v, size_t n)
         p[i] = v;
 }
 
-// Alg. 1 (threshold and partition initialisation): delta_0 and Alg. 2's topology in closed form (the first
-// `remainder` partitions hold quotient+1 blocks; positions are the exclusive
+// Alg. 1's threshold and partition initialisation: delta_0 and Alg. 2's topology
+// in closed form (the first `remainder` partitions hold quotient+1 blocks; positions are the exclusive
 // prefix sum).  The uniform initial partial-k vector is not stored:
 // with equal entries det = det2 for every pair, so the first Allocate moves
 // nothing, and every later Allocate uses the counts of the step before it.
