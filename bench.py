@@ -115,7 +115,7 @@ def main() -> int:
     cpu = None
     cpu_steps = args.cpu_steps
     if cpu_steps < 0:
-        cpu_steps = int(max(2, min(n_vec, 30, 15.0 / (w.n_g / 0.5e9))))   # oracle ~0.5 G elem/s
+        cpu_steps = int(max(2, min(n_vec, 60, 15.0 / (w.n_g / 0.6e9))))   # oracle ~0.6 G elem/s: about 15 s
     if cpu_steps > 0:
         from oracle import oracle
         o = oracle.Oracle(w.n_g, w.block_size, w.n_parts, w.density, thr)
