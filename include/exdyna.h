@@ -91,6 +91,8 @@ typedef struct {
     uint32_t moves;         /* boundary moves Alg. 3 made for the next iteration            */
     uint32_t bad_index;     /* worker view: gathered indices >= n_g, skipped by the exchange */
     uint32_t reserved;
+    uint64_t padding_overhead; /* C_t = P * sum_p (m_t - k_{p,t}) (Eq. 3-4): what an AllGather of
+                                  equal-sized lists pads, summed over the receivers        */
 } exdyna_stats;
 
 /* Fill *cfg with defaults: alpha 1.0, beta 1.1, gamma 0.01, blk_move 1,

@@ -607,3 +607,18 @@ void exo_apply_update(float *x, const uint32_t *idx_t, const float *g_t, uint64_
         x[idx_t[j]] = v;
     }
 }
+
+/* Eq. 2-4: m_t = max_i k_{i,t}; c_i = m_t - k_{i,t} elements padded by worker i;
+ * C_t = n * sum_i c_i. */
+uint64_t exo_padding_overhead(const uint64_t *k, uint32_t n)
+{
+    uint64_t m_t = 0;
+    for (uint32_t i = 0; i < n; ++i)
+        if (k[i] > m_t) m_t = k[i];
+    uint64_t sum = 0;
+    for (uint32_t i = 0; i < n; ++i) {
+        uint64_t c_i = m_t - k[i];
+        sum += c_i;
+    }
+    return (uint64_t)n * sum;
+}

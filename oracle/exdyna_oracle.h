@@ -144,6 +144,10 @@ const int64_t  *exo_workers_blk_pos(const exo_workers *s, int which);
 double          exo_workers_err_norm(const exo_workers *s, uint32_t i); /* Eq. 1; i == n: the mean */
 double          exo_workers_traffic_ratio(const exo_workers *s);        /* Eq. 5 */
 
+/* Eq. 2-4: the padding an AllGather of equal-sized lists adds, C_t = n * sum_i
+ * (max_j k_j - k_i), from the n selection counts of one iteration. */
+uint64_t exo_padding_overhead(const uint64_t *k, uint32_t n);
+
 /* Alg. 1 (model update) restricted to the sent entries: x[idx_t[j]] -= scale * g_t[j]
  * (scale = 1/n; fp32 product, then fp32 difference). */
 void exo_apply_update(float *x, const uint32_t *idx_t, const float *g_t, uint64_t len, float scale);

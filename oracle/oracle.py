@@ -77,6 +77,8 @@ def _load():
         fn = getattr(L, name)
         fn.restype = P(i64)
         fn.argtypes = [vp, C.c_int]
+    L.exo_padding_overhead.restype = u64
+    L.exo_padding_overhead.argtypes = [P(u64), u32]
     L.exo_apply_update.restype = None
     L.exo_apply_update.argtypes = [P(f32), P(u32), P(f32), u64, f32]
     L.exo_reindex.restype = None
@@ -149,6 +151,12 @@ def scale_factor(k, k_actual, beta, gamma) -> float:
 
 def estimate(k, k_actual, delta, beta, gamma) -> float:
     return float(_load().exo_estimate(k, k_actual, np.float32(delta), beta, gamma))
+
+
+def padding_overhead(counts) -> int:
+    """Eq. 2-4: C_t from the per-worker (= per-partition) selection counts."""
+    k = np.ascontiguousarray(counts, np.uint64)
+    return int(_load().exo_padding_overhead(_ptr(k, C.c_uint64), k.size))
 
 
 def apply_update(x: np.ndarray, idx_t: np.ndarray, g_t: np.ndarray, scale: float):

@@ -44,7 +44,7 @@ class Stats(C.Structure):
         ("k_max_part", C.c_uint64), ("density_error", C.c_double), ("traffic_ratio", C.c_double),
         ("err_norm", C.c_double), ("delta_used", C.c_float), ("delta_next", C.c_float),
         ("overflow", C.c_uint32), ("moves", C.c_uint32),
-        ("bad_index", C.c_uint32), ("reserved", C.c_uint32),
+        ("bad_index", C.c_uint32), ("reserved", C.c_uint32), ("padding_overhead", C.c_uint64),
     ]
 
 

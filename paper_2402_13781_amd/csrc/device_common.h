@@ -41,6 +41,7 @@ struct DevState {
     uint64_t own_emitted;  // (one worker's share in the worker view, everything otherwise)
     uint32_t bad_index;    // worker view: gathered indices >= n_g that were skipped
     uint32_t pad;
+    uint64_t padding;      // Eq. 4: P * (P * m_t - k')
 };
 
 struct CtrlParams {

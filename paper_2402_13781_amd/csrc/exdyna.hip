@@ -695,6 +695,7 @@ int exdyna_get_stats(exdyna_ctx *c, exdyna_stats *h_out)
     h_out->moves = st.moves;
     h_out->bad_index = st.bad_index;
     h_out->reserved = 0;
+    h_out->padding_overhead = st.padding;
     return EXDYNA_OK;
 }
 

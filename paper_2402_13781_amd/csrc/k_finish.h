@@ -323,6 +323,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
         st->k_max_part    = m_t;
         st->density_error = fabs(prm.k - (double)k_actual) / (double)prm.n_g;
         st->traffic_ratio = k_actual ? (double)P * (double)m_t / (double)k_actual : 0.0;
+        st->padding       = (uint64_t)P * ((uint64_t)P * m_t - k_actual);  // sum of (m_t - k_p) over p, times P
         st->t     = t_done + 1;  // counted on the device so that a captured graph can be replayed
         st->moves = prm.blk_move ? S.n_moves : 0u;  // blk_move = 0: the pairs decide, nothing moves
     }

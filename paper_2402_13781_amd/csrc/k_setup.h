@@ -44,7 +44,7 @@ __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_
         st->overflow = 0; st->moves = 0; st->t = 0;
         st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
         st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
-        st->own_actual = 0; st->own_emitted = 0; st->bad_index = 0; st->pad = 0;
+        st->own_actual = 0; st->own_emitted = 0; st->bad_index = 0; st->pad = 0; st->padding = 0;
     }
 }
 
@@ -68,7 +68,7 @@ __global__ void k_restore_state(DevState *st, uint64_t t, float delta)
     st->overflow = 0; st->moves = 0; st->t = t;
     st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
     st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
-    st->own_actual = 0; st->own_emitted = 0; st->bad_index = 0; st->pad = 0;
+    st->own_actual = 0; st->own_emitted = 0; st->bad_index = 0; st->pad = 0; st->padding = 0;
 }
 
 __global__ void k_norm_finalize(DevState *st, const double *err_slots)

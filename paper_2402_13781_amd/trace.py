@@ -4,9 +4,9 @@
 Runs the HIP library (never a CPU substitute) over a workload of
 paper_2402_13781_amd.synthetic and prints one CSV line per iteration:
 the actual density k'/n_g against the target d (Sec. 5.2's density plots), the
-density error of Eq. 6, the traffic ratio f(t) of Eq. 5, the threshold, and
-the number of boundary moves Alg. 3 made.  Two switches turn the paper's
-ablations on:
+density error of Eq. 6, the traffic ratio f(t) of Eq. 5, the all-gather padding
+C_t of Eq. 4, the threshold, and the number of boundary moves Alg. 3 made.  Two
+switches turn the paper's ablations on:
 
   --static-partitions   blk_move = 0: coarse-grained, never rebalanced (Sec. 4.1)
   --fixed-threshold     gamma = 0: the hard-threshold sparsifier of Sec. 3
@@ -41,8 +41,8 @@ def run_trace(workload, steps, device="cuda:0", static_partitions=False, fixed_t
                                  threshold0=thr, **kw)
     x = binding.ExDyna(cfg, device)
     rows = []
-    cols = ("t", "k_actual", "density", "density_error", "traffic_ratio", "delta_used", "moves",
-            "overflow")
+    cols = ("t", "k_actual", "density", "density_error", "traffic_ratio", "padding_overhead",
+            "delta_used", "moves", "overflow")
     if out is not None:
         print(",".join(cols), file=out)
     for t in range(steps):
@@ -52,6 +52,7 @@ def run_trace(workload, steps, device="cuda:0", static_partitions=False, fixed_t
         s = x.get_stats()
         row = dict(t=t, k_actual=s.k_actual, density=s.k_actual / workload.n_g,
                    density_error=s.density_error, traffic_ratio=s.traffic_ratio,
+                   padding_overhead=s.padding_overhead,
                    delta_used=s.delta_used, moves=s.moves, overflow=s.overflow)
         rows.append(row)
         if out is not None:

@@ -63,6 +63,7 @@ def compare_step(x, o, t, check_norm=False, tag=""):
     assert s.k_max_part == int(o.part_count().max())
     assert s.density_error == o.density_error(), where
     assert s.traffic_ratio == o.traffic_ratio(), where
+    assert s.padding_overhead == oracle.padding_overhead(o.part_count()), where
     if check_norm:
         want = o.err_norm()
         if np.isnan(want):

@@ -73,6 +73,7 @@ def _iteration(ctxs, w, grads, t, tag, check_norm=False):
         assert s.k_actual == w.k_actual and s.k_emitted == off[-1], where
         assert s.k_max_part == max(counts) and s.bad_index == 0
         assert s.traffic_ratio == w.traffic_ratio(), where
+        assert s.padding_overhead == oracle.padding_overhead(counts), where
         assert s.overflow == int(any(c > x.capacity for c in counts))
         used, nxt = x.get_partitions(0), x.get_partitions(1)
         assert np.array_equal(used["blk_part"].astype(np.int64), w.blk_part(0)), where

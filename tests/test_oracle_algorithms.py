@@ -140,3 +140,16 @@ def test_alg5_direction():
         if k_act < k / 1.1 - 1e-9:
             assert d1 < 1.0
         assert abs(d1 - 1.0) <= 0.01 + 1e-6      # fine-grained scaling only
+
+
+def test_padding_overhead_hand_cases():
+    """Eq. 2-4 by hand: counts (3, 1, 2): m_t = 3, c = (0, 2, 1), C_t = 3 * 3 = 9; equal counts pad
+    nothing; one busy worker among four idle ones pads (n - 1) * m_t per receiver."""
+    assert oracle.padding_overhead([3, 1, 2]) == 9
+    assert oracle.padding_overhead([7, 7, 7, 7]) == 0
+    assert oracle.padding_overhead([10, 0, 0, 0, 0]) == 5 * 4 * 10
+    assert oracle.padding_overhead([0, 0]) == 0
+    assert oracle.padding_overhead([5]) == 0
+    # C_t = n * (n * m_t - k'), and f(t) of Eq. 5 is n * m_t / k'
+    k = [12, 30, 7, 21]
+    assert oracle.padding_overhead(k) == 4 * (4 * 30 - sum(k))
