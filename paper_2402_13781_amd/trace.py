@@ -5,7 +5,8 @@ Runs the HIP library (never a CPU substitute) over a workload of
 paper_2402_13781_amd.synthetic and prints one CSV line per iteration:
 the actual density k'/n_g against the target d (Sec. 5.2's density plots), the
 density error of Eq. 6, the traffic ratio f(t) of Eq. 5, the all-gather padding
-C_t of Eq. 4, the threshold, and the number of boundary moves Alg. 3 made.  Two
+C_t of Eq. 4, the threshold next to the error norm of Eq. 1 (the pair Sec. 5.3
+compares), and the number of boundary moves Alg. 3 made.  Two
 switches turn the paper's ablations on:
 
   --static-partitions   blk_move = 0: coarse-grained, never rebalanced (Sec. 4.1)
@@ -38,11 +39,11 @@ def run_trace(workload, steps, device="cuda:0", static_partitions=False, fixed_t
         kw["gamma"] = gamma
     cfg = binding.default_config(n_g=workload.n_g, block_size=workload.block_size,
                                  n_parts=workload.n_parts, density=workload.density,
-                                 threshold0=thr, **kw)
+                                 threshold0=thr, want_err_norm=1, **kw)
     x = binding.ExDyna(cfg, device)
     rows = []
     cols = ("t", "k_actual", "density", "density_error", "traffic_ratio", "padding_overhead",
-            "delta_used", "moves", "overflow")
+            "delta_used", "err_norm", "moves", "overflow")
     if out is not None:
         print(",".join(cols), file=out)
     for t in range(steps):
@@ -53,7 +54,7 @@ def run_trace(workload, steps, device="cuda:0", static_partitions=False, fixed_t
         row = dict(t=t, k_actual=s.k_actual, density=s.k_actual / workload.n_g,
                    density_error=s.density_error, traffic_ratio=s.traffic_ratio,
                    padding_overhead=s.padding_overhead,
-                   delta_used=s.delta_used, moves=s.moves, overflow=s.overflow)
+                   delta_used=s.delta_used, err_norm=s.err_norm, moves=s.moves, overflow=s.overflow)
         rows.append(row)
         if out is not None:
             print(",".join(f"{row[c]:.6g}" if isinstance(row[c], float) else str(row[c]) for c in cols),
