@@ -142,14 +142,14 @@ def test_alg5_direction():
         assert abs(d1 - 1.0) <= 0.01 + 1e-6      # fine-grained scaling only
 
 
-def test_padding_overhead_hand_cases():
-    """Eq. 2-4 by hand: counts (3, 1, 2): m_t = 3, c = (0, 2, 1), C_t = 3 * 3 = 9; equal counts pad
-    nothing; one busy worker among four idle ones pads (n - 1) * m_t per receiver."""
-    assert oracle.padding_overhead([3, 1, 2]) == 9
-    assert oracle.padding_overhead([7, 7, 7, 7]) == 0
-    assert oracle.padding_overhead([10, 0, 0, 0, 0]) == 5 * 4 * 10
-    assert oracle.padding_overhead([0, 0]) == 0
-    assert oracle.padding_overhead([5]) == 0
-    # C_t = n * (n * m_t - k'), and f(t) of Eq. 5 is n * m_t / k'
-    k = [12, 30, 7, 21]
-    assert oracle.padding_overhead(k) == 4 * (4 * 30 - sum(k))
+def test_padding_overhead_hand_cases(golden_dir):
+    """Eq. 2-4 by hand (tests/golden/eq4_padding.json)."""
+    for c in _load(golden_dir, "eq4_padding.json")["cases"]:
+        assert max(c["k"]) == c["m_t"] and len(c["k"]) * sum(c["c"]) == c["C_t"]   # the fixture is consistent
+        assert oracle.padding_overhead(c["k"]) == c["C_t"], c
+
+
+def test_reindex_hand_cases(golden_dir):
+    """Rank order to partition order (tests/golden/alg3_reindex.json)."""
+    for c in _load(golden_dir, "alg3_reindex.json")["cases"]:
+        assert oracle.reindex(c["k_rank"], c["t"]).tolist() == c["k_part"], c
