@@ -319,3 +319,20 @@ def test_product_is_rounded_before_the_sum():
     o.set_residual(np.full(32, e0, np.float32))
     o.step_scaled(np.full(32, g, np.float32), 0, eta)
     assert o.residual()[0] == two_step
+
+
+def test_untruncated_counts_drive_the_threshold_and_the_next_allocate():
+    """Capacity reading: what does not fit the output is still COUNTED.  Every gradient passes the
+    threshold, so the four partitions hold 256 each (balanced: the next Allocate moves nothing) and
+    k' = 1024 = 2k (above beta: the threshold rises); the 100 emitted pairs all lie in partition 0,
+    so counts cut at the capacity would look like (100, 0, 0, 0) and a k' of 100 < k / beta."""
+    n, b, P = 1024, 128, 4
+    g = np.full(n, 1.0, np.float32)
+    o = oracle.Oracle(n, b, P, 0.5, 0.5, gamma=0.01, beta=1.1, max_selected=100)
+    o.step(g)
+    assert o.k_actual == 1024 and o.k_emitted == 100
+    assert o.part_count().tolist() == [256, 256, 256, 256] and o.part_off().tolist() == [0, 100, 100, 100, 100]
+    assert o.threshold == np.float32(np.float32(0.5) * np.float32(1.01))      # exam = 2 > beta
+    bp0 = o.blk_part(0).copy()
+    o.step(np.zeros(n, np.float32))
+    assert np.array_equal(o.blk_part(0), bp0) and o.blk_part(0).tolist() == [2, 2, 2, 2]

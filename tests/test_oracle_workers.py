@@ -247,3 +247,15 @@ def test_model_update_over_a_workers_iteration():
     x = x0.copy()
     oracle.apply_update(x, idx, w.sum(), 1.0 / n)
     assert np.array_equal(x.view(np.uint32), want.view(np.uint32))
+
+
+def test_workers_threshold_uses_the_uncut_total():
+    """Two workers, every gradient passes, capacity 10 per worker: k' = 512 (> beta * k = 281.6),
+    not the 20 entries that were sent (< k / beta)."""
+    n_g, b = 512, 128
+    w = oracle.Workers(n_g, b, 2, 0.5, 0.5, gamma=0.01, beta=1.1, max_selected=10)
+    g = [np.full(n_g, 1.0, np.float32), np.full(n_g, -2.0, np.float32)]
+    w.step(g)
+    assert w.k_rank().tolist() == [256, 256] and w.rank_off().tolist() == [0, 10, 20]
+    assert w.k_actual == 512
+    assert w.threshold == np.float32(np.float32(0.5) * np.float32(1.01))
