@@ -204,3 +204,19 @@ def test_rebalancing_reduces_traffic_ratio():
     log(f"f(t): first {f[0]:.3f} last {f[-1]:.3f}")
     assert f[-1] < 0.8 * f[0] and f[-1] >= 1.0
     x.close()
+
+
+@pytest.mark.parametrize("counts", [(25, 10, 40, 25), (25, 40, 10, 25), (25, 25, 25, 25), (40, 10, 40, 10)])
+def test_partition_counts_exactly_at_the_average(counts):
+    """Alg. 3 compares k_i / avg with alpha = 1 strictly: a partition that holds exactly the average
+    is neither above nor below it.  The counts are planted exactly."""
+    n, b, P = 4096, 256, 4                       # four blocks per partition
+    g = np.full(n, 0.125, np.float32)
+    for p, c in enumerate(counts):
+        g[p * 1024 + 3: p * 1024 + 3 + 7 * c: 7] = 1.0 + p
+    log(f"case planted counts {counts}")
+    x, o = make_pair(n, b, P, 100 / n, 0.5, blk_move=1)
+    dev_g = torch.from_numpy(g).to(DEV)
+    run_trajectory(x, o, [dev_g, torch.zeros_like(dev_g), dev_g], tag=f"planted-{counts}")
+    assert o.part_count().sum() > 0
+    x.close()
