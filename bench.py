@@ -243,7 +243,9 @@ def main() -> int:
     if prof:
         ms = ms_events
         kern = {"k_stream_ms": round(float(ms[:, 0].mean()), 5),
-                "k_finish_ms": round(float(ms[:, 1].mean()), 5)}
+                "k_finish_ms": round(float(ms[:, 1].mean()), 5),
+                "k_stream_ms_p10_p50_p90": [round(float(v), 5) for v in np.percentile(ms[:, 0], [10, 50, 90])],
+                "k_finish_ms_p10_p50_p90": [round(float(v), 5) for v in np.percentile(ms[:, 1], [10, 50, 90])]}
         achieved = alg_bytes_per_elem * w.n_g / (ms[:, 0].mean() * 1e-3) / 1e9
         roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": round(achieved, 1),
                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
