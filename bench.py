@@ -61,6 +61,8 @@ def main() -> int:
     ap.add_argument("--block-size", type=int, default=0,
                     help="override the workload's block size b (any multiple of 32; multiples "
                          "of 256 take the faster kernel variant)")
+    ap.add_argument("--density", type=float, default=0.0,
+                    help="override the workload's target density d")
     ap.add_argument("--hbm-budget-gb", type=float, default=160.0,
                     help="HBM to spend on pre-generated gradient vectors")
     args = ap.parse_args()
@@ -82,6 +84,9 @@ def main() -> int:
     w = synthetic.WORKLOADS[args.config]
     if args.block_size:
         w = w.scaled(w.n_g, args.block_size)
+    if args.density:
+        import dataclasses
+        w = dataclasses.replace(w, density=args.density, name=f"{w.name}/d={args.density:g}")
     K, W = args.steps, args.warmup
     src = synthetic.GradientSource(w, dev)
 
