@@ -182,6 +182,9 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
     const size_t P = c->n_parts;
     L.n_tiles  = (c->n_g + kTile - 1) / kTile;
     L.chunk_shift = chunk_shift_for(c->density);
+    // ... but not so small that the compaction workgroups (16 chunks each) need a second round on
+    // the chip (256 CUs hold two of them each): a round is latency, the copy inside it is not
+    while (L.chunk_shift < kChunkShift && ((L.n_tiles >> L.chunk_shift) + 15) / 16 > 480) ++L.chunk_shift;
     L.n_chunks = (L.n_tiles + (1u << L.chunk_shift) - 1) >> L.chunk_shift;
     L.slots    = staging_slots(c->density);
     L.seg_shift = segment_shift(c->density);
