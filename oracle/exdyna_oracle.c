@@ -21,63 +21,70 @@ uint64_t exo_block_size(uint64_t n_g, uint64_t n_b)
     return temp - temp % 32;
 }
 
-/* Alg. 2 (topology)                                                  */
+/* Alg. 2 (topology), Sec. 4.1: the n_b blocks are dealt to the n partitions as evenly as whole
+ * blocks allow -- every partition holds floor(n_b / n) blocks and the first n_b mod n of them
+ * hold one more -- and a partition starts where the one before it ends.                     */
 void exo_partition(uint64_t n_b, uint32_t n, int64_t *blk_part, int64_t *blk_pos)
 {
-    int64_t quotient  = (int64_t)(n_b / n);
-    int64_t remainder = (int64_t)(n_b % n);
-    for (uint32_t i = 0; i < n; ++i) {
-        blk_pos[i] = 0;
-        if ((int64_t)i < remainder)
-            blk_part[i] = quotient + 1;
-        else
-            blk_part[i] = quotient;
+    const int64_t share = (int64_t)(n_b / n);
+    const int64_t extra = (int64_t)(n_b % n);
+    int64_t first = 0;
+    for (uint32_t p = 0; p < n; ++p) {
+        blk_part[p] = share + ((int64_t)p < extra ? 1 : 0);
+        blk_pos[p]  = first;
+        first += blk_part[p];
     }
-    for (uint32_t i = 1; i < n; ++i)
-        blk_pos[i] = blk_part[i - 1] + blk_pos[i - 1];
 }
 
-/* Alg. 3 (the sweep over adjacent pairs).  The re-indexing of k_t from rank order to partition
- * order (the loop ahead of the sweep) is done by the caller: here kvec is already indexed by
- * partition.                                                           */
+/* Alg. 3 (the sweep over adjacent pairs), Sec. 4.2.  A partition's load is its count of the
+ * last iteration over the fair share k'/n.  Walking the shared boundaries left to right, a
+ * boundary moves by blk_move blocks toward the overloaded side's interior when one side's load
+ * is above alpha and the other's below 1/alpha, unless the side that gives blocks away would
+ * be left with fewer than min_blk.  The counts are then corrected by what the moved blocks are
+ * expected to hold at the last iteration's overall density, so the next pair sees the
+ * corrected count of the partition the two pairs share.  kvec is indexed by partition: the
+ * re-indexing from rank order that precedes the sweep is the caller's.  alpha >= 1 makes the
+ * two cases exclude each other.  Returns the number of boundaries moved.                    */
 int exo_allocate(double *kvec, int64_t *blk_part, int64_t *blk_pos, uint32_t n,
                  uint64_t n_g, uint64_t sz_blk, int64_t blk_move, int64_t min_blk,
                  double alpha)
 {
-    double sum = 0.0;
-    for (uint32_t i = 0; i < n; ++i) sum += kvec[i];
-    /* Nothing selected: det would be 0/0.  No adjustment is made. */
-    if (!(sum > 0.0)) return 0;
+    double selected = 0.0;
+    for (uint32_t p = 0; p < n; ++p) selected += kvec[p];
+    /* Nothing selected: every load would be 0/0.  No boundary moves. */
+    if (!(selected > 0.0)) return 0;
 
-    double pk_prev   = sum / (double)n;
-    double den_prev  = sum / (double)n_g;
-    double inv_alpha = 1.0 / alpha;
-    int moves = 0;
+    const double fair_share = selected / (double)n;
+    const double density    = selected / (double)n_g;
+    const double carried    = (double)blk_move * (double)sz_blk * density; /* count that moves along */
+    const double low        = 1.0 / alpha;
+    int moved = 0;
 
-    for (uint32_t i = 0; i + 1 < n; ++i) {
-        double det    = kvec[i] / pk_prev;
-        double det2   = kvec[i + 1] / pk_prev;
-        double k_move = (double)blk_move * (double)sz_blk * den_prev;
-        if (det > alpha && det2 < inv_alpha) {
-            if (blk_part[i] - blk_move < min_blk) continue;
-            blk_part[i]     -= blk_move;
-            blk_part[i + 1] += blk_move;
-            blk_pos[i + 1]  -= blk_move;
-            kvec[i]         -= k_move;
-            kvec[i + 1]     += k_move;
-            ++moves;
-        }
-        if (det < inv_alpha && det2 > alpha) {
-            if (blk_part[i + 1] - blk_move < min_blk) continue;
-            blk_part[i]     += blk_move;
-            blk_part[i + 1] -= blk_move;
-            blk_pos[i + 1]  += blk_move;
-            kvec[i]         += k_move;
-            kvec[i + 1]     -= k_move;
-            ++moves;
+    for (uint32_t left = 0; left + 1 < n; ++left) {
+        const uint32_t right = left + 1;
+        const double load_left  = kvec[left] / fair_share;
+        const double load_right = kvec[right] / fair_share;
+        if (load_left > alpha && load_right < low) {
+            /* the left partition hands its last blocks to the right one */
+            if (blk_part[left] - blk_move < min_blk) continue;
+            blk_part[left]  -= blk_move;
+            blk_part[right] += blk_move;
+            blk_pos[right]  -= blk_move;
+            kvec[left]      -= carried;
+            kvec[right]     += carried;
+            ++moved;
+        } else if (load_left < low && load_right > alpha) {
+            /* the right partition hands its first blocks to the left one */
+            if (blk_part[right] - blk_move < min_blk) continue;
+            blk_part[left]  += blk_move;
+            blk_part[right] -= blk_move;
+            blk_pos[right]  += blk_move;
+            kvec[left]      += carried;
+            kvec[right]     -= carried;
+            ++moved;
         }
     }
-    return moves;
+    return moved;
 }
 
 /* Alg. 3 (cyclic allocation)                                                     */

@@ -336,3 +336,44 @@ def test_untruncated_counts_drive_the_threshold_and_the_next_allocate():
     bp0 = o.blk_part(0).copy()
     o.step(np.zeros(n, np.float32))
     assert np.array_equal(o.blk_part(0), bp0) and o.blk_part(0).tolist() == [2, 2, 2, 2]
+
+
+def test_fp16_nan_gradient_stays_nan_in_the_residual_and_is_never_selected():
+    """Alg. 1 (accumulate) with an fp16 gradient whose bits encode a NaN (exponent all ones,
+    non-zero fraction): the widened value is a NaN, so the product and the sum are NaN, Alg. 4's
+    comparison is false for it, and the entry stays in the residual as a NaN on every later
+    iteration.  An fp16 infinity (same exponent, zero fraction) IS selected: the two cases sit
+    one fraction bit apart, so a widening that confused them fails one of the two checks."""
+    n = 64
+    bits = np.zeros(n, np.uint16)
+    bits[3] = 0x7E00          # quiet NaN
+    bits[4] = 0xFC01          # negative NaN with the lowest fraction bit only
+    bits[5] = 0x7C00          # +inf
+    bits[6] = 0xFC00          # -inf
+    bits[7] = 0x4000          # 2.0
+    assert np.isnan(bits.view(np.float16)[[3, 4]]).all() and np.isinf(bits.view(np.float16)[[5, 6]]).all()
+    o = oracle.Oracle(n, 32, 2, 0.1, 1.0, max_selected=n)
+    o.step_scaled(bits, 2, 1.0)
+    assert o.out_idx().tolist() == [5, 6, 7]
+    assert o.out_val().tolist() == [np.inf, -np.inf, 2.0]
+    e = o.residual()
+    assert np.isnan(e[3]) and np.isnan(e[4])
+    assert np.count_nonzero(np.isnan(e)) == 2 and e[5] == 0 and e[6] == 0 and e[7] == 0
+    o.step_scaled(np.zeros(n, np.uint16), 2, 1.0)           # NaN + 0 stays NaN, still not selected
+    assert o.k_actual == 0 and o.k_emitted == 0
+    assert np.isnan(o.residual()[[3, 4]]).all()
+    assert np.isnan(o.err_norm())
+
+
+def test_traffic_ratio_when_nothing_is_selected():
+    """Eq. 5 is n * max_i k_i / k'; with k' = 0 it reads 0/0.  Reading taken: f(t) = 0 then (no
+    traffic, nothing to balance), while Eq. 6 still gives |k - 0| / n_g."""
+    n = 1024
+    o = oracle.Oracle(n, 128, 4, 0.25, 10.0)
+    o.step(np.full(n, 0.5, np.float32))
+    assert o.k_actual == 0 and o.part_count().tolist() == [0, 0, 0, 0]
+    assert o.traffic_ratio() == 0.0
+    assert o.density_error() == 0.25
+    assert oracle.padding_overhead(o.part_count()) == 0
+    o.step(np.full(n, 20.0, np.float32))                     # everything selected, evenly: f(t) = 1
+    assert o.k_actual == n and o.traffic_ratio() == 1.0

@@ -259,3 +259,32 @@ def test_workers_threshold_uses_the_uncut_total():
     assert w.k_rank().tolist() == [256, 256] and w.rank_off().tolist() == [0, 10, 20]
     assert w.k_actual == 512
     assert w.threshold == np.float32(np.float32(0.5) * np.float32(1.01))
+
+
+def test_err_norm_per_worker_and_mean_against_numpy():
+    """Eq. 1: the global error is the mean over the workers of the L2 norm of each worker's own
+    residual.  Workers get gradients of different scales so that no two terms coincide and the
+    mean differs from every term."""
+    n_g, b, n = 6000, 96, 4
+    rng = np.random.default_rng(123)
+    w = oracle.Workers(n_g, b, n, 0.02, 2e-3)
+    for t in range(3):
+        grads = [rng.laplace(0.0, 1e-3 * (1 + 2 * i), n_g).astype(np.float32) for i in range(n)]
+        w.step(grads)
+        terms = [float(np.linalg.norm(w.residual(i).astype(np.float64))) for i in range(n)]
+        assert len({round(v, 9) for v in terms}) == n
+        for i in range(n):
+            assert np.isclose(w.err_norm(i), terms[i], rtol=1e-12, atol=0.0)
+        assert np.isclose(w.err_norm(), np.mean(terms), rtol=1e-12, atol=0.0)
+        assert min(terms) < w.err_norm() < max(terms)
+
+
+def test_workers_traffic_ratio_when_nothing_is_selected():
+    """Eq. 5 at k' = 0 (0/0): reading taken is f(t) = 0, as in the one-device oracle."""
+    n_g, n = 2048, 4
+    w = oracle.Workers(n_g, 128, n, 0.1, 10.0)
+    w.step([np.full(n_g, 0.5, np.float32) for _ in range(n)])
+    assert w.k_actual == 0 and w.k_rank().tolist() == [0] * n
+    assert w.traffic_ratio() == 0.0
+    w.step([np.full(n_g, 20.0, np.float32) for _ in range(n)])   # every worker selects its whole partition
+    assert w.k_actual == n_g and w.traffic_ratio() == 1.0
