@@ -130,7 +130,17 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
  * stream capture of an EVEN number of consecutive exdyna_step calls (with
  * profiling off and fixed d_grad addresses) can therefore be replayed any
  * number of times; each replay advances the device state by that many
- * iterations and the getters keep reporting the last iteration. */
+ * iterations and the getters keep reporting the last iteration (every getter
+ * that synchronises also takes the iteration count from the device, so the
+ * host side follows the replays).
+ *
+ * Errors: every argument check happens before the first launch, so a negative
+ * return other than EXDYNA_EHIP means nothing was enqueued.  EXDYNA_EHIP means
+ * the HIP runtime refused a launch or an event record; the iteration counter
+ * has not advanced, but the first kernel may have run and left this
+ * iteration's counters and the residual half-updated: the context must not be
+ * stepped again -- restore the residual and call exdyna_set_state, or destroy
+ * the context. */
 int exdyna_step(exdyna_ctx *ctx, const float *d_grad, void *hip_stream);
 
 /* The same iteration with the learning rate fused in and a choice of gradient
@@ -181,8 +191,12 @@ int exdyna_step_scaled(exdyna_ctx *ctx, const void *d_grad, int grad_dtype, floa
  * moved from rank order to partition order (Alg. 3's re-indexing of the
  * partial-k vector) and drive Alg. 5 and Alg. 3 exactly as in exdyna_step; t advances.  stride may be 0 when
  * nothing was selected anywhere (the pointers may then be NULL).  Two kernels
- * in `select`, one in `exchange`; nothing synchronises.  Not for HIP-graph
- * replay: the owned partition is computed on the host from t. */
+ * in `select`, one in `exchange`; nothing synchronises.  The partition a worker
+ * owns and the re-indexing offset are computed inside the kernels from the
+ * iteration counter in device memory, so a worker-view iteration that follows
+ * a replayed HIP graph of steps selects the right partition, and an even number
+ * of select/exchange pairs can itself be captured under the rules given for
+ * exdyna_step. */
 int exdyna_worker_select(exdyna_ctx *ctx, const void *d_grad, int grad_dtype, float eta,
                          uint32_t rank, void *hip_stream);
 int exdyna_worker_exchange(exdyna_ctx *ctx, const uint32_t *d_idx_all,
@@ -276,7 +290,12 @@ const char *exdyna_strerror(int code);
 const char *exdyna_last_hip_error(const exdyna_ctx *ctx);
 
 /* Frees the host context.  Does not touch device memory; the caller must make
- * sure the stream has drained before freeing d_residual / d_workspace. */
+ * sure the stream has drained before freeing d_residual / d_workspace.  The
+ * library keeps a table of its live contexts and looks every handle up there
+ * before reading it: destroying a context twice, using it after exdyna_destroy,
+ * or passing memory that never was a context returns EXDYNA_ESTATE without
+ * touching that memory.  At most 1024 contexts can be live in one process
+ * (exdyna_init returns EXDYNA_ENOMEM beyond that). */
 int exdyna_destroy(exdyna_ctx *ctx);
 
 #ifdef __cplusplus

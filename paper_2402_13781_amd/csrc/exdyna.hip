@@ -64,6 +64,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 
 #include "exdyna.h"
@@ -104,7 +105,7 @@ struct exdyna_ctx {
     uint64_t      t;  // iterations completed (enqueued)
     uint32_t      phase;     // worker view: 1 between exdyna_worker_select and exdyna_worker_exchange
     uint32_t      rank;      // worker view: the rank of the pending selection
-    uint32_t      own_part;  // partition the current selection pass compares, or kAllParts
+    uint32_t      sel_rank;  // worker whose partition the current selection pass compares, or kAllParts
     float        *d_residual;
     char         *ws;
     hipStream_t   stream;  // stream of the most recent call
@@ -225,7 +226,46 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
     return L;
 }
 
-bool ctx_ok(const exdyna_ctx *c) { return c && c->magic == kMagic; }
+// Live contexts.  A handle is looked up here before it is dereferenced, so a
+// destroyed context, or memory that never was one, is turned away without being
+// read.  Fixed size: registering a context allocates nothing.
+constexpr uint32_t kMaxLive = 1024;
+std::mutex         g_live_mu;
+const exdyna_ctx  *g_live[kMaxLive];
+uint32_t           g_live_hi = 0;  // slots [0, g_live_hi) may be in use
+
+bool ctx_ok(const exdyna_ctx *c)
+{
+    if (!c) return false;
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    for (uint32_t i = 0; i < g_live_hi; ++i)
+        if (g_live[i] == c) return c->magic == kMagic;
+    return false;
+}
+
+bool ctx_register(const exdyna_ctx *c)
+{
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    for (uint32_t i = 0; i < kMaxLive; ++i)
+        if (!g_live[i]) {
+            g_live[i] = c;
+            if (i >= g_live_hi) g_live_hi = i + 1;
+            return true;
+        }
+    return false;
+}
+
+bool ctx_unregister(const exdyna_ctx *c)
+{
+    std::lock_guard<std::mutex> lock(g_live_mu);
+    for (uint32_t i = 0; i < g_live_hi; ++i)
+        if (g_live[i] == c) {
+            g_live[i] = nullptr;
+            while (g_live_hi && !g_live[g_live_hi - 1]) --g_live_hi;
+            return true;
+        }
+    return false;
+}
 
 int hip_fail(exdyna_ctx *c, hipError_t e, const char *what)
 {
@@ -272,7 +312,8 @@ void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
     for (uint32_t sh = 0; sh < 32; ++sh)
         if ((1u << sh) == A.gran_per_blk) A.gpb_shift = sh;
     A.parity = (uint32_t)(c->t & 1);
-    A.own_part = c->own_part;
+    A.sel_rank = c->sel_rank;
+    A.n_parts = c->cfg.n_parts;
     A.cur_part = slot_part(c, c->t);
     A.cur_pos = slot_pos(c, c->t);
     A.block_size = c->cfg.block_size;
@@ -313,8 +354,9 @@ FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
     A.pool_extra = c->lay.pool_extra;
     A.parity = (uint32_t)(t & 1);
     A.mode = mode;
-    A.own_part = c->own_part;
+    A.sel_rank = c->sel_rank;
     A.block_size = c->cfg.block_size;
+    A.n_parts = c->cfg.n_parts;
     return A;
 }
 
@@ -365,9 +407,8 @@ int step_impl(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, int6
     const bool norm = c->cfg.want_err_norm != 0;
     const bool prof = c->prof_slots != 0 && (c->t - c->prof_since) % c->prof_every == 0;
     hipEvent_t *ev = prof ? c->ev + 3 * (((c->t - c->prof_since) / c->prof_every) % c->prof_slots) : nullptr;
-    const uint32_t P = c->cfg.n_parts;
-    // Alg. 3 (cyclic allocation): the partition worker `rank` selects at iteration t
-    c->own_part = worker_rank < 0 ? kAllParts : (uint32_t)((c->t % P + (uint64_t)worker_rank) % P);
+    // the kernels work out which partition that worker owns from the device's iteration counter
+    c->sel_rank = worker_rank < 0 ? kAllParts : (uint32_t)worker_rank;
     const uint32_t mode = worker_rank < 0 ? kCtrlFull : kCtrlSelect;
 
     if (prof) HIP_TRY(c, hipEventRecord(ev[0], s));
@@ -394,6 +435,11 @@ int step_impl(exdyna_ctx *c, const void *d_grad, int grad_dtype, float eta, int6
     }
     return EXDYNA_OK;
 }
+
+// The device counts its iterations itself (a replayed HIP graph advances it without the
+// host's knowledge), so whenever a getter has synchronised and read the device state the host
+// counter is set from it.
+void adopt_device_iteration(exdyna_ctx *c, const DevState &st) { c->t = st.t; }
 
 // Iteration whose selection the getters describe: the last finished one, or the
 // one whose worker-view selection is waiting for its exchange.
@@ -459,7 +505,7 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
     c->t = 0;
     c->phase = 0;
     c->rank = 0;
-    c->own_part = kAllParts;
+    c->sel_rank = kAllParts;
     c->d_residual = d_residual;
     c->ws = static_cast<char *>(d_workspace);
     c->stream = static_cast<hipStream_t>(hip_stream);
@@ -509,6 +555,10 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
         return EXDYNA_EHIP;
     }
     c->magic = kMagic;
+    if (!ctx_register(c)) {
+        delete c;
+        return EXDYNA_ENOMEM;  // more live contexts than the registry holds
+    }
     *out = c;
     return EXDYNA_OK;
 }
@@ -553,7 +603,6 @@ int exdyna_worker_exchange(exdyna_ctx *c, const uint32_t *d_idx_all, const uint6
     X.own_val = at<float>(c, c->lay.out_val);
     X.stride = stride;
     X.rank = c->rank;
-    X.t_mod_p = (uint32_t)(c->t % P);
     const uint64_t gx = (stride + kFinishWG - 1) / kFinishWG;
     const dim3 grid((uint32_t)(gx ? gx : 1), P + 1);
     if (c->cfg.want_err_norm)
@@ -563,7 +612,7 @@ int exdyna_worker_exchange(exdyna_ctx *c, const uint32_t *d_idx_all, const uint6
     HIP_TRY(c, hipGetLastError());
     c->t += 1;
     c->phase = 0;
-    c->own_part = kAllParts;
+    c->sel_rank = kAllParts;
     return EXDYNA_OK;
 }
 
@@ -600,6 +649,7 @@ int exdyna_get_selected(exdyna_ctx *c, const uint32_t **d_idx, const float **d_v
         HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st,
                                   hipMemcpyDeviceToHost, c->stream));
         HIP_TRY(c, hipStreamSynchronize(c->stream));
+        adopt_device_iteration(c, st);
         if (h_k_actual) *h_k_actual = st.own_actual;
         if (h_k_emitted) *h_k_emitted = st.own_emitted;
     }
@@ -620,6 +670,13 @@ int exdyna_get_partitions(exdyna_ctx *c, int which, uint32_t *h_blk_pos, uint32_
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (which != 0 && which != 1) return EXDYNA_EINVAL;
+    {
+        DevState st;
+        HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st, hipMemcpyDeviceToHost,
+                                  c->stream));
+        HIP_TRY(c, hipStreamSynchronize(c->stream));
+        adopt_device_iteration(c, st);
+    }
     if (which == 0 && !have_iteration(c)) return EXDYNA_ESTATE;  // no step has selected yet
     if (which == 1 && c->phase) return EXDYNA_ESTATE;  // the pending exchange computes it
     const uint32_t P = c->cfg.n_parts;
@@ -685,6 +742,7 @@ int exdyna_get_stats(exdyna_ctx *c, exdyna_stats *h_out)
     HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st, hipMemcpyDeviceToHost,
                               c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    adopt_device_iteration(c, st);
     h_out->t = st.t;
     h_out->k_actual = st.k_actual;
     h_out->k_emitted = st.k_emitted;
@@ -711,7 +769,16 @@ int exdyna_get_dims(const exdyna_ctx *c, uint64_t *h_n_blocks, uint64_t *h_capac
 }
 
 namespace {
-void drop_events_fwd(exdyna_ctx *c);
+void drop_events(exdyna_ctx *c)
+{
+    if (c->ev) {
+        for (uint32_t i = 0; i < 3 * c->prof_slots; ++i) (void)hipEventDestroy(c->ev[i]);
+        free(c->ev);
+    }
+    c->ev = nullptr;
+    c->prof_slots = 0;
+}
+
 // Saved state (Alg. 1's loop-carried variables other than the residual, which the
 // caller owns): a small header, then blk_part[P] and blk_pos[P] of the topology
 // the next iteration will select with.
@@ -746,6 +813,7 @@ int exdyna_get_state(exdyna_ctx *c, void *h_state, size_t bytes)
     HIP_TRY(c, hipMemcpyAsync(out + sizeof(StateHeader), slot_part(c, c->t),
                               2 * P * sizeof(int32_t), hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
+    adopt_device_iteration(c, st);
     StateHeader h{};
     h.magic = kStateMagic;
     h.n_g = c->cfg.n_g;
@@ -782,11 +850,11 @@ int exdyna_set_state(exdyna_ctx *c, const void *h_state, size_t bytes, void *hip
     c->stream = s;
     if (c->prof_slots) {
         HIP_TRY(c, hipStreamSynchronize(s));
-        drop_events_fwd(c);
+        drop_events(c);
     }
     c->t = h.t;
     c->phase = 0;  // a selection waiting for its exchange is dropped
-    c->own_part = kAllParts;
+    c->sel_rank = kAllParts;
     const Layout &L = c->lay;
     HIP_TRY(c, hipMemcpyAsync(slot_part(c, c->t), part, 2 * P * sizeof(int32_t),
                               hipMemcpyHostToDevice, s));
@@ -805,22 +873,6 @@ int exdyna_set_state(exdyna_ctx *c, const void *h_state, size_t bytes, void *hip
     HIP_TRY(c, hipStreamSynchronize(s));  // h_state may be freed by the caller on return
     return EXDYNA_OK;
 }
-
-namespace {
-void drop_events(exdyna_ctx *c)
-{
-    if (c->ev) {
-        for (uint32_t i = 0; i < 3 * c->prof_slots; ++i) (void)hipEventDestroy(c->ev[i]);
-        free(c->ev);
-    }
-    c->ev = nullptr;
-    c->prof_slots = 0;
-}
-}  // namespace
-
-namespace {
-void drop_events_fwd(exdyna_ctx *c) { drop_events(c); }
-}  // namespace
 
 int exdyna_set_profiling(exdyna_ctx *c, uint32_t n_slots, uint32_t every)
 {
@@ -884,7 +936,7 @@ const char *exdyna_last_hip_error(const exdyna_ctx *c) { return ctx_ok(c) ? c->h
 int exdyna_destroy(exdyna_ctx *c)
 {
     if (!c) return EXDYNA_ENULL;
-    if (c->magic != kMagic) return EXDYNA_ESTATE;
+    if (!ctx_unregister(c)) return EXDYNA_ESTATE;  // never a context, or destroyed already: not touched
     drop_events(c);
     c->magic = 0;
     delete c;

@@ -24,7 +24,6 @@ struct ExchangeArgs {
     const float    *own_val;  // values of this worker's own list
     uint64_t        stride;
     uint32_t        rank;     // this worker
-    uint32_t        t_mod_p;  // iteration mod P
 };
 
 template <bool NORM>
@@ -37,11 +36,12 @@ k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
         if (blockIdx.x != 0) return;
         __shared__ CtrlShared S;
         if (tid < P) {
+            const uint32_t t_mod_p = (uint32_t)(A.st->t % P);  // read before this workgroup advances it
             S.lpos[tid]  = A.cur_pos[tid];
             S.lpart[tid] = A.cur_part[tid];
             // rank tid selected partition (t mod P + tid) mod P (Alg. 3 (cyclic allocation))
             const uint64_t k_r = X.counts[tid];
-            S.cnt[(X.t_mod_p + tid) % P] = (uint32_t)(k_r < prm.n_g ? k_r : prm.n_g);
+            S.cnt[(t_mod_p + tid) % P] = (uint32_t)(k_r < prm.n_g ? k_r : prm.n_g);
         }
         __syncthreads();
         control_decide(A, prm, S, kCtrlUpdate);

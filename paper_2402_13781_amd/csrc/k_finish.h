@@ -30,8 +30,9 @@ struct FinishArgs {
     double         *err_slots_next;  // cleared here
     uint32_t        n_tiles, n_chunks, n_segs, seg_shift, chunk_shift, slots_min, pool_extra, parity;
     uint32_t        mode;            // kCtrlFull or kCtrlSelect
-    uint32_t        own_part;        // worker view: the partition that was compared; else kAllParts
+    uint32_t        sel_rank;        // worker view: the worker whose partition was compared; else kAllParts
     uint32_t        block_size;
+    uint32_t        n_parts;
 };
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
@@ -561,8 +562,9 @@ __device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
 
     uint64_t flagged = __ballot((word & kFlag) != 0);
     uint32_t e_lo = 0u, e_hi = 0xFFFFFFFFu;
-    if (flagged && A.own_part != kAllParts)
-        partition_elems(A.cur_part, A.cur_pos, A.own_part, A.block_size, n_g, e_lo, e_hi);
+    if (flagged && A.sel_rank != kAllParts)  // the iteration counter moves only after the exchange
+        partition_elems(A.cur_part, A.cur_pos, owned_partition(A.st->t, A.sel_rank, A.n_parts),
+                        A.block_size, n_g, e_lo, e_hi);
     while (flagged) {  // wave-uniform
         const uint32_t l = (uint32_t)__ffsll((unsigned long long)flagged) - 1u;
         flagged &= flagged - 1u;

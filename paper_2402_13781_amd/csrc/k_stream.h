@@ -24,13 +24,21 @@ struct StreamArgs {
     uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
     uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
     uint32_t        one_counter;  // a block is exactly one segment: blk_cnt doubles as seg_cnt
-    // worker view (Alg. 1 (Sparsify)): compare only inside partition own_part of this
-    // iteration's topology; kAllParts = everywhere
-    uint32_t        own_part;
+    // worker view (Alg. 1 (Sparsify)): compare only inside the partition that worker sel_rank
+    // owns at this iteration (Alg. 3 (cyclic allocation), from the device's own iteration
+    // counter); kAllParts = everywhere
+    uint32_t        sel_rank;
+    uint32_t        n_parts;
     const int32_t  *cur_part;
     const int32_t  *cur_pos;
     uint32_t        block_size;  // b (the generic variant counts and masks by element index)
 };
+
+// Alg. 3 (cyclic allocation): the partition worker `rank` selects at iteration t.
+__device__ __forceinline__ uint32_t owned_partition(uint64_t t, uint32_t rank, uint32_t n_parts)
+{
+    return (uint32_t)((t % n_parts + rank) % n_parts);
+}
 
 // Gradient range [lo, hi) of partition p, cut at n_g (Alg. 3 (partition range)).
 __device__ __forceinline__ void partition_elems(const int32_t *part, const int32_t *pos, uint32_t p,
@@ -71,11 +79,12 @@ k_stream(StreamArgs A)
     float nrm = 0.f;
     uint32_t g_lo = 0u, g_hi = 0xFFFFFFFFu;  // granules that are compared at all
     uint32_t e_lo = 0u, e_hi = 0xFFFFFFFFu;  // GEN: the same as a gradient range
-    if (A.own_part != kAllParts) {
+    if (A.sel_rank != kAllParts) {
+        const uint32_t own_part = owned_partition(A.st->t, A.sel_rank, A.n_parts);
         if (GEN)
-            partition_elems(A.cur_part, A.cur_pos, A.own_part, A.block_size, A.n_g, e_lo, e_hi);
+            partition_elems(A.cur_part, A.cur_pos, own_part, A.block_size, A.n_g, e_lo, e_hi);
         else
-            partition_granules(A.cur_part, A.cur_pos, A.own_part, A.gran_per_blk, g_lo, g_hi);
+            partition_granules(A.cur_part, A.cur_pos, own_part, A.gran_per_blk, g_lo, g_hi);
     }
 
     if (live && fast) {

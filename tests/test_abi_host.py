@@ -103,6 +103,28 @@ def test_init_and_step_argument_errors_without_a_gpu():
     assert L.exdyna_destroy(C.cast(junk, C.c_void_p)) == binding.EXDYNA_ESTATE
 
 
+def test_a_handle_that_is_not_a_live_context_is_never_read():
+    """Double destroy / use after destroy: the library looks a handle up in its table of live
+    contexts before touching it.  An address in an unmapped page would fault if it were read."""
+    L = binding.load()
+    stale = C.c_void_p(0x10)
+    fake = C.c_void_p(0x7000_0000_1000)
+    st = binding.Stats()
+    n = C.c_size_t()
+    assert L.exdyna_destroy(stale) == binding.EXDYNA_ESTATE
+    assert L.exdyna_destroy(stale) == binding.EXDYNA_ESTATE
+    assert L.exdyna_step(stale, fake, None) == binding.EXDYNA_ESTATE
+    assert L.exdyna_step_scaled(stale, fake, binding.EXDYNA_F16, 1.0, None) == binding.EXDYNA_ESTATE
+    assert L.exdyna_worker_select(stale, fake, binding.EXDYNA_F32, 1.0, 0, None) == binding.EXDYNA_ESTATE
+    assert L.exdyna_worker_exchange(stale, fake, fake, 4, fake, None) == binding.EXDYNA_ESTATE
+    assert L.exdyna_get_stats(stale, C.byref(st)) == binding.EXDYNA_ESTATE
+    assert L.exdyna_get_selected(stale, None, None, None, None, None) == binding.EXDYNA_ESTATE
+    assert L.exdyna_get_dims(stale, None, None) == binding.EXDYNA_ESTATE
+    assert L.exdyna_state_bytes(stale, C.byref(n)) == binding.EXDYNA_ESTATE
+    assert L.exdyna_set_profiling(stale, 4, 1) == binding.EXDYNA_ESTATE
+    assert L.exdyna_last_hip_error(stale) == b""
+
+
 def test_strerror_is_total():
     for code in range(-8, 2):
         assert binding.strerror(code)
