@@ -120,6 +120,34 @@ int exdyna_workspace_bytes(const exdyna_config *cfg, size_t *h_bytes);
 int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
                 void *d_workspace, size_t ws_bytes, void *hip_stream);
 
+/* exdyna_init for callers that cannot allocate device memory -- code running under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc: the state, counters,
+ * tables and staging slots that exdyna_init lays into a caller-provided workspace live in a
+ * device array built into the library instead (EXDYNA_STATIC_SCRATCH_BYTES per device, held
+ * from the first call on that device until the process ends).  The caller still passes the
+ * residual and the two output arrays: d_out_idx and d_out_val, cfg->max_selected entries
+ * each (max_selected must be set, not 0), 4-byte aligned; exdyna_get_selected returns these
+ * same pointers.  The context itself is built-in storage too, so neither this call nor any
+ * later call on the context (steps, getters, exdyna_destroy) allocates or frees device
+ * memory, and this call allocates no host memory either.  Everything else -- exdyna_step
+ * and the other entry points, results, error codes -- is exactly as for a context made by
+ * exdyna_init.
+ *  - EXDYNA_ENOMEM: the configuration needs more scratch than the built-in array holds
+ *    (25 million gradients at density 0.01 or 138 million at 0.001, with four times
+ *    the target count as capacity, still fit; the exact need is exdyna_workspace_bytes
+ *    minus 8 bytes per output pair).
+ *  - EXDYNA_ESTATE: the current device's built-in context is still live.  There is ONE per
+ *    device because all of them would share that device's array: destroy it before making
+ *    the next (whose set-up clears what must start at zero; the rest of the array keeps the
+ *    last context's contents and is overwritten before it is read).  Work of a destroyed
+ *    built-in context that is still running on the device when the next one is created
+ *    races with it: drain the stream first, as before freeing a workspace.
+ *  - EXDYNA_EINVAL also for max_selected = 0 and for a device ordinal above 15.
+ * The device that is current at the call is the one whose array is used. */
+#define EXDYNA_STATIC_SCRATCH_BYTES (64u << 20)
+int exdyna_init_static(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
+                       uint32_t *d_out_idx, float *d_out_val, void *hip_stream);
+
 /* One iteration (see the top of this file).  d_grad: n_g floats, 16-byte
  * aligned, read only, already scaled by the learning rate (the accumulate is a
  * single fp32 add).  Asynchronous: returns after enqueueing two kernels.

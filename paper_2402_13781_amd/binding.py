@@ -20,6 +20,7 @@ EXDYNA_OK, EXDYNA_EINVAL, EXDYNA_ENULL, EXDYNA_EALIGN, EXDYNA_ESTATE, EXDYNA_ENO
 # every symbol include/exdyna.h declares
 SYMBOLS = (
     "exdyna_default_config", "exdyna_block_size_from_nb", "exdyna_workspace_bytes", "exdyna_init",
+    "exdyna_init_static",
     "exdyna_step", "exdyna_step_scaled", "exdyna_worker_select", "exdyna_worker_exchange",
     "exdyna_apply_update", "exdyna_get_selected", "exdyna_get_count_pointers", "exdyna_get_partitions", "exdyna_get_block_counts",
     "exdyna_get_part_counts", "exdyna_get_stats", "exdyna_get_dims", "exdyna_set_profiling",
@@ -72,6 +73,7 @@ def load() -> C.CDLL:
     L.exdyna_block_size_from_nb.argtypes = [u64, u64, u32, P(u32)]
     L.exdyna_workspace_bytes.argtypes = [P(Config), P(C.c_size_t)]
     L.exdyna_init.argtypes = [P(vp), P(Config), vp, vp, C.c_size_t, vp]
+    L.exdyna_init_static.argtypes = [P(vp), P(Config), vp, vp, vp, vp]
     L.exdyna_step.argtypes = [vp, vp, vp]
     L.exdyna_step_scaled.argtypes = [vp, vp, C.c_int, C.c_float, vp]
     L.exdyna_worker_select.argtypes = [vp, vp, C.c_int, C.c_float, u32, vp]
@@ -141,7 +143,9 @@ class ExDyna:
     its state, counters, staging slots and output pairs in.
     """
 
-    def __init__(self, cfg: Config, device="cuda:0", stream=None):
+    def __init__(self, cfg: Config, device="cuda:0", stream=None, static_scratch: bool = False):
+        """static_scratch: create the context with exdyna_init_static (the library's built-in
+        device array instead of a torch workspace; cfg.max_selected must be set)."""
         import torch
 
         self._torch = torch
@@ -150,13 +154,21 @@ class ExDyna:
         self.device = torch.device(device)
         self._h = C.c_void_p()
         nbytes = workspace_bytes(cfg)            # validates the configuration on the host
+        self.workspace = self.out_idx = self.out_val = None
         with torch.cuda.device(self.device):
             self.residual = torch.empty(cfg.n_g, dtype=torch.float32, device=self.device)
-            self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
-            rc = self._L.exdyna_init(C.byref(self._h), C.byref(cfg), self.residual.data_ptr(),
-                                     self.workspace.data_ptr(), nbytes, self._stream_ptr(stream))
+            if static_scratch:
+                self.out_idx = torch.empty(max(cfg.max_selected, 1), dtype=torch.int32, device=self.device)
+                self.out_val = torch.empty(max(cfg.max_selected, 1), dtype=torch.float32, device=self.device)
+                rc = self._L.exdyna_init_static(C.byref(self._h), C.byref(cfg), self.residual.data_ptr(),
+                                                self.out_idx.data_ptr(), self.out_val.data_ptr(),
+                                                self._stream_ptr(stream))
+            else:
+                self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
+                rc = self._L.exdyna_init(C.byref(self._h), C.byref(cfg), self.residual.data_ptr(),
+                                         self.workspace.data_ptr(), nbytes, self._stream_ptr(stream))
         if rc:
-            raise ExDynaError(rc, "exdyna_init")
+            raise ExDynaError(rc, "exdyna_init_static" if static_scratch else "exdyna_init")
         nb, cap = C.c_uint64(), C.c_uint64()
         self._L.exdyna_get_dims(self._h, C.byref(nb), C.byref(cap))
         self.n_blocks, self.capacity = nb.value, cap.value
@@ -174,12 +186,25 @@ class ExDyna:
             raise ExDynaError(rc, what, detail)
 
     def _view(self, ptr: int, n: int, dtype):
-        """A torch view of `n` items of the workspace starting at device address `ptr`."""
+        """A torch view of `n` items of device memory the library handed out at address `ptr`:
+        inside the torch workspace, inside the caller's output arrays, or (built-in context)
+        inside the library's own device array."""
         torch = self._torch
-        off = ptr - self.workspace.data_ptr()
         item = torch.empty((), dtype=dtype).element_size()
-        assert 0 <= off and off + n * item <= self.workspace.numel()
-        return self.workspace[off: off + n * item].view(dtype)
+        for base in (self.workspace, self.out_idx, self.out_val):
+            if base is None:
+                continue
+            off = ptr - base.data_ptr()
+            if 0 <= off and off + n * item <= base.numel() * base.element_size():
+                return base.view(torch.uint8)[off: off + n * item].view(dtype)
+        assert self.workspace is None, "pointer outside the workspace"
+        if n == 0:
+            return torch.empty(0, dtype=dtype, device=self.device)
+
+        class _Raw:          # memory torch did not allocate, described by its address
+            __cuda_array_interface__ = {"shape": (n * item,), "typestr": "|u1", "data": (ptr, False),
+                                        "version": 2}
+        return torch.as_tensor(_Raw(), device=self.device).view(dtype)
 
     def close(self):
         if self._h:

@@ -108,6 +108,9 @@ struct exdyna_ctx {
     uint32_t      sel_rank;  // worker whose partition the current selection pass compares, or kAllParts
     float        *d_residual;
     char         *ws;
+    uint32_t     *d_out_idx;   // output pairs: inside the workspace, or the caller's arrays
+    float        *d_out_val;
+    int           static_dev;  // >= 0: this is the built-in context of that device (its scratch is the static array)
     hipStream_t   stream;  // stream of the most recent call
     uint32_t      prof_slots;  // 0 = profiling off
     uint64_t      prof_since;  // first iteration recorded with the current events
@@ -177,7 +180,7 @@ uint32_t chunk_shift_for(double density)
     return sh;
 }
 
-Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
+Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap, bool with_outputs = true)
 {
     Layout L{};
     const size_t P = c->n_parts;
@@ -220,8 +223,10 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap)
     }
     L.slot_tab  = take(2 * L.n_tiles * sizeof(uint2));        // {first slot, slots} per tile, two parities
     L.stage     = take(L.pool_pairs * sizeof(uint2));
-    L.out_idx   = take(cap * sizeof(uint32_t));
-    L.out_val   = take(cap * sizeof(float));
+    if (with_outputs) {
+        L.out_idx = take(cap * sizeof(uint32_t));
+        L.out_val = take(cap * sizeof(float));
+    }
     L.total     = off;
     return L;
 }
@@ -341,8 +346,8 @@ FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
     A.nxt_pos = slot_pos(c, t + 1);
     A.part_cnt = at<uint64_t>(c, c->lay.part_cnt);
     A.part_off = at<uint64_t>(c, c->lay.part_off);
-    A.out_idx = at<uint32_t>(c, c->lay.out_idx);
-    A.out_val = at<float>(c, c->lay.out_val);
+    A.out_idx = c->d_out_idx;
+    A.out_val = c->d_out_val;
     A.err_slots = err_slots_of(c, t);
     A.err_slots_next = err_slots_of(c, t + 1);
     A.n_tiles = (uint32_t)c->lay.n_tiles;
@@ -446,6 +451,90 @@ void adopt_device_iteration(exdyna_ctx *c, const DevState &st) { c->t = st.t; }
 bool have_iteration(const exdyna_ctx *c) { return c->t + c->phase > 0; }
 uint64_t last_iteration(const exdyna_ctx *c) { return c->t + c->phase - 1; }
 
+
+// ---- the entry point for callers that cannot allocate -------------------------------
+// Everything exdyna_init lays into the caller's workspace except the output pairs lives in
+// this file-scope device array instead.  Each device the library runs on holds its own
+// copy; host code uses the address hipGetSymbolAddress returns for the current device,
+// never the array's name.
+constexpr size_t kStaticScratchBytes = (size_t)EXDYNA_STATIC_SCRATCH_BYTES;
+constexpr int    kMaxStaticDevices   = 16;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+struct StaticContext {
+    char      *scratch_ptr;  // device address of `scratch` on this device, once asked for
+    bool       live;
+    exdyna_ctx ctx;          // the built-in context itself: no host allocation either
+};
+StaticContext g_static[kMaxStaticDevices];
+std::mutex    g_static_mu;
+
+// Fills *c and enqueues the set-up kernels (Alg. 1 (initialisation), Alg. 2): the part
+// exdyna_init and exdyna_init_static share.  Counters, tables and state are cleared here,
+// so whatever an earlier context left in the scratch memory does not matter; the staging
+// pool and the outputs are written before they are read in every iteration.
+int init_context(exdyna_ctx *c, const exdyna_config *cfg, const Layout &L, uint64_t n_b, uint64_t cap,
+                 float *d_residual, char *ws, uint32_t *d_out_idx, float *d_out_val, int static_dev,
+                 void *hip_stream)
+{
+    c->cfg = *cfg;
+    c->lay = L;
+    c->n_b = n_b;
+    c->cap = cap;
+    c->t = 0;
+    c->phase = 0;
+    c->rank = 0;
+    c->sel_rank = kAllParts;
+    c->d_residual = d_residual;
+    c->ws = ws;
+    c->d_out_idx = d_out_idx;
+    c->d_out_val = d_out_val;
+    c->static_dev = static_dev;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    c->prof_slots = 0;
+    c->prof_every = 1;
+    c->ev = nullptr;
+    c->hip_err[0] = 0;
+
+    CtrlParams &p = c->prm;
+    p.n_g = cfg->n_g;
+    p.cap = cap;
+    p.k = cfg->density * (double)cfg->n_g;
+    p.alpha = cfg->alpha;
+    p.inv_alpha = 1.0 / cfg->alpha;
+    p.beta = cfg->beta;
+    p.inv_beta = 1.0 / cfg->beta;
+    p.sf_hi = (float)(1.0 + cfg->gamma);           // Alg. 5 (factor above beta)
+    p.sf_mid = (float)(1.0 + 0.25 * cfg->gamma);   // Alg. 5 (factor inside the band)
+    p.sf_lo = (float)(1.0 - cfg->gamma);           // Alg. 5 (factor below 1/beta)
+    p.n_b = (uint32_t)n_b;
+    p.n_parts = cfg->n_parts;
+    p.block_size = cfg->block_size;
+    p.blk_move = cfg->blk_move;
+    p.min_blk = cfg->min_blk;
+
+    hipStream_t s = c->stream;
+    const uint32_t P = cfg->n_parts;
+    // residual <- 0 (Alg. 1 (local-error initialisation)); counters start clean
+    hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, s,
+                       reinterpret_cast<uint32_t *>(d_residual), 0u, (size_t)cfg->n_g);
+    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
+                       (size_t)(2 * n_b));
+    hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.seg_cnt), 0u,
+                       (size_t)(2 * L.n_segs));
+    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.tile_cnt), 0u,
+                       L.n_tiles);
+    hipLaunchKernelGGL(k_init_slot_tab, dim3(256), dim3(256), 0, s, slot_tab_of(c, 0), slot_tab_of(c, 1),
+                       (uint32_t)L.n_tiles, L.slots);
+    const uint32_t init_threads = (P + 1 > 2 * kErrSlots ? P + 1 : 2 * kErrSlots);
+    hipLaunchKernelGGL(k_init_state, dim3((init_threads + 255) / 256), dim3(256), 0, s,
+                       at<DevState>(c, L.state), slot_part(c, 0), slot_pos(c, 0), slot_part(c, 1),
+                       slot_pos(c, 1), at<uint64_t>(c, L.part_cnt), at<uint64_t>(c, L.part_off),
+                       at<double>(c, L.err_slots), cfg->threshold0, (uint32_t)n_b, P);
+    if (hipGetLastError() != hipSuccess) return EXDYNA_EHIP;
+    c->magic = kMagic;
+    return EXDYNA_OK;
+}
 }  // namespace
 
 extern "C" {
@@ -498,67 +587,54 @@ int exdyna_init(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual, v
 
     exdyna_ctx *c = new (std::nothrow) exdyna_ctx();
     if (!c) return EXDYNA_ENOMEM;
-    c->cfg = *cfg;
-    c->lay = L;
-    c->n_b = n_b;
-    c->cap = cap;
-    c->t = 0;
-    c->phase = 0;
-    c->rank = 0;
-    c->sel_rank = kAllParts;
-    c->d_residual = d_residual;
-    c->ws = static_cast<char *>(d_workspace);
-    c->stream = static_cast<hipStream_t>(hip_stream);
-    c->prof_slots = 0;
-    c->prof_every = 1;
-    c->ev = nullptr;
-    c->hip_err[0] = 0;
-
-    CtrlParams &p = c->prm;
-    p.n_g = cfg->n_g;
-    p.cap = cap;
-    p.k = cfg->density * (double)cfg->n_g;
-    p.alpha = cfg->alpha;
-    p.inv_alpha = 1.0 / cfg->alpha;
-    p.beta = cfg->beta;
-    p.inv_beta = 1.0 / cfg->beta;
-    p.sf_hi = (float)(1.0 + cfg->gamma);           // Alg. 5 (factor above beta)
-    p.sf_mid = (float)(1.0 + 0.25 * cfg->gamma);   // Alg. 5 (factor inside the band)
-    p.sf_lo = (float)(1.0 - cfg->gamma);           // Alg. 5 (factor below 1/beta)
-    p.n_b = (uint32_t)n_b;
-    p.n_parts = cfg->n_parts;
-    p.block_size = cfg->block_size;
-    p.blk_move = cfg->blk_move;
-    p.min_blk = cfg->min_blk;
-
-    hipStream_t s = c->stream;
-    const uint32_t P = cfg->n_parts;
-    // residual <- 0 (Alg. 1 (local-error initialisation)); counters start clean
-    hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, s,
-                       reinterpret_cast<uint32_t *>(d_residual), 0u, (size_t)cfg->n_g);
-    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
-                       (size_t)(2 * n_b));
-    hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.seg_cnt), 0u,
-                       (size_t)(2 * L.n_segs));
-    hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.tile_cnt), 0u,
-                       L.n_tiles);
-    hipLaunchKernelGGL(k_init_slot_tab, dim3(256), dim3(256), 0, s, slot_tab_of(c, 0), slot_tab_of(c, 1),
-                       (uint32_t)L.n_tiles, L.slots);
-    const uint32_t init_threads = (P + 1 > 2 * kErrSlots ? P + 1 : 2 * kErrSlots);
-    hipLaunchKernelGGL(k_init_state, dim3((init_threads + 255) / 256), dim3(256), 0, s,
-                       at<DevState>(c, L.state), slot_part(c, 0), slot_pos(c, 0), slot_part(c, 1),
-                       slot_pos(c, 1), at<uint64_t>(c, L.part_cnt), at<uint64_t>(c, L.part_off),
-                       at<double>(c, L.err_slots), cfg->threshold0, (uint32_t)n_b, P);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) {
+    char *ws = static_cast<char *>(d_workspace);
+    rc = init_context(c, cfg, L, n_b, cap, d_residual, ws, reinterpret_cast<uint32_t *>(ws + L.out_idx),
+                      reinterpret_cast<float *>(ws + L.out_val), -1, hip_stream);
+    if (rc == EXDYNA_OK && !ctx_register(c)) rc = EXDYNA_ENOMEM;  // more live contexts than the table holds
+    if (rc != EXDYNA_OK) {
         delete c;
-        return EXDYNA_EHIP;
+        return rc;
     }
-    c->magic = kMagic;
-    if (!ctx_register(c)) {
-        delete c;
-        return EXDYNA_ENOMEM;  // more live contexts than the registry holds
+    *out = c;
+    return EXDYNA_OK;
+}
+
+int exdyna_init_static(exdyna_ctx **out, const exdyna_config *cfg, float *d_residual,
+                       uint32_t *d_out_idx, float *d_out_val, void *hip_stream)
+{
+    if (!out) return EXDYNA_ENULL;
+    *out = nullptr;
+    if (!cfg || !d_residual || !d_out_idx || !d_out_val) return EXDYNA_ENULL;
+    uint64_t n_b, cap;
+    int rc = validate_config(cfg, &n_b, &cap);
+    if (rc) return rc;
+    if (cfg->max_selected == 0) return EXDYNA_EINVAL;  // the caller sized its output arrays: it must say how
+    if ((uintptr_t)d_residual % 16 != 0 || (uintptr_t)d_out_idx % 4 != 0 || (uintptr_t)d_out_val % 4 != 0)
+        return EXDYNA_EALIGN;
+    const Layout L = make_layout(cfg, n_b, cap, false);
+    if (L.total > kStaticScratchBytes) return EXDYNA_ENOMEM;  // beyond what the static array holds
+
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess) return EXDYNA_EHIP;
+    if (dev < 0 || dev >= kMaxStaticDevices) return EXDYNA_EINVAL;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    StaticContext &sc = g_static[dev];
+    if (sc.live) return EXDYNA_ESTATE;  // one built-in context per device: its scratch is shared
+    if (!sc.scratch_ptr) {
+        // the array's name is a host-side stand-in; its address on this device is asked for once
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return EXDYNA_EHIP;
+        sc.scratch_ptr = static_cast<char *>(ptr);
     }
+    exdyna_ctx *c = &sc.ctx;
+    *c = exdyna_ctx();
+    rc = init_context(c, cfg, L, n_b, cap, d_residual, sc.scratch_ptr, d_out_idx, d_out_val, dev, hip_stream);
+    if (rc == EXDYNA_OK && !ctx_register(c)) rc = EXDYNA_ENOMEM;
+    if (rc != EXDYNA_OK) {
+        c->magic = 0;
+        return rc;
+    }
+    sc.live = true;
     *out = c;
     return EXDYNA_OK;
 }
@@ -600,7 +676,7 @@ int exdyna_worker_exchange(exdyna_ctx *c, const uint32_t *d_idx_all, const uint6
     X.idx_all = d_idx_all;
     X.counts = d_counts_by_rank;
     X.val_all = d_val_all;
-    X.own_val = at<float>(c, c->lay.out_val);
+    X.own_val = c->d_out_val;
     X.stride = stride;
     X.rank = c->rank;
     const uint64_t gx = (stride + kFinishWG - 1) / kFinishWG;
@@ -641,8 +717,8 @@ int exdyna_get_selected(exdyna_ctx *c, const uint32_t **d_idx, const float **d_v
                         const uint64_t **d_part_off, uint64_t *h_k_actual, uint64_t *h_k_emitted)
 {
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
-    if (d_idx) *d_idx = at<uint32_t>(c, c->lay.out_idx);
-    if (d_val) *d_val = at<float>(c, c->lay.out_val);
+    if (d_idx) *d_idx = c->d_out_idx;
+    if (d_val) *d_val = c->d_out_val;
     if (d_part_off) *d_part_off = at<uint64_t>(c, c->lay.part_off);
     if (h_k_actual || h_k_emitted) {
         DevState st;
@@ -939,7 +1015,13 @@ int exdyna_destroy(exdyna_ctx *c)
     if (!ctx_unregister(c)) return EXDYNA_ESTATE;  // never a context, or destroyed already: not touched
     drop_events(c);
     c->magic = 0;
-    delete c;
+    if (c->static_dev >= 0) {
+        // a built-in context is not heap memory: its device's scratch becomes free for the next one
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        g_static[c->static_dev].live = false;
+    } else {
+        delete c;
+    }
     return EXDYNA_OK;
 }
 
