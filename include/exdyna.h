@@ -107,7 +107,7 @@ int exdyna_default_config(exdyna_config *cfg);
 int exdyna_block_size_from_nb(uint64_t n_g, uint64_t n_b, uint32_t multiple, uint32_t *h_block_size);
 
 /* Bytes of device workspace exdyna_init needs for this configuration
- * (state, per-block / per-chunk / per-tile counters, the staging slots the
+ * (state, per-block / per-segment / per-tile counters, the staging slots the
  * streaming pass writes selected pairs into, and the output pairs).  Host only, launches nothing. */
 int exdyna_workspace_bytes(const exdyna_config *cfg, size_t *h_bytes);
 

@@ -7,28 +7,30 @@
 //              Each wavefront owns 1024 contiguous gradients (a "wave tile").
 //              It ranks its selected gradients with ballots, writes their
 //              (index, value) pairs in index order into the tile's staging
-//              slots, writes the residual with those entries already zeroed
-//              (Alg. 1, zeroing and residual carry), stores the tile's count, and
-//              adds the count to a per-block and a per-segment counter.  A tile with
-//              more selected gradients than it has slots is only counted and
-//              flagged; its residual is written unzeroed.
-//              Pure streaming: 8 B read + 4 B written per gradient, no
-//              workgroup barrier, no fence.
+//              slots, writes the residual -- with those entries already zeroed
+//              (Alg. 1, zeroing and residual carry) when the tile's output rank
+//              of the iteration before says they will fit the output -- stores
+//              the tile's count word, and adds the count to a per-block and a
+//              per-segment counter.  A tile whose rank lay far beyond the output
+//              capacity, or with more selected gradients than slots, is only
+//              counted and flagged.  Pure streaming: 8 B read + 4 B written per
+//              gradient, no workgroup barrier, no fence.
 //   k_finish   workgroup 0 = control: per-partition counts k_{p,t} and k'
 //              (Alg. 1, the gathered counts and their sum), output segment
 //              offsets, threshold scaling (Alg. 5), adjacent-partition
 //              rebalancing (Alg. 3's sweep), Eq. 2/5/6 statistics.
-//              other workgroups = compaction, one wavefront per chunk of up to
-//              64 wave tiles: prefix of the segment counters in front (summed
-//              by the whole workgroup), a wave scan of the tile counts, then
-//              all lanes copy the chunk's staged pairs to their final
-//              positions (Alg. 1, Sparsify and value gather).  Flagged tiles are
-//              re-read from the residual and compacted by the whole wave.  Pairs beyond the
-//              output capacity are put back into the residual.  The same
-//              prefix lays out the next iteration's staging slots: a tile gets
-//              slots in proportion to what it selected this time, so dense
-//              regions and threshold transients stay on the staged path.
-//              Control and compaction read the same finished counters and do
+//              The other workgroups place the pairs.  Each builds the same small
+//              offset table from the segment counters in LDS.  Some then work by
+//              tile (ranks of the tiles -> the next iteration's staging slots
+//              and zeroing rights); the rest work by OUTPUT RANK: a window of
+//              consecutive output positions per workgroup, whose tiles' running
+//              counts are spread out in LDS so that every thread finds its
+//              ranks' pairs with a short search and copies them (Alg. 1,
+//              Sparsify and value gather).  Work is therefore proportional to
+//              min(k', capacity) however the selected gradients are spread over
+//              the vector, also while the threshold is still catching up and
+//              k' is far above the capacity.
+//              Control and placement read the same finished counters and do
 //              not depend on each other, so they overlap inside one launch.
 //
 // Variants of the same two kernels: gradients stored as fp32, bf16 or fp16 with
@@ -55,9 +57,14 @@
 // What the measurements on this part ruled out: a device-scope fence or a
 // "last workgroup done" ticket per workgroup (about 150 ns each, serialised),
 // hot counters shared by many workgroups (same cost per same-address atomic),
-// a workgroup barrier in the streaming pass (6 % slower), and gathering the
+// a workgroup barrier in the streaming pass (6 % slower), gathering the
 // selected values from the residual afterwards (random 4-byte reads over
-// gigabytes cost more than the whole compaction does now).
+// gigabytes), and dealing the placement out by tile (a threshold transient
+// packs the whole output into a few per cent of the tiles: a few wavefronts
+// then copy thousands of pairs each while the rest idle).  In the finishing
+// kernel every first touch of memory costs 1.5-2 us and every shuffle through
+// the LDS crossbar about 60 ns, so loads are issued before anything waits and
+// wavefront scans use the vector ALU's lane-shift path.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -80,13 +87,16 @@ namespace {
 struct Layout {
     size_t state, parts, part_cnt, part_off, blk_cnt, seg_cnt, tile_cnt, err_slots, stage,
         out_idx, out_val, total;
-    size_t n_tiles, n_chunks, n_segs, pool_pairs;
-    uint32_t chunk_shift; // log2(wave tiles per compaction wavefront)
+    size_t n_tiles, n_segs, n_groups, pool_pairs;
+    size_t blk_stride, seg_stride;  // entries between the two parities' counter arrays (padded to 64)
+    size_t tile_pad;                // entries of tile_cnt (n_tiles rounded up to 1024, the rest stays 0)
     uint32_t one_counter; // blocks coincide with segments: one counter array serves both
     size_t slot_tab;
     uint32_t pool_extra; // staging pairs handed out in proportion to the last counts
     uint32_t slots;      // staging slots every wave tile always has
     uint32_t seg_shift;  // log2(wave tiles per segment counter)
+    uint32_t grp_shift;  // log2(segment counters per entry of the placement's offset table)
+    uint32_t tile_wgs, rank_wgs;  // placement workgroups per launch: by tile, by output rank
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -165,19 +175,16 @@ uint32_t staging_slots(double density)
 uint32_t segment_shift(double density)
 {
     const double p_hit = 1.0 - std::exp(-(double)kTile * density);
-    uint32_t sh = kChunkShift;
+    uint32_t sh = kSegShift;
     while (sh > 2 && (double)(1u << sh) * p_hit > 12.0) --sh;
     return sh;
 }
 
-// Wave tiles per compaction wavefront (a "chunk"): about 128 selected gradients
-// per wavefront at the target density, between 4 and 64 tiles.
-uint32_t chunk_shift_for(double density)
+// the placement keeps one prefix entry per group of 1, 4 or 16 segments in LDS
+bool groups_fit(size_t n_tiles, uint32_t sh)
 {
-    const double per_tile = (double)kTile * density;
-    uint32_t sh = kChunkShift;
-    while (sh > 2 && (double)(1u << sh) * per_tile > 128.0) --sh;
-    return sh;
+    const size_t n_segs = (n_tiles + (1u << sh) - 1) >> sh;
+    return (n_segs + 15) / 16 <= kMaxGroups;
 }
 
 Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap, bool with_outputs = true)
@@ -185,35 +192,38 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap, bool with
     Layout L{};
     const size_t P = c->n_parts;
     L.n_tiles  = (c->n_g + kTile - 1) / kTile;
-    L.chunk_shift = chunk_shift_for(c->density);
-    // ... but not so small that the compaction workgroups (16 chunks each) need a second round on
-    // the chip (256 CUs hold two of them each): a round is latency, the copy inside it is not
-    while (L.chunk_shift < kChunkShift && ((L.n_tiles >> L.chunk_shift) + 15) / 16 > 480) ++L.chunk_shift;
-    L.n_chunks = (L.n_tiles + (1u << L.chunk_shift) - 1) >> L.chunk_shift;
     L.slots    = staging_slots(c->density);
     L.seg_shift = segment_shift(c->density);
-    if (L.seg_shift > L.chunk_shift) L.seg_shift = L.chunk_shift;  // a chunk holds whole segments
+    while (!groups_fit(L.n_tiles, L.seg_shift)) ++L.seg_shift;  // 64 tiles per segment always fit
     // When a block is a power-of-two number of tiles that is no coarser than that
     // segment size (and there are not too many blocks to sum over), let segments
     // be the blocks: the streaming pass then adds to one counter instead of two.
     L.one_counter = 0;
     for (uint32_t sh = 2; sh <= L.seg_shift; ++sh)
-        if (c->block_size == (kTile << sh) && (sh == L.seg_shift || n_b <= 32768)) {
+        if (c->block_size == (kTile << sh) && (sh == L.seg_shift || n_b <= 32768) &&
+            groups_fit(L.n_tiles, sh)) {
             L.seg_shift = sh;
             L.one_counter = 1;
         }
     L.n_segs   = (L.n_tiles + (1u << L.seg_shift) - 1) >> L.seg_shift;
+    // few entries make the table quick to build; every level below it costs one more lookup
+    L.grp_shift = L.n_segs > 4096 ? 4 : L.n_segs > 1024 ? 2 : 0;
+    L.n_groups = (L.n_segs + (1u << L.grp_shift) - 1) >> L.grp_shift;
+    // the placement reads counters 16 and 64 at a time: arrays are padded with zeros that nothing writes
+    L.blk_stride = align_up(n_b, 64);
+    L.seg_stride = align_up(L.n_segs, 64);
+    L.tile_pad   = align_up(L.n_tiles, 1024);  // whole groups of segments (at most 16 x 64 tiles)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     L.state     = take(sizeof(DevState));
     L.parts     = take(4 * P * sizeof(int32_t));             // slot0 part,pos ; slot1 part,pos
     L.part_cnt  = take(P * sizeof(uint64_t));
     L.part_off  = take((P + 1) * sizeof(uint64_t));
-    L.blk_cnt   = take(2 * n_b * sizeof(uint32_t));           // two alternating counter arrays
-    L.seg_cnt   = take(2 * L.n_segs * sizeof(uint32_t));      // likewise
-    L.tile_cnt  = take(L.n_tiles * sizeof(uint32_t));
-    L.err_slots = take(2 * kErrSlots * sizeof(double));
-    // staging pool: slots for every tile plus two per pair for three output capacities
+    L.blk_cnt   = take(2 * L.blk_stride * sizeof(uint32_t));  // two alternating counter arrays
+    L.seg_cnt   = take(2 * L.seg_stride * sizeof(uint32_t));  // likewise
+    L.tile_cnt  = take(L.tile_pad * sizeof(uint32_t));
+    L.err_slots = take(2 * 2 * kErrSlots * sizeof(double));   // per parity: unselected, then left-behind selected
+    // staging pool: slots for every tile plus up to four per pair for one and a half output capacities
     {
         uint64_t extra = (6 * cap + 15) & ~15ull;
         const uint64_t fixed = (uint64_t)L.n_tiles * L.slots;
@@ -228,6 +238,17 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap, bool with
         L.out_val = take(cap * sizeof(float));
     }
     L.total     = off;
+    // placement workgroups: one per 4096 tiles and one per window of 1024 output ranks, but no
+    // more than the chip holds at once; they stride over the rest
+    {
+        const uint64_t rounds  = (L.n_tiles + kFinishWG * kTilesPerThr - 1) / (kFinishWG * kTilesPerThr);
+        const uint64_t windows = (cap + kFinishWG - 1) / kFinishWG;
+        L.tile_wgs = (uint32_t)(rounds < kMaxTileWG ? rounds : kMaxTileWG);
+        if (L.tile_wgs == 0) L.tile_wgs = 1;
+        L.rank_wgs = (uint32_t)(windows < kMaxPlaceWG - L.tile_wgs ? windows : kMaxPlaceWG - L.tile_wgs);
+        if (L.tile_wgs == 0) L.tile_wgs = 1;
+        if (L.rank_wgs == 0) L.rank_wgs = 1;
+    }
     return L;
 }
 
@@ -288,11 +309,11 @@ template <typename T> T *at(exdyna_ctx *c, size_t off) { return reinterpret_cast
 
 int32_t *slot_part(exdyna_ctx *c, uint64_t slot) { return at<int32_t>(c, c->lay.parts) + (slot & 1) * 2 * c->cfg.n_parts; }
 int32_t *slot_pos(exdyna_ctx *c, uint64_t slot) { return slot_part(c, slot) + c->cfg.n_parts; }
-uint32_t *blk_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.blk_cnt) + (t & 1) * c->n_b; }
-double *err_slots_of(exdyna_ctx *c, uint64_t t) { return at<double>(c, c->lay.err_slots) + (t & 1) * kErrSlots; }
+uint32_t *blk_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.blk_cnt) + (t & 1) * c->lay.blk_stride; }
+double *err_slots_of(exdyna_ctx *c, uint64_t t) { return at<double>(c, c->lay.err_slots) + (t & 1) * 2 * kErrSlots; }
 
 uint2 *slot_tab_of(exdyna_ctx *c, uint64_t t) { return at<uint2>(c, c->lay.slot_tab) + (t & 1) * c->lay.n_tiles; }
-uint32_t *seg_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.seg_cnt) + (t & 1) * c->lay.n_segs; }
+uint32_t *seg_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.seg_cnt) + (t & 1) * c->lay.seg_stride; }
 
 template <int CMP, bool NORM, int GT, bool SCALE, bool GEN>
 void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
@@ -303,6 +324,9 @@ void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
     A.e = c->d_residual;
     A.st = at<DevState>(c, c->lay.state);
     A.stage = at<uint2>(c, c->lay.stage);
+    A.stage_extra = A.stage + c->lay.n_tiles * c->lay.slots;
+    A.slots_min = c->lay.slots;
+    A.pack_off = c->lay.pool_extra <= kMaxPackedExtra;
     A.slot_tab = slot_tab_of(c, c->t);
     A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
     A.blk_cnt = blk_cnt_of(c, c->t);
@@ -333,8 +357,13 @@ FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
     A.st = at<DevState>(c, c->lay.state);
     A.e = c->d_residual;
     A.stage = at<uint2>(c, c->lay.stage);
+    A.stage_extra = A.stage + c->lay.n_tiles * c->lay.slots;
     A.slot_tab = slot_tab_of(c, t);
     A.slot_tab_next = slot_tab_of(c, t + 1);
+    A.n_tile_wgs = c->lay.tile_wgs;
+    A.grp_shift = c->lay.grp_shift;
+    A.pack_off = c->lay.pool_extra <= kMaxPackedExtra;
+    A.slots_min = c->lay.slots;
     A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
     A.blk_cnt = blk_cnt_of(c, t);
     A.seg_cnt = c->lay.one_counter ? blk_cnt_of(c, t) : seg_cnt_of(c, t);
@@ -351,11 +380,11 @@ FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
     A.err_slots = err_slots_of(c, t);
     A.err_slots_next = err_slots_of(c, t + 1);
     A.n_tiles = (uint32_t)c->lay.n_tiles;
-    A.n_chunks = (uint32_t)c->lay.n_chunks;
     A.n_segs = (uint32_t)c->lay.n_segs;
+    A.n_groups = (uint32_t)c->lay.n_groups;
+    A.search_step = 0;  // largest power of two <= n_groups - 1: the first stride of the offset search
+    for (uint32_t p2 = 1; p2 < A.n_groups; p2 <<= 1) A.search_step = p2;
     A.seg_shift = c->lay.seg_shift;
-    A.chunk_shift = c->lay.chunk_shift;
-    A.slots_min = c->lay.slots;
     A.pool_extra = c->lay.pool_extra;
     A.parity = (uint32_t)(t & 1);
     A.mode = mode;
@@ -369,8 +398,7 @@ template <bool NORM, int CMP>
 void launch_finish(exdyna_ctx *c, uint32_t mode, hipStream_t s)
 {
     const FinishArgs A = finish_args(c, mode);
-    const uint32_t per_wg = kFinishWG / 64;
-    const uint32_t grid = 1u + (uint32_t)((c->lay.n_chunks + per_wg - 1) / per_wg);
+    const uint32_t grid = 1u + c->lay.tile_wgs + c->lay.rank_wgs;
     hipLaunchKernelGGL((k_finish<NORM, CMP>), dim3(grid), dim3(kFinishWG), 0, s, A, c->prm);
 }
 
@@ -519,14 +547,14 @@ int init_context(exdyna_ctx *c, const exdyna_config *cfg, const Layout &L, uint6
     hipLaunchKernelGGL(k_fill_u32, dim3(2048), dim3(256), 0, s,
                        reinterpret_cast<uint32_t *>(d_residual), 0u, (size_t)cfg->n_g);
     hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
-                       (size_t)(2 * n_b));
+                       (size_t)(2 * L.blk_stride));
     hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.seg_cnt), 0u,
-                       (size_t)(2 * L.n_segs));
+                       (size_t)(2 * L.seg_stride));
     hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.tile_cnt), 0u,
-                       L.n_tiles);
+                       L.tile_pad);
     hipLaunchKernelGGL(k_init_slot_tab, dim3(256), dim3(256), 0, s, slot_tab_of(c, 0), slot_tab_of(c, 1),
-                       (uint32_t)L.n_tiles, L.slots);
-    const uint32_t init_threads = (P + 1 > 2 * kErrSlots ? P + 1 : 2 * kErrSlots);
+                       (uint32_t)L.n_tiles);
+    const uint32_t init_threads = (P + 1 > 4 * kErrSlots ? P + 1 : 4 * kErrSlots);
     hipLaunchKernelGGL(k_init_state, dim3((init_threads + 255) / 256), dim3(256), 0, s,
                        at<DevState>(c, L.state), slot_part(c, 0), slot_pos(c, 0), slot_part(c, 1),
                        slot_pos(c, 1), at<uint64_t>(c, L.part_cnt), at<uint64_t>(c, L.part_off),
@@ -813,7 +841,8 @@ int exdyna_get_stats(exdyna_ctx *c, exdyna_stats *h_out)
     if (!h_out) return EXDYNA_ENULL;
     if (c->cfg.want_err_norm && have_iteration(c))
         hipLaunchKernelGGL(k_norm_finalize, dim3(1), dim3(kErrSlots), 0, c->stream,
-                           at<DevState>(c, c->lay.state), err_slots_of(c, last_iteration(c)));
+                           at<DevState>(c, c->lay.state), err_slots_of(c, last_iteration(c)),
+                           (uint32_t)(last_iteration(c) & 1));
     DevState st;
     HIP_TRY(c, hipMemcpyAsync(&st, at<DevState>(c, c->lay.state), sizeof st, hipMemcpyDeviceToHost,
                               c->stream));
@@ -938,13 +967,13 @@ int exdyna_set_state(exdyna_ctx *c, const void *h_state, size_t bytes, void *hip
                               hipMemcpyHostToDevice, s));
     hipLaunchKernelGGL(k_restore_state, dim3(1), dim3(1), 0, s, at<DevState>(c, L.state), h.t, h.delta);
     hipLaunchKernelGGL(k_fill_u32, dim3(256), dim3(256), 0, s, at<uint32_t>(c, L.blk_cnt), 0u,
-                       (size_t)(2 * c->n_b));
+                       (size_t)(2 * L.blk_stride));
     hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.seg_cnt), 0u,
-                       (size_t)(2 * L.n_segs));
+                       (size_t)(2 * L.seg_stride));
     hipLaunchKernelGGL(k_fill_u32, dim3(64), dim3(256), 0, s, at<uint32_t>(c, L.err_slots), 0u,
-                       (size_t)(2 * kErrSlots * 2));
+                       (size_t)(4 * kErrSlots * 2));
     hipLaunchKernelGGL(k_init_slot_tab, dim3(256), dim3(256), 0, s, slot_tab_of(c, 0), slot_tab_of(c, 1),
-                       (uint32_t)L.n_tiles, L.slots);
+                       (uint32_t)L.n_tiles);
     HIP_TRY(c, hipGetLastError());
     HIP_TRY(c, hipStreamSynchronize(s));  // h_state may be freed by the caller on return
     return EXDYNA_OK;

@@ -35,8 +35,10 @@ k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
     if (blockIdx.y == P) {
         if (blockIdx.x != 0) return;
         __shared__ CtrlShared S;
+        const float    delta  = A.st->delta[A.parity];
+        const uint64_t t_done = A.st->t;  // read before this workgroup advances it
         if (tid < P) {
-            const uint32_t t_mod_p = (uint32_t)(A.st->t % P);  // read before this workgroup advances it
+            const uint32_t t_mod_p = (uint32_t)(t_done % P);
             S.lpos[tid]  = A.cur_pos[tid];
             S.lpart[tid] = A.cur_part[tid];
             // rank tid selected partition (t mod P + tid) mod P (Alg. 3 (cyclic allocation))
@@ -44,7 +46,7 @@ k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
             S.cnt[(t_mod_p + tid) % P] = (uint32_t)(k_r < prm.n_g ? k_r : prm.n_g);
         }
         __syncthreads();
-        control_decide(A, prm, S, kCtrlUpdate);
+        control_decide(A, prm, S, kCtrlUpdate, delta, t_done);
         return;
     }
     const uint32_t r = blockIdx.y;
@@ -73,9 +75,7 @@ k_exchange(FinishArgs A, CtrlParams prm, ExchangeArgs X)
     }
     if (NORM) {
         // the streaming pass counted these entries as residual: take them out again
-        double s = (double)sq;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+        const double s = wave_sum((double)sq);
         if ((tid & 63u) == 0 && s != 0.0) atomicAdd(&A.err_slots[(blockIdx.x + r) % kErrSlots], -s);
     }
 }

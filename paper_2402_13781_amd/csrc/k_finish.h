@@ -1,4 +1,4 @@
-// The finishing kernel: control workgroup (counts, Alg. 5, Alg. 3, statistics) and compaction.
+// The finishing kernel: control workgroup (counts, Alg. 5, Alg. 3, statistics) and placement.
 #ifndef EXDYNA_K_FINISH_H
 #define EXDYNA_K_FINISH_H
 
@@ -10,8 +10,9 @@ namespace {
 struct FinishArgs {
     DevState       *st;
     float          *e;
-    const uint2    *stage;
-    const uint2    *slot_tab;        // this iteration's {first slot, slots} per tile
+    const uint2    *stage;           // staging pool: slots_min per tile ...
+    const uint2    *stage_extra;     // ... then the part the slot table hands out
+    const uint2    *slot_tab;        // this iteration's {offset in the extra part, slots | bits} per tile
     uint2          *slot_tab_next;   // the next iteration's, written here
     const uint32_t *tile_cnt;
     const uint32_t *blk_cnt;         // this iteration's per-block counters (complete)
@@ -28,7 +29,11 @@ struct FinishArgs {
     float          *out_val;
     double         *err_slots;       // this iteration's norm partials
     double         *err_slots_next;  // cleared here
-    uint32_t        n_tiles, n_chunks, n_segs, seg_shift, chunk_shift, slots_min, pool_extra, parity;
+    uint32_t        n_tiles, n_segs, n_groups, seg_shift, slots_min, pool_extra, parity;
+    uint32_t        search_step;     // largest power of two below n_groups (0 if n_groups = 1)
+    uint32_t        n_tile_wgs;      // placement workgroups 1 .. n_tile_wgs work by tile, the rest by output rank
+    uint32_t        grp_shift;       // log2(segment counters per entry of the placement's offset table): 0, 2 or 4
+    uint32_t        pack_off;        // tile words carry the extra-part offset of their pairs
     uint32_t        mode;            // kCtrlFull or kCtrlSelect
     uint32_t        sel_rank;        // worker view: the worker whose partition was compared; else kAllParts
     uint32_t        block_size;
@@ -89,19 +94,24 @@ __device__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlS
     const uint32_t per_wave = (n_b + kWaves - 1) / kWaves;
     const uint32_t beg      = wave * per_wave < n_b ? wave * per_wave : n_b;
     const uint32_t end      = beg + per_wave < n_b ? beg + per_wave : n_b;
-    constexpr uint32_t kAhead = 4;
+    constexpr uint32_t kAhead = 12;  // 768 counters per wave and trip: one trip up to 12288 blocks
     uint32_t cbuf[kAhead];
+    // (index clamped instead of a guarded load: all loads of a trip are in flight together)
 #pragma unroll
     for (uint32_t q = 0; q < kAhead; ++q) {
         const uint32_t i = beg + q * 64u + lane;
-        cbuf[q] = i < end ? A.blk_cnt[i] : 0u;
+        cbuf[q] = A.blk_cnt[i < end ? i : 0u];
     }
     if (tid < P) {
         S.cnt[tid]   = 0u;
         S.lpos[tid]  = A.cur_pos[tid];
         S.lpart[tid] = A.cur_part[tid];
     }
-    if (tid < kErrSlots) A.err_slots_next[tid] = 0.0;
+    if (tid < 2 * kErrSlots) A.err_slots_next[tid] = 0.0;
+    if (tid == 0) {
+        A.st->nf_sel[A.parity ^ 1u]  = 0u;
+        A.st->nf_emit[A.parity ^ 1u] = 0u;
+    }
     __syncthreads();
 
     if (beg < end) {  // wave-uniform
@@ -119,7 +129,7 @@ __device__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlS
 #pragma unroll
                 for (uint32_t q = 0; q < kAhead; ++q) {
                     const uint32_t i = i0 + q * 64u + lane;
-                    cbuf[q] = i < end ? A.blk_cnt[i] : 0u;
+                    cbuf[q] = A.blk_cnt[i < end ? i : 0u];
                 }
             }
 #pragma unroll
@@ -127,12 +137,11 @@ __device__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlS
                 const uint32_t s0 = i0 + q * 64u;  // first block of this slice
                 const uint32_t i  = s0 + lane;
                 if (i < end) A.blk_cnt_next[i] = 0u;  // clean block counters for the next iteration
-                uint32_t c = cbuf[q];
+                uint32_t c = i < end ? cbuf[q] : 0u;
                 while (next_start < s0 + 64u && next_start < end) {  // the slice reaches the next partition
                     acc += i < next_start ? c : 0u;
                     c = i < next_start ? 0u : c;
-#pragma unroll
-                    for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+                    acc = wave_sum(acc);
                     if (lane == 0 && acc) atomicAdd(&S.cnt[pcur], acc);
                     acc = 0;
                     ++pcur;
@@ -141,53 +150,58 @@ __device__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlS
                 acc += c;
             }
         }
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) acc += __shfl_xor(acc, d, 64);
+        acc = wave_sum(acc);
         if (lane == 0 && acc) atomicAdd(&S.cnt[pcur], acc);
     }
     __syncthreads();
 }
 
 // Everything that follows from the per-partition counts in S.cnt (S.lpos /
-// S.lpart hold the topology they were counted with).
-__device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S, uint32_t mode)
+// S.lpart hold the topology they were counted with).  ONE_WAVE: P <= 64, the first wavefront
+// does it alone and the workgroup barriers fall away (a wavefront's LDS accesses stay in
+// program order); the caller has already sent the other wavefronts home.
+template <bool ONE_WAVE>
+__device__ __forceinline__ void ctrl_sync()
 {
-    constexpr uint32_t kWaves = kFinishWG / 64;
+    if (ONE_WAVE)
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    else
+        __syncthreads();
+}
+
+template <bool ONE_WAVE>
+__device__ void control_decide_impl(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S, uint32_t mode,
+                                    float delta_in, uint64_t t_in)
+{
+    constexpr uint32_t kWaves = ONE_WAVE ? 1u : kFinishWG / 64;
     constexpr uint32_t kIdent = 0u | (1u << 2) | (2u << 4);  // s -> s
     const uint32_t tid  = threadIdx.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wave = tid >> 6;
     const uint32_t P    = prm.n_parts;
 
-    float    delta  = 0.f;
-    uint64_t t_done = 0;
-    if (tid == 0) {
-        delta  = A.st->delta[A.parity];
-        t_done = A.st->t;
-        S.n_moves = 0u;
-    }
+    // threshold and iteration counter of this iteration: requested by the caller before the
+    // counting started, so that their latency is not added at the end
+    const float    delta  = delta_in;
+    const uint64_t t_done = t_in;
+    if (tid == 0) S.n_moves = 0u;
     const int32_t part = tid < P ? S.lpart[tid] : 0;
     const int32_t pos  = tid < P ? S.lpos[tid] : 0;
 
     // exclusive scan and maximum of the P counts (P <= 1024 = one value per thread)
     const uint32_t c    = tid < P ? S.cnt[tid] : 0u;
     const uint32_t incl = wave_incl_scan(c, lane);
-    uint32_t mx = c;
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) {
-        const uint32_t o = __shfl_xor(mx, d, 64);
-        mx = o > mx ? o : mx;
-    }
+    const uint32_t mx = wave_max(c);
     if (lane == 63) S.wsum[wave] = incl;
     if (lane == 0) S.wmax[wave] = mx;
-    __syncthreads();
+    ctrl_sync<ONE_WAVE>();
     if (wave == 0) {
         const uint32_t v  = lane < kWaves ? S.wsum[lane] : 0u;
         const uint32_t vi = wave_incl_scan(v, lane);
         if (lane < kWaves) S.wsum[lane] = vi - v;
         if (lane == kWaves - 1) S.k_total = vi;  // k' (Alg. 1 (k' sum))
     }
-    __syncthreads();
+    ctrl_sync<ONE_WAVE>();
     const uint64_t excl     = (uint64_t)S.wsum[wave] + (incl - c);
     const uint64_t k_actual = S.k_total;
     if (tid < P) {
@@ -197,6 +211,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
     if (mode == kCtrlSelect) {  // the gathered counts decide the rest, after the exchange
         if (tid == 0) {
             DevState *st = A.st;
+            st->k_hist[A.parity] = k_actual;
             A.part_off[P]   = k_actual < prm.cap ? k_actual : prm.cap;
             st->own_actual  = k_actual;
             st->own_emitted = k_actual < prm.cap ? k_actual : prm.cap;
@@ -229,7 +244,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
         }
         S.flags[tid] = (uint8_t)f;
     }
-    __syncthreads();
+    ctrl_sync<ONE_WAVE>();
 
     // decision table of pair (tid, tid+1) for the three incoming states
     const int64_t bm      = (int64_t)prm.blk_move;
@@ -256,14 +271,15 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
     }
     // inclusive scan of compositions: after it, `fun` maps the state entering
     // this wave's first pair to the state leaving pair tid
-    uint32_t fun = table;
-#pragma unroll
-    for (uint32_t d = 1; d < 64; d <<= 1) {
-        const uint32_t prev = __shfl_up(fun, d, 64);
-        if (lane >= d) fun = compose(fun, prev);
-    }
+    struct OpCompose {
+        __device__ __forceinline__ uint32_t operator()(uint32_t later, uint32_t earlier) const
+        {
+            return compose(later, earlier);
+        }
+    };
+    const uint32_t fun = wave_scan(table, kIdent, OpCompose());
     if (lane == 63) S.wfun[wave] = fun;
-    __syncthreads();
+    ctrl_sync<ONE_WAVE>();
     if (tid == 0) {
         uint32_t stt = 0;  // pair 0 starts untouched
         for (uint32_t w = 0; w < kWaves; ++w) {
@@ -271,9 +287,8 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
             stt = (S.wfun[w] >> (2u * stt)) & 3u;
         }
     }
-    __syncthreads();
-    uint32_t before = __shfl_up(fun, 1, 64);
-    if (lane == 0) before = kIdent;
+    ctrl_sync<ONE_WAVE>();
+    const uint32_t before = dpp_move<0x138, 0xF>(kIdent, fun);  // the lane below's; lane 0: identity
     const uint32_t st_in = (before >> (2u * S.wcarry[wave])) & 3u;  // what pair tid-1 did
     const uint32_t act   = (table >> (2u * st_in)) & 3u;            // what pair tid does
     const uint64_t moved = __ballot(act != 0);
@@ -287,7 +302,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
         A.nxt_part[tid] = part + d_in + d_out;
         A.nxt_pos[tid]  = pos - d_in;
     }
-    __syncthreads();
+    ctrl_sync<ONE_WAVE>();
 
     if (tid == 0) {
         DevState *st = A.st;
@@ -318,6 +333,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
             emitted = 0;
             for (uint32_t p = 0; p < P; ++p) emitted += S.cnt[p] < prm.cap ? S.cnt[p] : prm.cap;
         }
+        if (mode == kCtrlFull) st->k_hist[A.parity] = k_actual;
         st->k_actual      = k_actual;
         st->k_emitted     = emitted;
         st->overflow      = emitted < k_actual ? 1u : 0u;
@@ -330,32 +346,254 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
     }
 }
 
+__device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S, uint32_t mode,
+                               float delta, uint64_t t_done)
+{
+    if (prm.n_parts <= 64u) {  // workgroup-uniform
+        if (threadIdx.x < 64u) control_decide_impl<true>(A, prm, S, mode, delta, t_done);
+    } else {
+        control_decide_impl<false>(A, prm, S, mode, delta, t_done);
+    }
+}
+
 __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 {
     __shared__ CtrlShared S;
+    // requested before the counting starts (volatile: issued here, waited for where used)
+    const float    delta  = *reinterpret_cast<const volatile float *>(&A.st->delta[A.parity]);
+    const uint64_t t_done = *reinterpret_cast<const volatile uint64_t *>(&A.st->t);
     control_counts(A, prm, S);
-    control_decide(A, prm, S, A.mode);
+    control_decide(A, prm, S, A.mode, delta, t_done);
 }
 
-// ---- compaction: a workgroup takes 16 consecutive chunks, one wavefront per
-// chunk, one lane per wave tile.  The output position of the chunk's first pair
-// is the number of selected gradients in front of it: the workgroup sums the
-// segment counters before its first chunk (all 1024 threads, counters sit in L2)
-// and the wave totals inside the workgroup; a wave scan of the 64 tile counts
-// then gives every lane the position of its tile's first pair.  Tiles, and the
-// pairs staged inside a tile, are in index order, so the output is ascending. ----
+// ---- placement: every other workgroup of k_finish ----
+//
+// A pair's output position is the number of selected gradients in front of it (partitions are
+// contiguous and ascending, Sec. 4.1, so the per-partition lists in partition order are one
+// ascending list).  Every placement workgroup first builds the same small table in LDS: the
+// exclusive prefix of the segment counters, one entry per group of 16 segments.  With it
+//   - some workgroups work by TILE: four consecutive wave tiles per thread.  The thread learns
+//     its tiles' ranks, writes their slot table entries for the next iteration, and puts back
+//     what the streaming pass zeroed although it lies beyond the capacity (rare);
+//   - the others work by output RANK: windows of 1024 output positions, one per thread.  The
+//     thread finds the tile that holds its rank (group table, then the group's 16 segment
+//     counters, then the segment's tile counts) and copies that one pair from the tile's
+//     staging slots.  However the selected gradients are spread over the vector -- a sparse
+//     steady state, or a threshold transient that packs the whole output into the first few
+//     per cent of the tiles -- every thread moves one pair per window, and only ranks below
+//     min(k', capacity) cost anything.
+// A flagged tile (not staged) inside the capacity is re-read from the residual by the wave
+// that holds the rank of its first pair.
 
-// A flagged tile (more selected gradients than staging slots; its residual
-// still holds acc): the whole wave re-reads its 1024 gradients, repeats the
-// comparison with the threshold the streaming pass used, emits the pairs that
-// fit the output and zeroes them in the residual.
-template <bool NORM, int CMP>
-__device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32_t tile, uint64_t r0,
-                                                     float delta, uint32_t lane, uint32_t n_g,
-                                                     uint64_t cap, uint32_t e_lo, uint32_t e_hi,
-                                                     float &spill)
+constexpr uint32_t kWinTiles = 4096;  // tile words (or segment counters) a rank workgroup spreads out in LDS at a time
+
+struct alignas(16) PlaceShared {
+    uint32_t grp[kMaxGroups];          // group sums, then exclusive offsets
+    uint32_t wtot[kFinishWG / 64];
+    uint32_t wbase[kFinishWG / 64];
+    uint32_t total;
+    uint32_t win[2];                   // the groups of a window's first and last rank
+    uint32_t tpre[kWinTiles];          // a window's tiles (or segments): running (inclusive) count of selected gradients
+    uint32_t tword[kWinTiles];         // ... and their tile words
+};
+
+// Sum of the 16 per-wave totals in front of wave `wave` (four LDS reads side by side instead
+// of up to fifteen one after the other).
+__device__ __forceinline__ uint32_t waves_before(const uint32_t *wtot, uint32_t wave)
 {
-    if (!NORM && r0 >= cap) return;  // nothing fits: the tile stays in the residual as it is
+    const uint4 *p = reinterpret_cast<const uint4 *>(wtot);
+    const uint4 a = p[0], b = p[1], c = p[2], d = p[3];
+    const uint32_t v[16] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w, c.x, c.y, c.z, c.w, d.x, d.y, d.z, d.w};
+    uint32_t sum = 0;
+#pragma unroll
+    for (uint32_t w = 0; w < 16; ++w) sum += w < wave ? v[w] : 0u;
+    return sum;
+}
+
+// Builds S.grp (exclusive prefix of the segment counters, one entry per group of 1, 4 or 16
+// segments: A.grp_shift = 0, 2, 4) and S.total.
+__device__ __forceinline__ void place_table(const FinishArgs &A, PlaceShared &S)
+{
+    constexpr uint32_t kWaves = kFinishWG / 64;
+    const uint32_t tid  = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = tid >> 6;
+    // group sums: a lane takes four counters per load; the counter arrays are padded with
+    // zeros to a multiple of 64
+    {
+        const uint4 *__restrict__ src = reinterpret_cast<const uint4 *>(A.seg_cnt);
+        const uint32_t n_vec = (A.n_segs + 3u) >> 2;
+        const uint32_t gs    = A.grp_shift;
+        constexpr uint32_t kAhead = 4;
+        for (uint32_t v0 = wave * 64u + lane; v0 < ((n_vec + 63u) & ~63u); v0 += kAhead * kFinishWG) {
+            uint4 c[kAhead];
+#pragma unroll
+            for (uint32_t q = 0; q < kAhead; ++q) {  // index clamped, not a guarded load: all in flight together
+                const uint32_t v = v0 + q * kFinishWG;
+                c[q] = src[v < n_vec ? v : 0u];
+                if (v >= n_vec) c[q] = make_uint4(0u, 0u, 0u, 0u);
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < kAhead; ++q) {
+                const uint32_t v = v0 + q * kFinishWG;
+                if (gs == 0u) {  // every counter is a group
+                    if (4u * v + 0u < A.n_groups) S.grp[4u * v + 0u] = c[q].x;
+                    if (4u * v + 1u < A.n_groups) S.grp[4u * v + 1u] = c[q].y;
+                    if (4u * v + 2u < A.n_groups) S.grp[4u * v + 2u] = c[q].z;
+                    if (4u * v + 3u < A.n_groups) S.grp[4u * v + 3u] = c[q].w;
+                } else {
+                    uint32_t x = (c[q].x + c[q].y) + (c[q].z + c[q].w);
+                    if (gs == 4u) {  // four lanes = one group
+                        x += dpp_move<0xB1, 0xF>(0u, x);  // quad lanes 1 0 3 2
+                        x += dpp_move<0x4E, 0xF>(0u, x);  // quad lanes 2 3 0 1
+                        if ((lane & 3u) == 0u && (v >> 2) < A.n_groups) S.grp[v >> 2] = x;
+                    } else if (v < A.n_groups) {
+                        S.grp[v] = x;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    // exclusive scan of the group sums, a run of consecutive groups per thread
+    const uint32_t per = (A.n_groups + kFinishWG - 1u) / kFinishWG;  // <= kMaxGroups / 1024
+    const uint32_t g0  = tid * per;
+    uint32_t mine = 0;
+    for (uint32_t q = 0; q < per; ++q)
+        if (g0 + q < A.n_groups) mine += S.grp[g0 + q];
+    const uint32_t incl = wave_incl_scan(mine, lane);
+    if (lane == 63) S.wtot[wave] = incl;
+    __syncthreads();
+    if (wave == 0) {
+        const uint32_t w  = lane < kWaves ? S.wtot[lane] : 0u;
+        const uint32_t wi = wave_incl_scan(w, lane);
+        if (lane < kWaves) S.wbase[lane] = wi - w;
+        if (lane == kWaves - 1) S.total = wi;
+    }
+    __syncthreads();
+    uint32_t run = S.wbase[wave] + (incl - mine);
+    for (uint32_t q = 0; q < per; ++q)
+        if (g0 + q < A.n_groups) {
+            const uint32_t c = S.grp[g0 + q];
+            S.grp[g0 + q] = run;
+            run += c;
+        }
+    __syncthreads();
+}
+
+// Where a staged tile's pairs are: in its fixed slots if they fit there, else in the extra part
+// (at the offset the tile word carries, or the slot table's when the pool is too large for that).
+__device__ __forceinline__ const uint2 *staged_pairs(const FinishArgs &A, uint32_t tile, uint32_t word)
+{
+    if ((word & kCountMask) <= A.slots_min) return A.stage + (size_t)tile * A.slots_min;
+    if (A.pack_off) return A.stage_extra + ((size_t)(word >> kOffShift) << 4);
+    return A.stage_extra + A.slot_tab[tile].x;
+}
+
+// ---- by tile: ranks, the next slot table, clean segment counters, put-backs ----
+template <bool NORM>
+__device__ void place_tiles(const FinishArgs &A, PlaceShared &S, uint64_t cap, uint32_t wg, uint4 w4,
+                            uint64_t prev, double &add)
+{
+    // how fast the selected count grows: this pass's total over the last pass's (prev), 1 .. 4
+    uint64_t zero_below = cap;
+    uint32_t slots_per8 = 20;  // extra staging slots per selected gradient, in eighths
+    {
+        const double   now  = (double)S.total;
+        double growth = prev ? now / (double)prev : 1.0;
+        growth = growth < 1.0 ? 1.0 : growth > 4.0 ? 4.0 : growth;
+        zero_below = (uint64_t)((double)cap / (growth * 1.125));
+        slots_per8 = (uint32_t)(16.0 * growth * 1.25);  // in eighths: 2.5 slots per pair when nothing grows
+        slots_per8 = slots_per8 > 32u ? 32u : slots_per8;
+    }
+    const uint32_t tid  = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = tid >> 6;
+    const uint32_t sh   = A.seg_shift;
+    constexpr uint32_t kBig = kFinishWG * kTilesPerThr;  // wave tiles per workgroup and round
+    const uint32_t n_big = (A.n_tiles + kBig - 1u) / kBig;
+    for (uint32_t big = wg; big < n_big; big += A.n_tile_wgs) {
+        const uint32_t tile0 = (big * kFinishWG + tid) * kTilesPerThr;
+        const uint32_t word[4] = {w4.x, w4.y, w4.z, w4.w};
+        {   // the next round's tile words are requested before this round waits for anything
+            const uint32_t nxt = ((big + A.n_tile_wgs) * kFinishWG + tid) * kTilesPerThr;
+            if (big + A.n_tile_wgs < n_big && nxt < A.n_tiles)
+                w4 = *reinterpret_cast<const uint4 *>(A.tile_cnt + nxt);
+            else
+                w4 = make_uint4(0u, 0u, 0u, 0u);
+        }
+        const uint32_t c4[4] = {word[0] & kCountMask, word[1] & kCountMask, word[2] & kCountMask,
+                                word[3] & kCountMask};
+        const uint32_t mine = (c4[0] + c4[1]) + (c4[2] + c4[3]);
+        const uint32_t incl = wave_incl_scan(mine, lane);
+        if (lane == 63) S.wtot[wave] = incl;
+        __syncthreads();
+        uint32_t r0 = S.grp[big * ((kBig >> sh) >> A.grp_shift)] + (incl - mine);  // a round starts on a group boundary
+        r0 += waves_before(S.wtot, wave);
+        __syncthreads();  // S.wtot is rewritten by the next round
+
+        {   // a round holds whole segments: their counters of the other parity are cleared here
+            const uint32_t per_big = kBig >> sh;
+            for (uint32_t i = tid; i < per_big; i += kFinishWG) {
+                const uint32_t sg = big * per_big + i;
+                if (sg < A.n_segs) A.seg_cnt_next[sg] = 0u;
+            }
+        }
+        // Staging slots for the next iteration follow this iteration's ranks and counts.
+        // Beyond its fixed slots a tile gets two and a half to four slots per gradient it
+        // selected now (more while the total is growing) in the extra part of the pool, at an
+        // offset that is the running sum of those sizes (taken from the rank, rounded down to
+        // 16 pairs = 128 bytes so that two tiles never share a cache line), for as long as
+        // the extra part lasts: it covers at least one and a half output capacities.  A tile ranked beyond that only counts; a tile whose pairs would
+        // still end within the capacity if all ranks grew as the total just did (and an
+        // eighth more) may zero what it stages.
+        const uint64_t ex = A.pool_extra;  // multiple of 16
+#pragma unroll
+        for (uint32_t k = 0; k < kTilesPerThr; ++k) {
+            const uint32_t tile = tile0 + k;
+            const uint32_t c    = c4[k];
+            if (tile < A.n_tiles) {
+                const uint64_t a2 = (((uint64_t)r0 * slots_per8) >> 3) & ~15ull;
+                const uint64_t b2 = ((((uint64_t)r0 + c) * slots_per8) >> 3) & ~15ull;
+                uint2 nxt;
+                if (a2 >= ex) {
+                    nxt = make_uint2(0u, kCountOnly);
+                } else {
+                    const uint64_t hi2 = b2 < ex ? b2 : ex;
+                    uint32_t       y   = (uint32_t)(hi2 - a2);
+                    if ((uint64_t)r0 + c <= zero_below) y |= kZeroBit;
+                    nxt = make_uint2((uint32_t)a2, y);
+                }
+                A.slot_tab_next[tile] = nxt;
+
+                // zeroed in registers, yet beyond the capacity: not sent, so back into the residual
+                if (c && !(word[k] & (kFlag | kKept)) && (uint64_t)r0 + c > cap) {
+                    const uint32_t first = r0 < cap ? (uint32_t)(cap - r0) : 0u;
+                    const uint2 *__restrict__ src = staged_pairs(A, tile, word[k]);
+                    for (uint32_t j = first; j < c; ++j) {
+                        const uint2 pr = src[j];
+                        const float v  = __uint_as_float(pr.y);
+                        A.e[pr.x] = v;
+                        if (NORM) add += (double)(v * v);
+                    }
+                }
+            }
+            r0 += c;
+        }
+    }
+}
+
+// Wave-cooperative: re-read flagged tile `tile` (its residual still holds acc), repeat the
+// comparison, and emit its selected gradients whose output rank lies below n_out; r0 is the
+// rank of the tile's first selected gradient.  Emitted entries are zeroed in the residual
+// (Alg. 1 (zeroing of the sent entries)), which is why ONE wave does the whole tile: a second
+// wave re-reading it meanwhile would no longer find what the first has sent.
+template <bool NORM, int CMP>
+__device__ __forceinline__ void emit_flagged_tile(const FinishArgs &A, uint32_t tile, uint32_t r0,
+                                                  uint32_t n_out, float delta,
+                                                  uint32_t lane, uint32_t n_g, uint32_t e_lo,
+                                                  uint32_t e_hi, double &sub, uint32_t &sub_nf)
+{
     float *__restrict__ e = A.e;
     const uint32_t gran0 = tile * kTileGran;
     float    v[kTileGran][4];
@@ -387,22 +625,21 @@ __device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32
                 if (base + q < n_g) nib[u] |= sel<CMP>(v[u][q], delta) << q;
         }
     }
-    uint64_t running = r0;
+    uint32_t running = r0;
 #pragma unroll
     for (uint32_t u = 0; u < kTileGran; ++u) {
         const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
         uint32_t cu, below;
         granule_ranks(nib[u], cu, below);
-        uint64_t r = running + below;
+        uint32_t r = running + below;
 #pragma unroll
         for (uint32_t q = 0; q < 4; ++q) {
             if (nib[u] & (1u << q)) {
-                if (r < cap) {
+                if (r < n_out) {
                     A.out_idx[r] = (uint32_t)(base + q);
                     A.out_val[r] = v[u][q];
-                    e[base + q]  = 0.0f;  // +0 where sent (Alg. 1 (zeroing of the sent entries))
-                } else if (NORM) {
-                    spill += v[u][q] * v[u][q];  // selected but not emitted: stays in the residual
+                    e[base + q]  = 0.0f;
+                    if (NORM) left_selected(v[u][q], sub, sub_nf);
                 }
                 ++r;
             }
@@ -411,174 +648,297 @@ __device__ __forceinline__ void compact_flagged_tile(const FinishArgs &A, uint32
     }
 }
 
-template <bool NORM, int CMP>
-__device__ void finish_compact(const FinishArgs &A, uint32_t n_g, uint64_t cap)
+// Group that holds output rank r: the last one whose offset is <= r (empty groups in front
+// share the offset).
+__device__ __forceinline__ uint32_t find_group(const FinishArgs &A, const PlaceShared &S, uint32_t r)
 {
-    constexpr uint32_t kWaves = kFinishWG / 64;
-    __shared__ uint32_t red[kWaves];
-    __shared__ uint32_t wtot[kWaves];
-    __shared__ uint32_t s_incl[kWaves][64];  // per wave: running count of staged pairs over its tiles
-    __shared__ uint32_t s_off[kWaves][64];   // first staging slot of each tile
-    __shared__ uint32_t s_rel[kWaves][64];   // output position of each tile's first pair, minus the chunk's
-    const uint32_t tid    = threadIdx.x;
-    const uint32_t lane   = tid & 63u;
-    const uint32_t wave   = tid >> 6;
-    const uint32_t cs     = A.chunk_shift;             // log2(wave tiles per chunk)
-    const uint32_t chunk0 = (blockIdx.x - 1u) * kWaves;
-    const uint32_t chunk  = chunk0 + wave;
-    const uint32_t tile   = (chunk << cs) + lane;
-
-    // all first loads are requested before anything waits on them
-    uint32_t word = 0;
-    uint2    tab  = make_uint2(0u, 0u);
-    const bool have_tile = chunk < A.n_chunks && lane < (1u << cs) && tile < A.n_tiles;
-    if (have_tile) {
-        word = A.tile_cnt[tile];
-        tab  = A.slot_tab[tile];
+    uint32_t g = 0;
+    for (uint32_t step = A.search_step; step; step >>= 1) {
+        const uint32_t m = g + step;
+        if (m < A.n_groups && S.grp[m] <= r) g = m;
     }
-    float delta = 0.f;
-    if (word & kFlag) delta = A.st->delta[A.parity];
-    uint32_t s0 = 0, s1 = 0, s2 = 0, s3 = 0;
-    {
-        const uint32_t seg0 = (chunk0 << cs) >> A.seg_shift;  // segments in front of this workgroup
-        uint32_t i = tid;
-        for (; i + 3u * kFinishWG < seg0; i += 4u * kFinishWG) {
-            s0 += A.seg_cnt[i];
-            s1 += A.seg_cnt[i + kFinishWG];
-            s2 += A.seg_cnt[i + 2u * kFinishWG];
-            s3 += A.seg_cnt[i + 3u * kFinishWG];
+    return g;
+}
+
+// Segment that holds position rem of group g (groups of 4 or 16 segments): the group's
+// counters, requested together, then one after the other.  rem becomes the position inside
+// the segment.
+__device__ __forceinline__ uint32_t find_segment(const FinishArgs &A, uint32_t g, uint32_t &rem)
+{
+    uint32_t seg = g << A.grp_shift;
+    if (A.grp_shift) {  // workgroup-uniform
+        const uint32_t n_vec = A.grp_shift == 4u ? 4u : 1u;
+        const uint4 *p = reinterpret_cast<const uint4 *>(A.seg_cnt + seg);
+        uint4 c4[4];
+#pragma unroll
+        for (uint32_t v = 0; v < 4; ++v) c4[v] = p[v < n_vec ? v : 0u];
+        bool found = false;
+#pragma unroll
+        for (uint32_t v = 0; v < 4; ++v) {
+            const uint32_t cc[4] = {c4[v].x, c4[v].y, c4[v].z, c4[v].w};
+#pragma unroll
+            for (uint32_t k = 0; k < 4; ++k) {
+                const bool here = !found && v < n_vec && rem < cc[k];
+                found = found || here;
+                if (!found && v < n_vec) {
+                    rem -= cc[k];
+                    ++seg;
+                }
+            }
         }
-        for (; i < seg0; i += kFinishWG) s0 += A.seg_cnt[i];
     }
-    uint32_t s = (s0 + s1) + (s2 + s3);
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
+    return seg;
+}
 
-    const uint32_t c     = word & ~kFlag;                 // selected in this lane's tile
-    const uint32_t cstg  = (word & kFlag) ? 0u : c;       // ... of which staged
-    const uint32_t incl  = wave_incl_scan(c, lane);
-    const uint32_t incls = wave_incl_scan(cstg, lane);
-    const uint32_t tot   = __shfl(incl, 63, 64);
-    const uint32_t tots  = __shfl(incls, 63, 64);
-    s_incl[wave][lane] = incls;
-    s_off[wave][lane]  = tab.x;
-    s_rel[wave][lane]  = incl - c;
-    if (lane == 0) {
-        red[wave]  = s;
-        wtot[wave] = tot;
-    }
-    __syncthreads();
-    if (chunk >= A.n_chunks) return;
-    uint64_t base = 0;  // selected gradients in front of this chunk
+// Tile that holds position rem of segment seg: the segment's tile words, 16 requested
+// together, then one after the other.  rem becomes the position inside the tile.
+__device__ __forceinline__ uint32_t find_tile(const FinishArgs &A, uint32_t seg, uint32_t &rem, uint32_t &word)
+{
+    const uint32_t sh     = A.seg_shift;
+    const uint32_t n_vec  = sh >= 4u ? 4u : 1u << (sh - 2u);
+    const uint32_t rounds = sh > 4u ? 1u << (sh - 4u) : 1u;
+    uint32_t tile = seg << sh;
+    bool found = false;
+    word = 0;
+    for (uint32_t round = 0; round < rounds && !found; ++round) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(A.tile_cnt + (seg << sh)) + round * 4u;
+        uint4 c4[4];
 #pragma unroll
-    for (uint32_t w = 0; w < kWaves; ++w) base += red[w] + (w < wave ? wtot[w] : 0u);
-
-    {   // clean segment counters for the next iteration (a chunk holds whole segments)
-        const uint32_t per_chunk = 1u << (cs - A.seg_shift);
-        const uint32_t sg        = chunk * per_chunk + lane;
-        if (lane < per_chunk && sg < A.n_segs) A.seg_cnt_next[sg] = 0u;
-    }
-    const uint64_t r0 = base + (incl - c);  // output position of this tile's first pair
-
-    // Staging slots for the next iteration follow this iteration's counts: every
-    // tile keeps slots_min slots and gets about two more per gradient it selected
-    // now, as long as the pool's extra part lasts (it covers three times the
-    // ranks the output can hold: tiles just beyond the capacity are the ones
-    // that come within it next time).  Offsets are the running sum of the
-    // sizes, taken from the same prefix that gives the output positions, and
-    // rounded down to 16 pairs = 128 bytes, so two tiles never write into the
-    // same cache line (partial writes to one line from different dies are slow).
-    if (have_tile) {
-        const uint64_t ex  = A.pool_extra;  // multiple of 16
-        const uint64_t a2  = (2u * r0) & ~15ull, b2 = (2u * (r0 + c)) & ~15ull;
-        const uint64_t lo2 = a2 < ex ? a2 : ex;
-        const uint64_t hi2 = b2 < ex ? b2 : ex;
-        A.slot_tab_next[tile] = make_uint2((uint32_t)((uint64_t)tile * A.slots_min + lo2),
-                                           A.slots_min + (uint32_t)(hi2 - lo2));
-    }
-
-    if (tot == 0) return;
-    float spill = 0.f;
-
-    // Staged pairs of the whole chunk, copied by all lanes: pair number j of the
-    // chunk (tiles in order, pairs in order inside a tile) belongs to the first
-    // tile whose running staged count exceeds j.
-    {
-        const uint2 *__restrict__    stage   = A.stage;
-        uint32_t *__restrict__       out_idx = A.out_idx;
-        float *__restrict__          out_val = A.out_val;
-        const uint32_t *__restrict__ incl_w  = s_incl[wave];
-        const uint32_t *__restrict__ off_w = s_off[wave];
-        const uint32_t *__restrict__ rel_w = s_rel[wave];
-        // kCopy pairs per lane and trip.  The searches of one trip run side by side,
-        // step by step (six LDS reads each, one after the other), and so do the loads
-        // of the pairs they find.
-        constexpr uint32_t kCopy = 8;
-        for (uint32_t j0 = lane; j0 < tots; j0 += 64u * kCopy) {
-            uint32_t pos[kCopy];
+        for (uint32_t v = 0; v < 4; ++v) c4[v] = p[v < n_vec ? v : 0u];
 #pragma unroll
-            for (uint32_t q = 0; q < kCopy; ++q) pos[q] = 0u;
-            // first tile with incl_w[tile] > j: incl_w is non-decreasing over all 64
-            // entries and incl_w[63] = tots > j, so the answer is in [0, 63]
+        for (uint32_t v = 0; v < 4; ++v) {
+            const uint32_t ww[4] = {c4[v].x, c4[v].y, c4[v].z, c4[v].w};
 #pragma unroll
-            for (uint32_t step = 32u; step >= 1u; step >>= 1) {
-#pragma unroll
-                for (uint32_t q = 0; q < kCopy; ++q) {
-                    const uint32_t j = j0 + q * 64u;
-                    if (incl_w[pos[q] + step - 1u] <= j) pos[q] += step;
+            for (uint32_t k = 0; k < 4; ++k) {
+                const uint32_t cnt  = ww[k] & kCountMask;
+                const bool     here = !found && v < n_vec && rem < cnt;
+                if (here) word = ww[k];
+                found = found || here;
+                if (!found && v < n_vec) {
+                    rem -= cnt;
+                    ++tile;
                 }
             }
-            uint2    pr[kCopy];
-            uint32_t rr[kCopy];
+        }
+    }
+    return tile;
+}
+
+// ---- by rank: a workgroup takes a window of consecutive output ranks, 1024 to 4096 of them
+// (as many as it takes for all workgroups together to cover the output in one pass), one to
+// four per thread.  Two threads look the window's first and last rank up in the table; the
+// groups in between hold every pair of the window.  If their tile words fit (4096), the
+// workgroup spreads the tiles' running counts out in LDS -- one coalesced load, one scan --
+// and every thread finds its ranks' tiles there with a short binary search.  If only their
+// segment counters fit (sparse selections: hundreds of tiles per output pair), the same is
+// done with segments, and each thread then walks through its segment's tile words.  Beyond
+// that every thread walks down all levels on its own.  Then the pairs are copied, all loads
+// of a thread in flight together. ----
+template <bool NORM, int CMP>
+__device__ void place_ranks(const FinishArgs &A, PlaceShared &S, uint32_t n_g, uint32_t n_out,
+                            uint32_t wg, uint32_t n_wg, float delta, double &sub, uint32_t &sub_nf)
+{
+    constexpr uint32_t kMaxPer = 4;  // output ranks per thread and window
+    const uint32_t tid  = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = tid >> 6;
+    const uint32_t sh   = A.seg_shift;
+    const uint32_t gs   = A.grp_shift;
+    uint32_t e_lo = 0u, e_hi = 0xFFFFFFFFu;
+    if (A.sel_rank != kAllParts)  // the iteration counter moves only after the exchange
+        partition_elems(A.cur_part, A.cur_pos, owned_partition(A.st->t, A.sel_rank, A.n_parts),
+                        A.block_size, n_g, e_lo, e_hi);
+    // ranks per thread: as many as it takes to cover the output in one pass, at most kMaxPer
+    const uint64_t one_each = (uint64_t)n_wg * kFinishWG;
+    const uint32_t per  = n_out > 3u * one_each ? 4u : n_out > 2u * one_each ? 3u : n_out > one_each ? 2u : 1u;
+    const uint64_t span = (uint64_t)per * kFinishWG;
+    for (uint64_t w0 = (uint64_t)wg * span; w0 < n_out; w0 += (uint64_t)n_wg * span) {  // workgroup-uniform
+        const uint32_t w1 = w0 + span < n_out ? (uint32_t)(w0 + span) : n_out;  // the window is [w0, w1)
+        // every thread looks at a few groups: the two that hold the window's ends report
+        for (uint32_t g = tid; g < A.n_groups; g += kFinishWG) {
+            const uint32_t lo = S.grp[g], hi = g + 1u < A.n_groups ? S.grp[g + 1u] : S.total;
+            if (lo <= (uint32_t)w0 && (uint32_t)w0 < hi) S.win[0] = g;
+            if (lo <= w1 - 1u && w1 - 1u < hi) S.win[1] = g;
+        }
+        __syncthreads();
+        const uint32_t g_lo = S.win[0], n_grp = S.win[1] - g_lo + 1u;
+        const uint32_t base = S.grp[g_lo];  // rank of the first pair of group g_lo
+        // what is spread out: tile words if they fit, else segment counters, else nothing
+        const bool by_tile = ((uint64_t)n_grp << (gs + sh)) <= kWinTiles;        // workgroup-uniform
+        const bool by_seg  = !by_tile && ((uint64_t)n_grp << gs) <= kWinTiles;   // workgroup-uniform
+        const uint32_t *src_cnt = by_tile ? A.tile_cnt + ((size_t)g_lo << (gs + sh)) : A.seg_cnt + (g_lo << gs);
+        const uint32_t  n_ent   = by_tile ? n_grp << (gs + sh) : n_grp << gs;    // multiple of 4 when it is used
+        const uint32_t  cmask   = by_tile ? kCountMask : 0xFFFFFFFFu;
+
+        uint32_t tile[kMaxPer], within[kMaxPer], word[kMaxPer];
+        bool     active[kMaxPer];
 #pragma unroll
-            for (uint32_t q = 0; q < kCopy; ++q) {
-                const uint32_t j = j0 + q * 64u;
-                pr[q] = make_uint2(0u, 0u);
-                rr[q] = 0;
-                if (j < tots) {
-                    const uint32_t t      = pos[q];
-                    const uint32_t within = j - (t ? incl_w[t - 1u] : 0u);
-                    pr[q] = stage[off_w[t] + within];
-                    rr[q] = rel_w[t] + within;
-                }
+        for (uint32_t q = 0; q < kMaxPer; ++q) {
+            active[q] = q < per && w0 + (uint64_t)q * kFinishWG + tid < w1;
+            tile[q] = 0; within[q] = 0; word[q] = 0;
+        }
+        if (by_tile || by_seg) {
+            // running counts of the window's tiles (segments), four per thread
+            uint4 w4 = *reinterpret_cast<const uint4 *>(src_cnt + (4u * tid < n_ent ? 4u * tid : 0u));
+            if (4u * tid >= n_ent) w4 = make_uint4(0u, 0u, 0u, 0u);
+            const uint32_t c0 = w4.x & cmask, c1 = w4.y & cmask, c2 = w4.z & cmask, c3 = w4.w & cmask;
+            const uint32_t incl = wave_incl_scan((c0 + c1) + (c2 + c3), lane);
+            if (lane == 63) S.wtot[wave] = incl;
+            __syncthreads();
+            uint32_t run = incl - ((c0 + c1) + (c2 + c3));
+            run += waves_before(S.wtot, wave);
+            run += c0; S.tpre[4u * tid]      = run;
+            run += c1; S.tpre[4u * tid + 1u] = run;
+            run += c2; S.tpre[4u * tid + 2u] = run;
+            run += c3; S.tpre[4u * tid + 3u] = run;
+            if (by_tile) *reinterpret_cast<uint4 *>(&S.tword[4u * tid]) = w4;
+            __syncthreads();
+            // first entry whose running count exceeds the rank's position among the window's
+            // groups: tpre is non-decreasing over all kWinTiles entries and the window's last
+            // rank lies in its last group, so the answer is below n_ent
+            uint32_t pos[kMaxPer], j[kMaxPer];
+#pragma unroll
+            for (uint32_t q = 0; q < kMaxPer; ++q) {
+                pos[q] = active[q] ? (uint32_t)w0 + q * kFinishWG + tid - base : 0u;
+                j[q]   = 0;
+            }
+            // the searches of a thread's ranks go side by side, step by step
+#pragma unroll
+            for (uint32_t step = kWinTiles / 2u; step >= 1u; step >>= 1) {
+                uint32_t probe[kMaxPer];
+#pragma unroll
+                for (uint32_t q = 0; q < kMaxPer; ++q) probe[q] = S.tpre[j[q] + step - 1u];
+#pragma unroll
+                for (uint32_t q = 0; q < kMaxPer; ++q)
+                    if (probe[q] <= pos[q]) j[q] += step;
             }
 #pragma unroll
-            for (uint32_t q = 0; q < kCopy; ++q) {
-                if (j0 + q * 64u < tots) {
-                    const uint64_t r = base + rr[q];
-                    if (r < cap) {
-                        out_idx[r] = pr[q].x;
-                        out_val[r] = __uint_as_float(pr[q].y);
-                    } else {
-                        // beyond the output capacity: not sent, so it goes back into the residual
-                        const float v = __uint_as_float(pr[q].y);
-                        A.e[pr[q].x] = v;
-                        if (NORM) spill += v * v;
+            for (uint32_t q = 0; q < kMaxPer; ++q) within[q] = pos[q] - (j[q] ? S.tpre[j[q] - 1u] : 0u);
+            if (by_tile) {
+#pragma unroll
+                for (uint32_t q = 0; q < kMaxPer; ++q) {
+                    tile[q] = (g_lo << (gs + sh)) + j[q];
+                    word[q] = S.tword[j[q]];
+                }
+            } else {
+#pragma unroll 1
+                for (uint32_t q = 0; q < per; ++q) {
+                    uint32_t rem = 0, wd = 0, t = 0, seg = 0;
+#pragma unroll
+                    for (uint32_t k = 0; k < kMaxPer; ++k)
+                        if (k == q) {
+                            rem = within[k];
+                            seg = (g_lo << gs) + j[k];
+                        }
+                    if (active[q]) t = find_tile(A, seg, rem, wd);
+#pragma unroll
+                    for (uint32_t k = 0; k < kMaxPer; ++k)
+                        if (k == q) {
+                            tile[k] = t; within[k] = rem; word[k] = wd;
+                        }
+                }
+            }
+        } else {
+#pragma unroll 1
+            for (uint32_t q = 0; q < per; ++q) {
+                const uint32_t r = (uint32_t)w0 + q * kFinishWG + tid;
+                uint32_t rem = 0, wd = 0, t = 0;
+                if (w0 + (uint64_t)q * kFinishWG + tid < w1) {
+                    const uint32_t g = find_group(A, S, r);
+                    rem = r - S.grp[g];
+                    const uint32_t seg = find_segment(A, g, rem);
+                    t = find_tile(A, seg, rem, wd);
+                }
+#pragma unroll
+                for (uint32_t k = 0; k < kMaxPer; ++k)
+                    if (k == q) {
+                        tile[k] = t; within[k] = rem; word[k] = wd;
+                    }
+            }
+        }
+        // the pairs themselves: within is the position among the tile's staged pairs
+        {
+            const uint2 *src[kMaxPer];
+            uint2        pr[kMaxPer];
+#pragma unroll
+            for (uint32_t q = 0; q < kMaxPer; ++q) {
+                src[q] = nullptr;
+                if (active[q] && !(word[q] & kFlag)) src[q] = staged_pairs(A, tile[q], word[q]) + within[q];
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < kMaxPer; ++q) pr[q] = src[q] ? *src[q] : make_uint2(0u, 0u);
+#pragma unroll
+            for (uint32_t q = 0; q < kMaxPer; ++q) {
+                if (src[q]) {
+                    const uint32_t r = (uint32_t)w0 + q * kFinishWG + tid;
+                    A.out_idx[r] = pr[q].x;
+                    A.out_val[r] = __uint_as_float(pr[q].y);
+                    if (word[q] & kKept) {
+                        // staged but left in the residual: zeroed now that it is sent
+                        A.e[pr[q].x] = 0.0f;
+                        if (NORM) left_selected(__uint_as_float(pr[q].y), sub, sub_nf);
                     }
                 }
             }
         }
+        // Flagged tiles: the lane whose rank is a flagged tile's FIRST pair has its wave re-read
+        // that tile and emit all of it (up to the capacity); the tile's other ranks, in this
+        // wave or elsewhere, are left to that one wave.
+#pragma unroll
+        for (uint32_t q = 0; q < kMaxPer; ++q) {
+            uint64_t pend = __ballot(active[q] && (word[q] & kFlag) != 0 && within[q] == 0u);
+            while (pend) {  // wave-uniform
+                const uint32_t l = (uint32_t)__ffsll((unsigned long long)pend) - 1u;
+                pend &= pend - 1u;
+                emit_flagged_tile<NORM, CMP>(A, wave_lane(tile[q], l),
+                                             wave_lane((uint32_t)w0 + q * kFinishWG + tid, l), n_out, delta,
+                                             lane, n_g, e_lo, e_hi, sub, sub_nf);
+            }
+        }
+        __syncthreads();  // S.win, S.tpre, S.tword are rewritten by the next window
     }
+}
 
-    uint64_t flagged = __ballot((word & kFlag) != 0);
-    uint32_t e_lo = 0u, e_hi = 0xFFFFFFFFu;
-    if (flagged && A.sel_rank != kAllParts)  // the iteration counter moves only after the exchange
-        partition_elems(A.cur_part, A.cur_pos, owned_partition(A.st->t, A.sel_rank, A.n_parts),
-                        A.block_size, n_g, e_lo, e_hi);
-    while (flagged) {  // wave-uniform
-        const uint32_t l = (uint32_t)__ffsll((unsigned long long)flagged) - 1u;
-        flagged &= flagged - 1u;
-        const uint32_t lo = __shfl((uint32_t)r0, l, 64), hi = __shfl((uint32_t)(r0 >> 32), l, 64);
-        const float    dl = __shfl(delta, l, 64);
-        compact_flagged_tile<NORM, CMP>(A, (chunk << cs) + l, ((uint64_t)hi << 32) | lo, dl, lane,
-                                        n_g, cap, e_lo, e_hi, spill);
+template <bool NORM, int CMP>
+__device__ void finish_place(const FinishArgs &A, uint32_t n_g, uint64_t cap)
+{
+    constexpr uint32_t kWaves = kFinishWG / 64;
+    __shared__ PlaceShared S;
+    const uint32_t tid  = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t wave = tid >> 6;
+    const uint32_t wg   = blockIdx.x - 1u;
+    const bool by_tile  = wg < A.n_tile_wgs;  // workgroup-uniform
+
+    // what the device state is asked for, and a tile workgroup's first tile words, are requested
+    // before the table is built: every first touch of memory costs over a microsecond here
+    // (volatile: issued here, in program order, and waited for only where the value is used)
+    const float    delta  = *reinterpret_cast<const volatile float *>(&A.st->delta[A.parity]);
+    const uint64_t k_prev = *reinterpret_cast<const volatile uint64_t *>(&A.st->k_hist[A.parity ^ 1u]);  // the control workgroup writes the other entry
+    uint4 w4 = make_uint4(0u, 0u, 0u, 0u);
+    if (by_tile) {
+        const uint32_t tile0 = (wg * kFinishWG + tid) * kTilesPerThr;
+        if (tile0 < A.n_tiles) w4 = *reinterpret_cast<const uint4 *>(A.tile_cnt + tile0);
     }
+    place_table(A, S);
+    const uint32_t total = S.total;                                  // selected by this pass
+    const uint32_t n_out = total < cap ? total : (uint32_t)cap;      // pairs the output receives
+    double   sub = 0.0, add = 0.0;   // norm statistic: squares leaving / re-entering the residual
+    uint32_t sub_nf = 0;
+    if (by_tile)
+        place_tiles<NORM>(A, S, cap, wg, w4, k_prev, add);
+    else
+        place_ranks<NORM, CMP>(A, S, n_g, n_out, wg - A.n_tile_wgs, gridDim.x - 1u - A.n_tile_wgs, delta, sub,
+                               sub_nf);
 
     if (NORM) {
-        double sq = (double)spill;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) sq += __shfl_xor(sq, d, 64);
-        if (lane == 0 && sq != 0.0) atomicAdd(&A.err_slots[chunk % kErrSlots], sq);
+        const double net = wave_sum(add - sub);
+        sub_nf = wave_sum(sub_nf);
+        if (lane == 0) {
+            // into the slots that hold the squares of the selected entries the streaming pass left behind
+            if (net != 0.0) atomicAdd(&A.err_slots[kErrSlots + (wg * kWaves + wave) % kErrSlots], net);
+            if (sub_nf) atomicAdd(&A.st->nf_emit[A.parity], sub_nf);
+        }
     }
 }
 
@@ -589,7 +949,7 @@ k_finish(FinishArgs A, CtrlParams prm)
     if (blockIdx.x == 0)
         finish_control(A, prm);
     else
-        finish_compact<NORM, CMP>(A, (uint32_t)prm.n_g, prm.cap);
+        finish_place<NORM, CMP>(A, (uint32_t)prm.n_g, prm.cap);
 }
 
 }  // namespace

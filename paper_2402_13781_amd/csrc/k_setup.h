@@ -35,7 +35,7 @@ __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_
         part_off[tid] = 0;
     }
     if (tid == P) part_off[P] = 0;
-    if (tid < 2 * kErrSlots) err_slots[tid] = 0.0;
+    if (tid < 4 * kErrSlots) err_slots[tid] = 0.0;
     if (tid == 0) {
         st->delta[0] = delta0;
         st->delta[1] = delta0;
@@ -45,14 +45,17 @@ __global__ void k_init_state(DevState *st, int32_t *part0, int32_t *pos0, int32_
         st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
         st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
         st->own_actual = 0; st->own_emitted = 0; st->bad_index = 0; st->pad = 0; st->padding = 0;
+        st->nf_sel[0] = st->nf_sel[1] = 0; st->nf_emit[0] = st->nf_emit[1] = 0;
+        st->k_hist[0] = st->k_hist[1] = 0;
     }
 }
 
-// Before the first iteration every wave tile has its slots_min staging slots.
-__global__ void k_init_slot_tab(uint2 *tab0, uint2 *tab1, uint32_t n_tiles, uint32_t slots_min)
+// Before the first iteration every wave tile has only its fixed staging slots and zeroes what
+// it stages (nothing is known yet that would place a tile beyond the output capacity).
+__global__ void k_init_slot_tab(uint2 *tab0, uint2 *tab1, uint32_t n_tiles)
 {
     for (uint32_t i = blockIdx.x * blockDim.x + threadIdx.x; i < n_tiles; i += gridDim.x * blockDim.x) {
-        const uint2 v = make_uint2(i * slots_min, slots_min);
+        const uint2 v = make_uint2(0u, kZeroBit);
         tab0[i] = v;
         tab1[i] = v;
     }
@@ -69,18 +72,27 @@ __global__ void k_restore_state(DevState *st, uint64_t t, float delta)
     st->k_actual = 0; st->k_emitted = 0; st->k_max_part = 0;
     st->density_error = 0.0; st->traffic_ratio = 0.0; st->err_norm = -1.0;
     st->own_actual = 0; st->own_emitted = 0; st->bad_index = 0; st->pad = 0; st->padding = 0;
+    st->nf_sel[0] = st->nf_sel[1] = 0; st->nf_emit[0] = st->nf_emit[1] = 0;
+    st->k_hist[0] = st->k_hist[1] = 0;
 }
 
-__global__ void k_norm_finalize(DevState *st, const double *err_slots)
+// Eq. 1 from the partial sums of squares.  A selected infinity that stayed in the residual is
+// not in the sums (it would cancel badly against the ones that were emitted): it is counted.
+__global__ void k_norm_finalize(DevState *st, const double *err_slots, uint32_t parity)
 {
     __shared__ double s[kErrSlots];
-    s[threadIdx.x] = err_slots[threadIdx.x];
+    // unselected squares, and what is left of the selected entries that stayed in the residual
+    s[threadIdx.x] = err_slots[threadIdx.x] + err_slots[kErrSlots + threadIdx.x];
     __syncthreads();
     for (uint32_t d = kErrSlots / 2; d >= 1; d >>= 1) {
         if (threadIdx.x < d) s[threadIdx.x] += s[threadIdx.x + d];
         __syncthreads();
     }
-    if (threadIdx.x == 0) st->err_norm = sqrt(s[0] > 0.0 ? s[0] : s[0] == s[0] ? 0.0 : s[0]);
+    if (threadIdx.x == 0) {
+        double sq = s[0] > 0.0 ? s[0] : s[0] == s[0] ? 0.0 : s[0];
+        if (sq == sq && st->nf_sel[parity] > st->nf_emit[parity]) sq = INFINITY;
+        st->err_norm = sqrt(sq);
+    }
 }
 
 }  // namespace

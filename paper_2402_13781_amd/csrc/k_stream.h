@@ -13,13 +13,17 @@ struct StreamArgs {
     const void     *g;          // n_g gradients of the kernel's element type
     float           eta;        // learning rate (used by the scaled variants only)
     float          *e;
-    const DevState *st;
-    uint2          *stage;      // staging pool of (index, value bits) pairs
-    const uint2    *slot_tab;   // per tile: {first slot, number of slots} for this iteration
-    uint32_t       *tile_cnt;   // n_tiles: selected in the tile, kFlag if not staged
+    DevState       *st;
+    uint2          *stage;      // staging pool of (index, value bits) pairs: slots_min per tile ...
+    uint2          *stage_extra;  // ... then the part handed out by the slot table
+    const uint2    *slot_tab;   // per tile: {offset in the extra part, slots there | bits} for this iteration
+    uint32_t       *tile_cnt;   // n_tiles: selected in the tile | kFlag (only counted) | kKept (staged, not zeroed)
+    uint32_t        slots_min;  // fixed staging slots of every tile
+    uint32_t        pack_off;   // the tile word also carries the offset of pairs staged in the extra part
     uint32_t       *blk_cnt;    // this iteration's per-block counters (zero on entry)
     uint32_t       *seg_cnt;    // this iteration's per-segment counters (zero on entry)
-    double         *err_slots;
+    double         *err_slots;  // norm statistic: kErrSlots sums of unselected squares, then
+                                // kErrSlots sums over selected entries left in the residual
     uint32_t        n_g, n_tiles, gran_per_blk, parity;
     uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
     uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
@@ -59,10 +63,32 @@ __device__ __forceinline__ void partition_granules(const int32_t *part, const in
     hi = (ps + pn) * gran_per_blk;
 }
 
+// Norm statistic: a selected entry that this pass leaves in the residual (its tile is not
+// zeroed in registers) goes into a separate fp64 sum, from which the placement subtracts
+// exactly the same square when it emits the entry; infinities are counted instead.
+__device__ __forceinline__ void left_selected(float v, double &sum, uint32_t &nonfinite)
+{
+    if (__builtin_isinf(v))
+        ++nonfinite;
+    else
+        sum += (double)(v * v);
+}
+
 // GEN: block sizes that are multiples of 32 but not of 256.  Block and partition
 // boundaries then fall inside granules (always between lanes: a lane's four
 // gradients share a 32-aligned group), so the comparison is masked per lane
 // and every lane adds its own selected gradients to its block's counter.
+//
+// What a tile does with its selected gradients follows its slot table entry, which the
+// finishing kernel of the iteration before wrote from the tile's output rank then:
+//   zero bit     stage the pairs, zero them in registers (rank well inside the capacity)
+//   no bit       stage the pairs, leave the residual alone: the placement zeroes what it
+//                emits (rank near the capacity: it may or may not fit)
+//   count only   only count (rank far beyond the capacity)
+// Up to slots_min pairs go to the tile's fixed slots (found without the table), more to its
+// slots in the extra part of the pool if the table gave it enough.  A tile with more selected
+// gradients than that is counted and flagged; the placement re-reads it from the residual if
+// its rank turns out to lie within the capacity.
 template <int CMP, bool NORM, int GT, bool SCALE, bool GEN>
 __global__ void __launch_bounds__(kStreamWG)
 k_stream(StreamArgs A)
@@ -76,7 +102,9 @@ k_stream(StreamArgs A)
     const uint32_t n_full = A.n_g >> 8;  // complete granules
     const bool     live   = tile < A.n_tiles;            // wave-uniform
     const bool     fast   = gran0 + kTileGran <= n_full;  // wave-uniform: no ragged end inside
-    float nrm = 0.f;
+    float    nrm = 0.f;
+    double   left = 0.0;
+    uint32_t left_nf = 0;
     uint32_t g_lo = 0u, g_hi = 0xFFFFFFFFu;  // granules that are compared at all
     uint32_t e_lo = 0u, e_hi = 0xFFFFFFFFu;  // GEN: the same as a gradient range
     if (A.sel_rank != kAllParts) {
@@ -87,11 +115,11 @@ k_stream(StreamArgs A)
             partition_granules(A.cur_part, A.cur_pos, own_part, A.gran_per_blk, g_lo, g_hi);
     }
 
-    if (live && fast) {
+    if (live) {
         f32x4    a[kTileGran];
         uint32_t nib[kTileGran];
         const uint2 tab = A.slot_tab[tile];  // requested with the data, used only if something is selected
-        {
+        if (fast) {
             f32x4 gv[kTileGran], ev[kTileGran];
 #pragma unroll
             for (uint32_t u = 0; u < kTileGran; ++u) {
@@ -107,12 +135,34 @@ k_stream(StreamArgs A)
                 a[u].w = accumulate<SCALE>(ev[u].w, gv[u].w, A.eta);
                 nib[u] = sel<CMP>(a[u].x, delta) | (sel<CMP>(a[u].y, delta) << 1) |
                          (sel<CMP>(a[u].z, delta) << 2) | (sel<CMP>(a[u].w, delta) << 3);
-                if (GEN) {
-                    const uint32_t i0 = ((gran0 + u) << 8) + lane * 4u;
-                    if (i0 < e_lo || i0 >= e_hi) nib[u] = 0u;
-                } else if (gran0 + u < g_lo || gran0 + u >= g_hi) {
-                    nib[u] = 0u;  // wave-uniform: another worker's partition
+            }
+        } else {
+            // the ragged end of the vector (its last wave tile): guarded scalar loads; what
+            // lies beyond n_g reads as zero and is never compared
+#pragma unroll
+            for (uint32_t u = 0; u < kTileGran; ++u) {
+                const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
+                float    v[4];
+                uint32_t f = 0;
+#pragma unroll
+                for (uint32_t q = 0; q < 4; ++q) {
+                    v[q] = 0.f;
+                    if (base + q < A.n_g) {
+                        v[q] = accumulate<SCALE>(A.e[base + q], load_grad1<GT>(A.g, base + q), A.eta);
+                        f |= sel<CMP>(v[q], delta) << q;
+                    }
                 }
+                a[u].x = v[0]; a[u].y = v[1]; a[u].z = v[2]; a[u].w = v[3];
+                nib[u] = f;
+            }
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < kTileGran; ++u) {
+            if (GEN) {
+                const uint32_t i0 = ((gran0 + u) << 8) + lane * 4u;
+                if (i0 < e_lo || i0 >= e_hi) nib[u] = 0u;
+            } else if (gran0 + u < g_lo || gran0 + u >= g_hi) {
+                nib[u] = 0u;  // wave-uniform: another worker's partition
             }
         }
 
@@ -137,24 +187,51 @@ k_stream(StreamArgs A)
                 total += cu[u];
             }
             word = total;
-            if (total <= tab.y) {
-                // staged: pairs in index order, residual zeroed where sent (+0)
-                uint2   *slot = A.stage + tab.x;
+            uint2 *slot = nullptr;  // wave-uniform
+            if (!(tab.y & kCountOnly)) {
+                if (total <= A.slots_min)
+                    slot = A.stage + (size_t)tile * A.slots_min;
+                else if (total <= (tab.y & kSlotMask)) {
+                    slot = A.stage_extra + tab.x;
+                    if (A.pack_off) word |= (tab.x >> 4) << kOffShift;  // offsets are multiples of 16
+                }
+            }
+            if (slot) {
+                // staged: pairs in index order
                 uint32_t pre  = 0;
 #pragma unroll
                 for (uint32_t u = 0; u < kTileGran; ++u) {
                     if (nib[u]) {
                         uint32_t       r  = pre + below[u];
                         const uint32_t i0 = ((gran0 + u) << 8) + lane * 4u;
-                        if (nib[u] & 1u) { slot[r++] = make_uint2(i0, __float_as_uint(a[u].x)); a[u].x = 0.f; }
-                        if (nib[u] & 2u) { slot[r++] = make_uint2(i0 + 1u, __float_as_uint(a[u].y)); a[u].y = 0.f; }
-                        if (nib[u] & 4u) { slot[r++] = make_uint2(i0 + 2u, __float_as_uint(a[u].z)); a[u].z = 0.f; }
-                        if (nib[u] & 8u) { slot[r++] = make_uint2(i0 + 3u, __float_as_uint(a[u].w)); a[u].w = 0.f; }
+                        if (nib[u] & 1u) slot[r++] = make_uint2(i0, __float_as_uint(a[u].x));
+                        if (nib[u] & 2u) slot[r++] = make_uint2(i0 + 1u, __float_as_uint(a[u].y));
+                        if (nib[u] & 4u) slot[r++] = make_uint2(i0 + 2u, __float_as_uint(a[u].z));
+                        if (nib[u] & 8u) slot[r++] = make_uint2(i0 + 3u, __float_as_uint(a[u].w));
                     }
                     pre += cu[u];
                 }
             } else {
-                word = total | kFlag;  // too many for the slots: compaction re-reads this tile
+                word |= kFlag;  // more than the slots hold (or no slots at all): counted only
+            }
+            if (slot && !(tab.y & kZeroBit)) word |= kKept;
+            if (slot && (tab.y & kZeroBit)) {  // wave-uniform
+                // the residual is zeroed where sent (+0), before its only store
+#pragma unroll
+                for (uint32_t u = 0; u < kTileGran; ++u) {
+                    if (nib[u] & 1u) a[u].x = 0.f;
+                    if (nib[u] & 2u) a[u].y = 0.f;
+                    if (nib[u] & 4u) a[u].z = 0.f;
+                    if (nib[u] & 8u) a[u].w = 0.f;
+                }
+            } else if (NORM) {
+#pragma unroll
+                for (uint32_t u = 0; u < kTileGran; ++u) {
+                    if (nib[u] & 1u) left_selected(a[u].x, left, left_nf);
+                    if (nib[u] & 2u) left_selected(a[u].y, left, left_nf);
+                    if (nib[u] & 4u) left_selected(a[u].z, left, left_nf);
+                    if (nib[u] & 8u) left_selected(a[u].w, left, left_nf);
+                }
             }
             if (GEN) {
 #pragma unroll
@@ -190,58 +267,47 @@ k_stream(StreamArgs A)
             }
         }
 
+        if (fast) {
 #pragma unroll
-        for (uint32_t u = 0; u < kTileGran; ++u) {
-            const size_t off = ((size_t)(gran0 + u) << 8) + lane * 4u;
-            __builtin_nontemporal_store(a[u], reinterpret_cast<f32x4 *>(A.e + off));
+            for (uint32_t u = 0; u < kTileGran; ++u) {
+                const size_t off = ((size_t)(gran0 + u) << 8) + lane * 4u;
+                __builtin_nontemporal_store(a[u], reinterpret_cast<f32x4 *>(A.e + off));
+            }
+        } else {
+#pragma unroll
+            for (uint32_t u = 0; u < kTileGran; ++u) {
+                const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
+                if (base < A.n_g) A.e[base] = a[u].x;
+                if (base + 1 < A.n_g) A.e[base + 1] = a[u].y;
+                if (base + 2 < A.n_g) A.e[base + 2] = a[u].z;
+                if (base + 3 < A.n_g) A.e[base + 3] = a[u].w;
+            }
         }
         if (lane == 0) A.tile_cnt[tile] = word;
-    } else if (live) {
-        // The ragged end of the vector (at most the last workgroup): guarded
-        // scalar accesses, one granule at a time.  The tile is only counted and
-        // flagged; compaction ranks and zeroes it from the residual.
-        uint32_t total = 0;
-#pragma unroll 1
-        for (uint32_t u = 0; u < kTileGran; ++u) {
-            const uint64_t base = ((uint64_t)(gran0 + u) << 8) + lane * 4u;
-            uint32_t f = 0;
-            const bool mine = GEN ? (base >= e_lo && base < e_hi)
-                                  : (gran0 + u >= g_lo && gran0 + u < g_hi);  // wave-uniform unless GEN
-#pragma unroll
-            for (uint32_t q = 0; q < 4; ++q) {
-                if (base + q < A.n_g) {
-                    const float v = accumulate<SCALE>(A.e[base + q], load_grad1<GT>(A.g, base + q), A.eta);
-                    A.e[base + q] = v;
-                    const uint32_t hit = mine ? sel<CMP>(v, delta) : 0u;
-                    f |= hit << q;
-                    if (NORM) nrm += hit ? 0.f : v * v;
-                }
-            }
-            uint32_t cu, below;
-            granule_ranks(f, cu, below);
-            if (GEN) {
-                if (f) atomicAdd(&A.blk_cnt[(uint32_t)base / A.block_size], (uint32_t)__popc(f));
-            } else if (cu && lane == 0) {
-                atomicAdd(&A.blk_cnt[(gran0 + u) / A.gran_per_blk], cu);  // = its segment if one_counter
-            }
-            total += cu;
-        }
-        if (lane == 0) {
-            if (total && !A.one_counter) atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
-            A.tile_cnt[tile] = total ? (total | kFlag) : 0u;
-        }
     }
 
     if (NORM) {
-        __shared__ double wsum[kWavesPerWG];
-        double s = (double)nrm;
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) s += __shfl_xor(s, d, 64);
-        if (lane == 0) wsum[wave] = s;
+        __shared__ double   wsum[kWavesPerWG];
+        __shared__ double   wleft[kWavesPerWG];
+        __shared__ uint32_t wnf[kWavesPerWG];
+        const double s = wave_sum((double)nrm);
+        left    = wave_sum(left);
+        left_nf = wave_sum(left_nf);
+        if (lane == 0) {
+            wsum[wave]  = s;
+            wleft[wave] = left;
+            wnf[wave]   = left_nf;
+        }
         __syncthreads();
         if (threadIdx.x == 0) {
-            double tot = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+            // The two sums go to separate slots: what the placement subtracts later must meet
+            // a sum of its own kind, not one already rounded together with many small squares.
+            const double   tot  = wsum[0] + wsum[1] + wsum[2] + wsum[3];
+            const double   totl = wleft[0] + wleft[1] + wleft[2] + wleft[3];
+            const uint32_t nf   = wnf[0] + wnf[1] + wnf[2] + wnf[3];
             atomicAdd(&A.err_slots[blockIdx.x % kErrSlots], tot);
+            if (totl != 0.0) atomicAdd(&A.err_slots[kErrSlots + blockIdx.x % kErrSlots], totl);
+            if (nf) atomicAdd(&A.st->nf_sel[A.parity], nf);
         }
     }
 }
