@@ -2,10 +2,19 @@
 """Benchmark of the ExDyna gradient-selection hot path on one MI355X.
 
 A step is one exdyna_step (the streaming accumulate + compare + stage pass, then
-the finishing kernel: control + compaction) over one synthetic gradient vector
+the finishing kernel: control + placement) over one synthetic gradient vector
 that is already resident in HBM.  Prints ONE JSON line: whole-step throughput in G elements/s, the HBM
 roofline of the dominant kernel measured with HIP events over the timed steps,
 and the CPU oracle timed on a bounded sample of the same trajectory.
+
+The headline numbers are those of the window the caller asks for (--warmup W, --steps K:
+iterations W .. W+K-1 of the workload's trajectory from its first iteration on).  With the
+default hyper-parameters the threshold needs about 50 iterations to catch up with the
+residual build-up of workload 4, so a short warm-up times the transient, in which k' is far
+above the output capacity.  Two more measurements ride along in the same JSON line, labelled
+as such: `steady_state` (the same context carried on to iteration 60, then 40 more timed
+steps) and `cfg5` (the 1.5 G-gradient workload, a few timed steps), so that one run shows
+both windows and both configurations the target is stated for.
 """
 from __future__ import annotations
 
@@ -22,12 +31,32 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 ALG_BYTES_PER_ELEM = 12.0      # read g (4) + read e (4) + write e' (4)
 ALG_BYTES_PER_PAIR = 8.0       # u32 index + fp32 value per selected gradient
+STEADY_FROM, STEADY_STEPS = 60, 40            # the second, settled window of the same context
+CFG5_VECTORS, CFG5_WARMUP, CFG5_STEPS = 4, 5, 20   # the 1.5 G-gradient workload riding along
 
 # HBM bytes per k_stream launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
-# summarised in profiles/k_stream_cfg4_hbm_traffic.txt (each counter scaled by what it reads for
-# a plain device copy of one gradient vector: FETCH_SIZE x2.000, WRITE_SIZE x1.000, KiB), keyed
-# by workload index; None for workloads that have not been measured.
-MEASURED_TRAFFIC_BYTES = {4: int((542666.0 * 2.0 + 546328.1) * 1024)}
+# summarised under profiles/ (each counter scaled by what it reads for a plain device copy of
+# one gradient vector: FETCH_SIZE x2.000, WRITE_SIZE x1.000, KiB).  Counters cannot be read
+# from inside this program, so the figure is the one of the committed summary for the same
+# workload and kind of window, and `traffic_source` names it; None where nothing was measured.
+MEASURED_TRAFFIC = {
+    (4, "steady"): (int((542666.0 * 2.0 + 546328.1) * 1024),
+                    "profiles/k_stream_cfg4_hbm_traffic.txt (rocprofv3 --pmc, --warmup 60 window)"),
+}
+
+
+def cpu_description():
+    """Model string and logical core count of the host the oracle is timed on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return model, os.cpu_count()
 
 
 def main() -> int:
@@ -63,6 +92,8 @@ def main() -> int:
                          "of 256 take the faster kernel variant)")
     ap.add_argument("--density", type=float, default=0.0,
                     help="override the workload's target density d")
+    ap.add_argument("--no-extras", dest="extras", action="store_false",
+                    help="only the asked-for window: no steady_state and cfg5 measurements")
     ap.add_argument("--hbm-budget-gb", type=float, default=160.0,
                     help="HBM to spend on pre-generated gradient vectors")
     args = ap.parse_args()
@@ -92,7 +123,8 @@ def main() -> int:
 
     # ---- gradients resident in HBM before the clock starts -------------------
     vec_gb = w.n_g * (4 if args.grad_dtype == "f32" else 2) / 1e9
-    n_vec = int(max(2, min(W + K, args.hbm_budget_gb // vec_gb)))
+    want_vec = W + K
+    n_vec = int(max(2, min(want_vec, args.hbm_budget_gb // vec_gb)))
     scaled = args.grad_dtype != "f32"
     eta = float(np.float32(args.eta))
     if scaled:
@@ -106,7 +138,7 @@ def main() -> int:
         grads = [src.grad(t) for t in range(n_vec)]
         thr = synthetic.initial_threshold(grads[0], w.density)
         alg_bytes_per_elem = ALG_BYTES_PER_ELEM
-    recycled = n_vec < W + K
+    recycled = n_vec < want_vec
 
     def gpu_step(ctx, g):
         if scaled:
@@ -153,8 +185,9 @@ def main() -> int:
             return 1
         xv.close()
         del xv, o, h
+        cpu_model, host_cores = cpu_description()
         cpu = {"value": round(w.n_g * cpu_steps / cpu_s / 1e9, 4), "unit": "G elem/s", "cores": 1,
-               "kind": "oracle",
+               "kind": "oracle", "cpu_model": cpu_model, "host_cores_total": host_cores,
                "sample": f"first {cpu_steps} iterations of the same trajectory at full n_g, "
                          f"single thread, {cpu_s:.1f} s; GPU outputs bit-equal on these steps"}
         torch.cuda.empty_cache()
@@ -214,21 +247,64 @@ def main() -> int:
             n = idx_all.numel()
             ctx.worker_exchange(idx_all, counts, val_buf[:n].view(idx_all.shape))
 
-    # ---- timed region ---------------------------------------------------------
+    # ---- timed regions ---------------------------------------------------------
+    prof = not args.no_profile_events
+    every = max(1, args.event_every)
+
+    def timed_window(ctx, step_fn, grad_at, t_first, n_steps, n_g, bytes_per_elem):
+        """Times iterations t_first .. t_first + n_steps - 1 of `ctx` (already at t_first)."""
+        torch.cuda.synchronize()
+        if prof:
+            ctx.set_profiling((n_steps + every - 1) // every, every)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for t in range(t_first, t_first + n_steps):
+            step_fn(ctx, grad_at(t))
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        st = ctx.get_stats()
+        step_bytes = bytes_per_elem * n_g + ALG_BYTES_PER_PAIR * st.k_emitted
+        res = {"first_iteration": t_first, "steps": n_steps,
+               "ms_per_step": round(elapsed / n_steps * 1e3, 5),
+               "value": round(n_g * n_steps / elapsed / 1e9, 3),
+               "hbm_roofline_pct_per_step": round(100.0 * step_bytes / (elapsed / n_steps) / (HBM_PEAK_GBS * 1e9), 2),
+               "step_alg_gb_per_s": round(step_bytes / (elapsed / n_steps) / 1e9, 1),
+               "last_step": {"k_actual": st.k_actual, "k_emitted": st.k_emitted,
+                             "k_target": ctx.cfg.density * n_g, "traffic_ratio": round(st.traffic_ratio, 4),
+                             "delta_next": st.delta_next},
+               "kernels": None, "roofline": None}
+        if prof:
+            ms = np.array([ctx.get_kernel_ms(t) for t in range(t_first, t_first + n_steps, every)],
+                          dtype=np.float64)
+            ctx.set_profiling(0)
+            res["kernels"] = {
+                "k_stream_ms": round(float(ms[:, 0].mean()), 5),
+                "k_finish_ms": round(float(ms[:, 1].mean()), 5),
+                "k_stream_ms_p10_p50_p90": [round(float(v), 5) for v in np.percentile(ms[:, 0], [10, 50, 90])],
+                "k_finish_ms_p10_p50_p90": [round(float(v), 5) for v in np.percentile(ms[:, 1], [10, 50, 90])]}
+            achieved = bytes_per_elem * n_g / (ms[:, 0].mean() * 1e-3) / 1e9
+            res["roofline"] = {"bound": "hbm", "kernel": "k_stream", "achieved": round(achieved, 1),
+                               "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                               "traffic": None, "traffic_source": None,
+                               "alg_bytes_per_launch": bytes_per_elem * n_g,
+                               "launches_timed": int(ms.shape[0])}
+        return res, elapsed
+
+    def add_traffic(res, index, settled):
+        """Counter-measured HBM bytes of one k_stream launch, from the committed summary for this
+        workload and kind of window (transient: k' still far above the capacity)."""
+        if res["roofline"] is None or scaled or args.worker_view or args.block_size or args.density:
+            return
+        hit = MEASURED_TRAFFIC.get((index, "steady" if settled else "transient"))
+        if hit:
+            res["roofline"]["traffic"], res["roofline"]["traffic_source"] = hit
+
     x = binding.ExDyna(cfg, dev)
     for t in range(W):
         gpu_step(x, grads[t % n_vec])
-    torch.cuda.synchronize()
-    prof = not args.no_profile_events
-    every = max(1, args.event_every)
-    if prof:
-        x.set_profiling((K + every - 1) // every, every)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for t in range(W, W + K):
-        gpu_step(x, grads[t % n_vec])
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    head, elapsed = timed_window(x, gpu_step, lambda t: grads[t % n_vec], W, K, w.n_g, alg_bytes_per_elem)
+    settled = head["last_step"]["k_actual"] <= x.capacity
+    add_traffic(head, args.config, settled)
 
     if args.worker_view:
         same = (torch.equal(x.residual.view(torch.int32), ref_residual.view(torch.int32))
@@ -236,35 +312,66 @@ def main() -> int:
         if not same:
             print("bench.py: the worker's trajectory left the reference's", file=sys.stderr)
             return 1
-    ms_events = None
-    if prof:
-        ms_events = np.array([x.get_kernel_ms(t) for t in range(W, W + K, every)], dtype=np.float64)
-    st = x.get_stats()
-    ms_per_step = elapsed / K * 1e3
-    value = w.n_g * K / elapsed / 1e9
-    step_bytes = alg_bytes_per_elem * w.n_g + ALG_BYTES_PER_PAIR * st.k_emitted
-    kern = None
-    roofline = None
-    if prof:
-        ms = ms_events
-        kern = {"k_stream_ms": round(float(ms[:, 0].mean()), 5),
-                "k_finish_ms": round(float(ms[:, 1].mean()), 5),
-                "k_stream_ms_p10_p50_p90": [round(float(v), 5) for v in np.percentile(ms[:, 0], [10, 50, 90])],
-                "k_finish_ms_p10_p50_p90": [round(float(v), 5) for v in np.percentile(ms[:, 1], [10, 50, 90])]}
-        achieved = alg_bytes_per_elem * w.n_g / (ms[:, 0].mean() * 1e-3) / 1e9
-        roofline = {"bound": "hbm", "kernel": "k_stream", "achieved": round(achieved, 1),
-                    "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                    "traffic": None if (scaled or args.worker_view) else MEASURED_TRAFFIC_BYTES.get(args.config),
-                    "alg_bytes_per_launch": alg_bytes_per_elem * w.n_g,
-                    "launches_timed": int(ms.shape[0])}
+
+    # ---- the same context carried on past the threshold transient -------------
+    steady = None
+    extras = args.extras and not args.worker_view
+    if extras and W + K < STEADY_FROM:
+        def fresh(t, out):
+            g = src.grad(t, out=out if not scaled else None)
+            return (g / eta).to(tdt) if scaled else g
+        # the vectors of the first window are done with: they are overwritten with the gradients
+        # of the iterations in between, and a few more buffers make room for the second window
+        for t in range(W + K, STEADY_FROM):
+            grads[t % n_vec] = fresh(t, grads[t % n_vec])
+            gpu_step(x, grads[t % n_vec])
+        n_vec2 = int(max(2, min(STEADY_STEPS, args.hbm_budget_gb // vec_gb)))
+        while len(grads) < n_vec2:
+            grads.append(torch.empty_like(grads[0]))
+        for t in range(STEADY_FROM, STEADY_FROM + n_vec2):
+            grads[t % n_vec2] = fresh(t, grads[t % n_vec2])
+        steady, _ = timed_window(x, gpu_step, lambda t: grads[t % n_vec2], STEADY_FROM, STEADY_STEPS, w.n_g,
+                                 alg_bytes_per_elem)
+        add_traffic(steady, args.config, steady["last_step"]["k_actual"] <= x.capacity)
+        steady["note"] = (f"same context and trajectory carried on untimed to iteration {STEADY_FROM}, "
+                          f"then {STEADY_STEPS} timed steps; gradient vectors "
+                          f"{'recycled' if n_vec2 < STEADY_STEPS or recycled else 'fresh'}")
+    x.close()
+    del x, grads
+    torch.cuda.empty_cache()
+
+    # ---- the 1.5 G-gradient workload, a few steps ------------------------------
+    cfg5 = None
+    if extras and args.config == 4 and not scaled and not args.block_size and not args.density:
+        w5 = synthetic.WORKLOADS[5]
+        src5 = synthetic.GradientSource(w5, dev)
+        g5 = [src5.grad(t) for t in range(CFG5_VECTORS)]
+        thr5 = synthetic.initial_threshold(g5[0], w5.density)
+        c5 = binding.default_config(n_g=w5.n_g, block_size=w5.block_size, n_parts=w5.n_parts,
+                                    density=w5.density, threshold0=thr5)
+        x5 = binding.ExDyna(c5, dev)
+        for t in range(CFG5_WARMUP):
+            x5.step(g5[t % CFG5_VECTORS])
+        cfg5, _ = timed_window(x5, lambda c, g: c.step(g), lambda t: g5[t % CFG5_VECTORS], CFG5_WARMUP,
+                               CFG5_STEPS, w5.n_g, ALG_BYTES_PER_ELEM)
+        cfg5["config"] = {"workload": w5.name, "n_g": w5.n_g, "block_size": w5.block_size,
+                          "n_parts": w5.n_parts, "density": w5.density, "threshold0": thr5,
+                          "gradient_vectors_in_hbm": CFG5_VECTORS, "recycled": True}
+        cfg5["note"] = (f"{CFG5_WARMUP} untimed iterations, then {CFG5_STEPS} timed; with gamma = 0.01 this "
+                        "workload's threshold transient lasts about 160 iterations, so k' is still far "
+                        "above the capacity here; parity at this size is covered by the GPU tests")
+        x5.close()
+        del x5, g5
+        torch.cuda.empty_cache()
+
     out = {
         "metric": "gradient elements sparsified/sec",
-        "value": round(value, 3),
+        "value": head["value"],
         "unit": "G elem/s",
         "n_gpus": 1,
         "steps": K,
         "warmup": W,
-        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step": head["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -275,17 +382,18 @@ def main() -> int:
                    "gradient_vectors_in_hbm": n_vec, "recycled": recycled,
                    "cmp": ">=", "grad_dtype": args.grad_dtype, "eta_fused": eta if scaled else None,
                    "view": "worker rank 0: select + exchange" if args.worker_view else "whole step",
+                   "window": ("threshold transient: k' above the output capacity" if not settled
+                              else "threshold settled: k' within the output capacity"),
                    "parallelism": "1 GPU, P partitions as index ranges"},
-        "hbm_roofline_pct_per_step": round(100.0 * step_bytes / (elapsed / K) / (HBM_PEAK_GBS * 1e9), 2),
-        "step_alg_gb_per_s": round(step_bytes / (elapsed / K) / 1e9, 1),
-        "last_step": {"k_actual": st.k_actual, "k_emitted": st.k_emitted,
-                      "k_target": w.density * w.n_g, "traffic_ratio": round(st.traffic_ratio, 4),
-                      "delta_next": st.delta_next},
-        "kernels": kern,
-        "roofline": roofline,
+        "hbm_roofline_pct_per_step": head["hbm_roofline_pct_per_step"],
+        "step_alg_gb_per_s": head["step_alg_gb_per_s"],
+        "last_step": head["last_step"],
+        "kernels": head["kernels"],
+        "roofline": head["roofline"],
         "cpu_baseline": cpu,
+        "steady_state": steady,
+        "cfg5": cfg5,
     }
-    x.close()
     print(json.dumps(out), flush=True)
     return 0
 

@@ -86,5 +86,10 @@ def run_trajectory(x, o, grads, tag="", check_norm=False, every=1):
         if t % every == 0:
             ka, ke = compare_step(x, o, t, check_norm=check_norm, tag=tag)
             log(f"  [{tag}] t={t} k'={ka} emitted={ke} delta_next={float(o.threshold):.6g} ok")
+        else:
+            # between the fully compared steps: the scalars that drive the closed loop
+            s = x.get_stats()
+            assert (s.k_actual, s.k_emitted) == (o.k_actual, o.k_emitted), (tag, t)
+            assert np.float32(s.delta_next) == o.threshold, (tag, t)
         announced = x.get_partitions(1)
     torch.cuda.synchronize()

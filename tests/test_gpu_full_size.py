@@ -11,11 +11,17 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
+# Steps and the stride of the compared ones.  Workload 4 is followed through the peak of its
+# threshold transient (k' about 70 times k around iteration 25: the output overflows its
+# capacity, only the first tiles emit, most tiles only count), its end (around iteration 50)
+# and into the settled state; workload 5 far enough for the overflow and the count-only tiles;
+# workload 3 through its dense segments.  Steps that are not compared still have their
+# announced topology checked against the oracle's next Allocate.
 @pytest.mark.timeout(900)
-@pytest.mark.parametrize("index,steps", [(1, 20), (2, 12), (3, 6), (4, 4), (5, 2)])
-def test_full_size_configuration(index, steps):
+@pytest.mark.parametrize("index,steps,every", [(1, 20, 1), (2, 30, 3), (3, 21, 2), (4, 61, 10), (5, 7, 2)])
+def test_full_size_configuration(index, steps, every):
     w = synthetic.WORKLOADS[index]
-    log(f"case {w.name}: n_g={w.n_g} b={w.block_size} P={w.n_parts} d={w.density} steps={steps}")
+    log(f"case {w.name}: n_g={w.n_g} b={w.block_size} P={w.n_parts} d={w.density} steps={steps} every={every}")
     src = synthetic.GradientSource(w, DEV)
     g = src.grad(0)
     thr = synthetic.initial_threshold(g, w.density)
@@ -25,7 +31,31 @@ def test_full_size_configuration(index, steps):
         for t in range(steps):
             yield src.grad(t, out=g)
 
-    run_trajectory(x, o, grads(), tag=w.name)
+    run_trajectory(x, o, grads(), tag=w.name, every=every)
+    x.close()
+    del g, x
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("n_g,b,P,d,steps", [
+    (20_000_000, 16384, 8, 2e-5, 4),     # a window of output ranks spans more tiles than fit LDS: spread by segment
+    (80_000_000, 65536, 8, 4e-6, 4),     # ... and more segments than fit: every thread walks the levels itself
+])
+def test_sparse_selection_over_a_long_vector(n_g, b, P, d, steps):
+    """Hundreds to thousands of wave tiles per selected gradient."""
+    w = synthetic.WORKLOADS[5].scaled(n_g, b, P)
+    log(f"case sparse: n_g={n_g} b={b} P={P} d={d}")
+    src = synthetic.GradientSource(w, DEV)
+    g = src.grad(0)
+    thr = synthetic.initial_threshold(g, d)
+    x, o = make_pair(n_g, b, P, d, thr, gamma=0.05)
+
+    def grads():
+        for t in range(steps):
+            yield src.grad(t, out=g)
+
+    run_trajectory(x, o, grads(), tag=f"sparse-{n_g}")
     x.close()
     del g, x
     torch.cuda.empty_cache()
