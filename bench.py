@@ -40,8 +40,10 @@ CFG5_VECTORS, CFG5_WARMUP, CFG5_STEPS = 4, 5, 20   # the 1.5 G-gradient workload
 # from inside this program, so the figure is the one of the committed summary for the same
 # workload and kind of window, and `traffic_source` names it; None where nothing was measured.
 MEASURED_TRAFFIC = {
-    (4, "steady"): (int((542666.0 * 2.0 + 546328.1) * 1024),
-                    "profiles/k_stream_cfg4_hbm_traffic.txt (rocprofv3 --pmc, --warmup 60 window)"),
+    (4, "transient"): (int((543268.5 * 2.0 + 555879.1) * 1024),
+                       "profiles/k_stream_cfg4_hbm_traffic.txt (rocprofv3 --pmc, --warmup 5 --steps 20 window)"),
+    (4, "steady"): (int((543213.4 * 2.0 + 546324.5) * 1024),
+                    "profiles/k_stream_cfg4_hbm_traffic.txt (rocprofv3 --pmc, --warmup 60 --steps 10 window)"),
 }
 
 
