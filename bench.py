@@ -33,6 +33,7 @@ ALG_BYTES_PER_ELEM = 12.0      # read g (4) + read e (4) + write e' (4)
 ALG_BYTES_PER_PAIR = 8.0       # u32 index + fp32 value per selected gradient
 STEADY_FROM, STEADY_STEPS = 60, 40            # the second, settled window of the same context
 CFG5_VECTORS, CFG5_WARMUP, CFG5_STEPS = 4, 5, 20   # the 1.5 G-gradient workload riding along
+CFG5_BAND_LIMIT = 300                         # untimed search for the end of its threshold transient
 
 # HBM bytes per k_stream launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
 # summarised under profiles/ (each counter scaled by what it reads for a plain device copy of
@@ -292,6 +293,10 @@ def main() -> int:
                                "launches_timed": int(ms.shape[0])}
         return res, elapsed
 
+    def in_band(k_actual, c):
+        """Alg. 5 takes its fine step: 1/beta < k'/k <= beta."""
+        return 1.0 / c.beta < k_actual / (c.density * c.n_g) <= c.beta
+
     def add_traffic(res, index, settled):
         """Counter-measured HBM bytes of one k_stream launch, from the committed summary for this
         workload and kind of window (transient: k' still far above the capacity)."""
@@ -324,9 +329,12 @@ def main() -> int:
             return (g / eta).to(tdt) if scaled else g
         # the vectors of the first window are done with: they are overwritten with the gradients
         # of the iterations in between, and a few more buffers make room for the second window
+        band_at = None
         for t in range(W + K, STEADY_FROM):
             grads[t % n_vec] = fresh(t, grads[t % n_vec])
             gpu_step(x, grads[t % n_vec])
+            if band_at is None and in_band(x.get_stats().k_actual, cfg):
+                band_at = t
         n_vec2 = int(max(2, min(STEADY_STEPS, args.hbm_budget_gb // vec_gb)))
         while len(grads) < n_vec2:
             grads.append(torch.empty_like(grads[0]))
@@ -335,6 +343,8 @@ def main() -> int:
         steady, _ = timed_window(x, gpu_step, lambda t: grads[t % n_vec2], STEADY_FROM, STEADY_STEPS, w.n_g,
                                  alg_bytes_per_elem)
         add_traffic(steady, args.config, steady["last_step"]["k_actual"] <= x.capacity)
+        steady["first_iteration_in_band"] = band_at
+        steady["band_searched"] = [W + K, STEADY_FROM - 1]
         steady["note"] = (f"same context and trajectory carried on untimed to iteration {STEADY_FROM}, "
                           f"then {STEADY_STEPS} timed steps; gradient vectors "
                           f"{'recycled' if n_vec2 < STEADY_STEPS or recycled else 'fresh'}")
@@ -360,8 +370,17 @@ def main() -> int:
                           "n_parts": w5.n_parts, "density": w5.density, "threshold0": thr5,
                           "gradient_vectors_in_hbm": CFG5_VECTORS, "recycled": True}
         cfg5["note"] = (f"{CFG5_WARMUP} untimed iterations, then {CFG5_STEPS} timed; with gamma = 0.01 this "
-                        "workload's threshold transient lasts about 160 iterations, so k' is still far "
-                        "above the capacity here; parity at this size is covered by the GPU tests")
+                        "workload's threshold transient outlasts the window (first_iteration_in_band, found by "
+                        "carrying the same context on untimed over the recycled vectors), so k' is still "
+                        "far above the capacity here; parity at this size is covered by the GPU tests")
+        band5 = None
+        for t in range(CFG5_WARMUP + CFG5_STEPS, CFG5_BAND_LIMIT):      # untimed: how long the transient lasts
+            x5.step(g5[t % CFG5_VECTORS])
+            if in_band(x5.get_stats().k_actual, c5):
+                band5 = t
+                break
+        cfg5["first_iteration_in_band"] = band5
+        cfg5["band_searched"] = [CFG5_WARMUP + CFG5_STEPS, CFG5_BAND_LIMIT - 1]
         x5.close()
         del x5, g5
         torch.cuda.empty_cache()

@@ -371,17 +371,17 @@ __device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 // A pair's output position is the number of selected gradients in front of it (partitions are
 // contiguous and ascending, Sec. 4.1, so the per-partition lists in partition order are one
 // ascending list).  Every placement workgroup first builds the same small table in LDS: the
-// exclusive prefix of the segment counters, one entry per group of 16 segments.  With it
+// exclusive prefix of the segment counters, one entry per group of 1, 4 or 16 segments (at
+// most 4096 entries).  With it
 //   - some workgroups work by TILE: four consecutive wave tiles per thread.  The thread learns
 //     its tiles' ranks, writes their slot table entries for the next iteration, and puts back
 //     what the streaming pass zeroed although it lies beyond the capacity (rare);
-//   - the others work by output RANK: windows of 1024 output positions, one per thread.  The
-//     thread finds the tile that holds its rank (group table, then the group's 16 segment
-//     counters, then the segment's tile counts) and copies that one pair from the tile's
-//     staging slots.  However the selected gradients are spread over the vector -- a sparse
-//     steady state, or a threshold transient that packs the whole output into the first few
-//     per cent of the tiles -- every thread moves one pair per window, and only ranks below
-//     min(k', capacity) cost anything.
+//   - the others work by output RANK: windows of 1024 to 4096 consecutive output positions,
+//     one to four per thread.  The thread finds the tile that holds its rank and copies that
+//     one pair from the tile's staging slots.  However the selected gradients are spread over
+//     the vector -- a sparse steady state, or a threshold transient that packs the whole
+//     output into the first few per cent of the tiles -- every thread moves the same number
+//     of pairs, and only ranks below min(k', capacity) cost anything.
 // A flagged tile (not staged) inside the capacity is re-read from the residual by the wave
 // that holds the rank of its first pair.
 
@@ -544,9 +544,10 @@ __device__ void place_tiles(const FinishArgs &A, PlaceShared &S, uint64_t cap, u
         // selected now (more while the total is growing) in the extra part of the pool, at an
         // offset that is the running sum of those sizes (taken from the rank, rounded down to
         // 16 pairs = 128 bytes so that two tiles never share a cache line), for as long as
-        // the extra part lasts: it covers at least one and a half output capacities.  A tile ranked beyond that only counts; a tile whose pairs would
-        // still end within the capacity if all ranks grew as the total just did (and an
-        // eighth more) may zero what it stages.
+        // the extra part lasts: it covers at least one and a half output capacities.  A tile
+        // ranked beyond that only counts; a tile whose pairs would still end within the
+        // capacity if all ranks grew as the total just did (and an eighth more) may zero what
+        // it stages.
         const uint64_t ex = A.pool_extra;  // multiple of 16
 #pragma unroll
         for (uint32_t k = 0; k < kTilesPerThr; ++k) {

@@ -6,7 +6,8 @@ paper_2402_13781_amd.synthetic and prints one CSV line per iteration:
 the actual density k'/n_g against the target d (Sec. 5.2's density plots), the
 density error of Eq. 6, the traffic ratio f(t) of Eq. 5, the all-gather padding
 C_t of Eq. 4, the threshold next to the error norm of Eq. 1 (the pair Sec. 5.3
-compares), and the number of boundary moves Alg. 3 made.  Two
+compares), and the number of boundary moves Alg. 3 made.  A last line on stderr says at
+which iteration k'/k first entered Alg. 5's band (1/beta, beta] and when it was last outside.  Two
 switches turn the paper's ablations on:
 
   --static-partitions   blk_move = 0: coarse-grained, never rebalanced (Sec. 4.1)
@@ -63,6 +64,17 @@ def run_trace(workload, steps, device="cuda:0", static_partitions=False, fixed_t
     return rows
 
 
+def band_entry(rows, k, beta):
+    """Alg. 5 takes its fine step while 1/beta < k'/k <= beta.  Returns (first iteration inside
+    that band, last iteration outside it), either None if there is none: how long the closed loop
+    of Sec. 4.4 needs from the caller's first threshold to the target density, and whether it
+    stays there."""
+    inside = [1.0 / beta < r["k_actual"] / k <= beta for r in rows]
+    first = next((r["t"] for r, ok in zip(rows, inside) if ok), None)
+    last_out = next((r["t"] for r, ok in zip(reversed(rows), reversed(inside)) if not ok), None)
+    return first, last_out
+
+
 def main(argv=None) -> int:
     from . import synthetic
 
@@ -80,8 +92,13 @@ def main(argv=None) -> int:
     w = synthetic.WORKLOADS[a.config]
     if a.n_g or a.block_size or a.n_parts:
         w = w.scaled(a.n_g or w.n_g, a.block_size or None, a.n_parts or None)
-    run_trace(w, a.steps or w.iters, static_partitions=a.static_partitions,
-              fixed_threshold=a.fixed_threshold, gamma=a.gamma, blk_move=a.blk_move, out=sys.stdout)
+    rows = run_trace(w, a.steps or w.iters, static_partitions=a.static_partitions,
+                     fixed_threshold=a.fixed_threshold, gamma=a.gamma, blk_move=a.blk_move, out=sys.stdout)
+    from . import binding
+    beta = binding.default_config().beta
+    first, last_out = band_entry(rows, w.density * w.n_g, beta)
+    print(f"# k'/k first within (1/{beta:g}, {beta:g}] at iteration {first}; last iteration outside: "
+          f"{last_out} of {len(rows)}", file=sys.stderr)
     return 0
 
 
