@@ -10,8 +10,13 @@
 //              slots, writes the residual -- with those entries already zeroed
 //              (Alg. 1, zeroing and residual carry) when the tile's output rank
 //              of the iteration before says they will fit the output -- stores
-//              the tile's count word, and adds the count to a per-block and a
-//              per-segment counter.  A tile whose rank lay far beyond the output
+//              the tile's count word, and adds the count to its segment's
+//              counter: a segment is the four tiles of one workgroup (longer
+//              vectors: 16 to 64 tiles), because adds to one address serialise
+//              and a wavefront does not retire before its add has returned.
+//              Blocks that are not whole segments are counted as well; the
+//              counts of those that are follow from the segment counters in
+//              k_finish.  A tile whose rank lay far beyond the output
 //              capacity, or with more selected gradients than slots, is only
 //              counted and flagged.  Pure streaming: 8 B read + 4 B written per
 //              gradient, no workgroup barrier, no fence.
@@ -56,7 +61,9 @@
 //
 // What the measurements on this part ruled out: a device-scope fence or a
 // "last workgroup done" ticket per workgroup (about 150 ns each, serialised),
-// hot counters shared by many workgroups (same cost per same-address atomic),
+// counters shared by many workgroups (16 tiles per counter cost the streaming
+// pass 4 % when every tile adds, 64 tiles 15 %; 4 tiles under 1 %), summing a
+// workgroup's counts in LDS first (the barrier costs more than the adds),
 // a workgroup barrier in the streaming pass (6 % slower), gathering the
 // selected values from the residual afterwards (random 4-byte reads over
 // gigabytes), and dealing the placement out by tile (a threshold transient
@@ -67,6 +74,7 @@
 // wavefront scans use the vector ALU's lane-shift path.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -91,6 +99,7 @@ struct Layout {
     size_t blk_stride, seg_stride;  // entries between the two parities' counter arrays (padded to 64)
     size_t tile_pad;                // entries of tile_cnt (n_tiles rounded up to 1024, the rest stays 0)
     uint32_t one_counter; // blocks coincide with segments: one counter array serves both
+    uint32_t segs_per_blk; // blocks are this many whole segments (0: they are not; the streaming pass counts blocks too)
     size_t slot_tab;
     uint32_t pool_extra; // staging pairs handed out in proportion to the last counts
     uint32_t slots;      // staging slots every wave tile always has
@@ -193,25 +202,28 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap, bool with
     const size_t P = c->n_parts;
     L.n_tiles  = (c->n_g + kTile - 1) / kTile;
     L.slots    = staging_slots(c->density);
-    L.seg_shift = segment_shift(c->density);
-    while (!groups_fit(L.n_tiles, L.seg_shift)) ++L.seg_shift;  // 64 tiles per segment always fit
-    // When a block is a power-of-two number of tiles that is no coarser than that
-    // segment size (and there are not too many blocks to sum over), let segments
-    // be the blocks: the streaming pass then adds to one counter instead of two.
-    L.one_counter = 0;
-    for (uint32_t sh = 2; sh <= L.seg_shift; ++sh)
-        if (c->block_size == (kTile << sh) && (sh == L.seg_shift || n_b <= 32768) &&
-            groups_fit(L.n_tiles, sh)) {
-            L.seg_shift = sh;
-            L.one_counter = 1;
-        }
+    // One counter per workgroup of the streaming pass (four tiles) while the finishing kernel
+    // can still read them all (every placement workgroup does); coarser ones for longer vectors.
+    if ((L.n_tiles + 3) / 4 <= kMaxFineSegs) {
+        L.seg_shift = 2;
+    } else {
+        L.seg_shift = segment_shift(c->density);
+        while (!groups_fit(L.n_tiles, L.seg_shift)) ++L.seg_shift;  // 64 tiles per segment always fit
+    }
+    // Blocks that are whole segments are not counted by the streaming pass: the control
+    // workgroup adds their segments up.  A block of exactly one segment shares its counter.
+    {
+        const uint64_t seg_elems = (uint64_t)kTile << L.seg_shift;
+        L.segs_per_blk = c->block_size % seg_elems == 0 ? (uint32_t)(c->block_size / seg_elems) : 0u;
+        L.one_counter  = L.segs_per_blk == 1;
+    }
     L.n_segs   = (L.n_tiles + (1u << L.seg_shift) - 1) >> L.seg_shift;
     // few entries make the table quick to build; every level below it costs one more lookup
     L.grp_shift = L.n_segs > 4096 ? 4 : L.n_segs > 1024 ? 2 : 0;
     L.n_groups = (L.n_segs + (1u << L.grp_shift) - 1) >> L.grp_shift;
     // the placement reads counters 16 and 64 at a time: arrays are padded with zeros that nothing writes
     L.blk_stride = align_up(n_b, 64);
-    L.seg_stride = align_up(L.n_segs, 64);
+    L.seg_stride = align_up(std::max<size_t>(L.n_segs, (size_t)n_b * L.segs_per_blk), 64);  // whole blocks' worth
     L.tile_pad   = align_up(L.n_tiles, 1024);  // whole groups of segments (at most 16 x 64 tiles)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
@@ -332,7 +344,7 @@ void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
     A.blk_cnt = blk_cnt_of(c, c->t);
     A.seg_cnt = c->lay.one_counter ? blk_cnt_of(c, c->t) : seg_cnt_of(c, c->t);
     A.seg_shift = c->lay.seg_shift;
-    A.one_counter = c->lay.one_counter;
+    A.seg_only = c->lay.segs_per_blk != 0;
     A.err_slots = err_slots_of(c, c->t);
     A.n_g = (uint32_t)c->cfg.n_g;
     A.n_tiles = (uint32_t)c->lay.n_tiles;
@@ -381,6 +393,7 @@ FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
     A.err_slots_next = err_slots_of(c, t + 1);
     A.n_tiles = (uint32_t)c->lay.n_tiles;
     A.n_segs = (uint32_t)c->lay.n_segs;
+    A.segs_per_blk = c->lay.one_counter ? 0u : c->lay.segs_per_blk;
     A.n_groups = (uint32_t)c->lay.n_groups;
     A.search_step = 0;  // largest power of two <= n_groups - 1: the first stride of the offset search
     for (uint32_t p2 = 1; p2 < A.n_groups; p2 <<= 1) A.search_step = p2;

@@ -15,7 +15,7 @@ struct FinishArgs {
     const uint2    *slot_tab;        // this iteration's {offset in the extra part, slots | bits} per tile
     uint2          *slot_tab_next;   // the next iteration's, written here
     const uint32_t *tile_cnt;
-    const uint32_t *blk_cnt;         // this iteration's per-block counters (complete)
+    uint32_t       *blk_cnt;         // this iteration's per-block counts: complete, or written here from the segment counters
     const uint32_t *seg_cnt;         // this iteration's per-segment counters (complete)
     uint32_t       *blk_cnt_next;    // the other parity's counters, cleared here
     uint32_t       *seg_cnt_next;
@@ -38,6 +38,7 @@ struct FinishArgs {
     uint32_t        sel_rank;        // worker view: the worker whose partition was compared; else kAllParts
     uint32_t        block_size;
     uint32_t        n_parts;
+    uint32_t        segs_per_blk;    // > 1: a block's count is the sum of this many segment counters, written to blk_cnt here
 };
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
@@ -78,11 +79,64 @@ enum : uint32_t {
     kCtrlUpdate = 2   // worker view, after the exchange: Alg. 5, Alg. 3, statistics from the gathered counts
 };
 
-// k_{p,t} from the per-block counters (Sec. 4.2: the workload of a partition).
-// Each wave takes a contiguous run of the counters, 64 at a time; its first
+// Selected gradients of blocks i0 + 64 q + lane, q < N (index clamped into [.., end) so that
+// every load can be issued at once).  The streaming pass counts per block only when blocks are
+// not whole segments; otherwise a block's count is the sum of its segments' counters: one load
+// of two or four counters when there are that many (the usual cases), all of a trip's loads
+// in flight before the first sum waits for one.
+template <uint32_t N>
+__device__ __forceinline__ void block_counts(const FinishArgs &A, uint32_t i0, uint32_t end, uint32_t lane,
+                                             uint32_t (&out)[N])
+{
+    const uint32_t m = A.segs_per_blk;  // workgroup-uniform
+    if (m == 0u) {
+#pragma unroll
+        for (uint32_t q = 0; q < N; ++q) {
+            const uint32_t i = i0 + q * 64u + lane;
+            out[q] = A.blk_cnt[i < end ? i : 0u];
+        }
+    } else if (m == 4u) {
+        uint4 raw[N];
+#pragma unroll
+        for (uint32_t q = 0; q < N; ++q) {
+            const uint32_t i = i0 + q * 64u + lane;
+            raw[q] = reinterpret_cast<const uint4 *>(A.seg_cnt)[i < end ? i : 0u];
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < N; ++q) out[q] = (raw[q].x + raw[q].y) + (raw[q].z + raw[q].w);
+    } else if (m == 2u) {
+        uint2 raw[N];
+#pragma unroll
+        for (uint32_t q = 0; q < N; ++q) {
+            const uint32_t i = i0 + q * 64u + lane;
+            raw[q] = reinterpret_cast<const uint2 *>(A.seg_cnt)[i < end ? i : 0u];
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < N; ++q) out[q] = raw[q].x + raw[q].y;
+    } else {
+        // any other number of segments per block: the blocks side by side, segment by segment
+        // (the counter arrays are padded with zeros to whole blocks)
+#pragma unroll
+        for (uint32_t q = 0; q < N; ++q) out[q] = 0u;
+        for (uint32_t j = 0; j < m; ++j) {
+            uint32_t raw[N];
+#pragma unroll
+            for (uint32_t q = 0; q < N; ++q) {
+                const uint32_t i = i0 + q * 64u + lane;
+                raw[q] = A.seg_cnt[(size_t)(i < end ? i : 0u) * m + j];
+            }
+#pragma unroll
+            for (uint32_t q = 0; q < N; ++q) out[q] += raw[q];
+        }
+    }
+}
+
+// k_{p,t} from the per-block counts (Sec. 4.2: the workload of a partition).
+// Each wave takes a contiguous run of the blocks, 64 at a time; its first
 // slices are requested before anything waits on memory.  Also clears the other
-// parity's block counters and norm partials for the next iteration.
-__device__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S)
+// parity's block counters and norm partials for the next iteration (or, when the
+// block counts are sums of segment counters, stores them for the getters).
+__device__ __forceinline__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S)
 {
     constexpr uint32_t kWaves = kFinishWG / 64;
     const uint32_t tid  = threadIdx.x;
@@ -94,14 +148,9 @@ __device__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlS
     const uint32_t per_wave = (n_b + kWaves - 1) / kWaves;
     const uint32_t beg      = wave * per_wave < n_b ? wave * per_wave : n_b;
     const uint32_t end      = beg + per_wave < n_b ? beg + per_wave : n_b;
-    constexpr uint32_t kAhead = 12;  // 768 counters per wave and trip: one trip up to 12288 blocks
+    constexpr uint32_t kAhead = 12;  // 768 blocks per wave and trip: one trip up to 12288 blocks
     uint32_t cbuf[kAhead];
-    // (index clamped instead of a guarded load: all loads of a trip are in flight together)
-#pragma unroll
-    for (uint32_t q = 0; q < kAhead; ++q) {
-        const uint32_t i = beg + q * 64u + lane;
-        cbuf[q] = A.blk_cnt[i < end ? i : 0u];
-    }
+    block_counts(A, beg, end, lane, cbuf);
     if (tid < P) {
         S.cnt[tid]   = 0u;
         S.lpos[tid]  = A.cur_pos[tid];
@@ -125,19 +174,18 @@ __device__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlS
         uint32_t next_start = pcur + 1 < P ? (uint32_t)S.lpos[pcur + 1] : 0xFFFFFFFFu;
         uint32_t acc        = 0;  // this lane's share of partition pcur so far
         for (uint32_t i0 = beg; i0 < end; i0 += kAhead * 64u) {
-            if (i0 != beg) {
-#pragma unroll
-                for (uint32_t q = 0; q < kAhead; ++q) {
-                    const uint32_t i = i0 + q * 64u + lane;
-                    cbuf[q] = A.blk_cnt[i < end ? i : 0u];
-                }
-            }
+            if (i0 != beg) block_counts(A, i0, end, lane, cbuf);
 #pragma unroll
             for (uint32_t q = 0; q < kAhead; ++q) {
                 const uint32_t s0 = i0 + q * 64u;  // first block of this slice
                 const uint32_t i  = s0 + lane;
-                if (i < end) A.blk_cnt_next[i] = 0u;  // clean block counters for the next iteration
                 uint32_t c = i < end ? cbuf[q] : 0u;
+                if (i < end) {
+                    if (A.segs_per_blk)
+                        A.blk_cnt[i] = c;       // the block's count, for the getters
+                    else
+                        A.blk_cnt_next[i] = 0u;  // clean block counters for the next iteration
+                }
                 while (next_start < s0 + 64u && next_start < end) {  // the slice reaches the next partition
                     acc += i < next_start ? c : 0u;
                     c = i < next_start ? 0u : c;
@@ -170,7 +218,7 @@ __device__ __forceinline__ void ctrl_sync()
 }
 
 template <bool ONE_WAVE>
-__device__ void control_decide_impl(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S, uint32_t mode,
+__device__ __forceinline__ void control_decide_impl(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S, uint32_t mode,
                                     float delta_in, uint64_t t_in)
 {
     constexpr uint32_t kWaves = ONE_WAVE ? 1u : kFinishWG / 64;
@@ -346,7 +394,7 @@ __device__ void control_decide_impl(const FinishArgs &A, const CtrlParams &prm, 
     }
 }
 
-__device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S, uint32_t mode,
+__device__ __forceinline__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S, uint32_t mode,
                                float delta, uint64_t t_done)
 {
     if (prm.n_parts <= 64u) {  // workgroup-uniform
@@ -356,7 +404,7 @@ __device__ void control_decide(const FinishArgs &A, const CtrlParams &prm, CtrlS
     }
 }
 
-__device__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
+__device__ __forceinline__ void finish_control(const FinishArgs &A, const CtrlParams &prm)
 {
     __shared__ CtrlShared S;
     // requested before the counting starts (volatile: issued here, waited for where used)
@@ -410,6 +458,45 @@ __device__ __forceinline__ uint32_t waves_before(const uint32_t *wtot, uint32_t 
     return sum;
 }
 
+// Sums of the groups' segment counters into S.grp: thread tid takes counters 4 (tid + 1024 q)
+// .. + 3 for q < N, which covers all n_vec <= 1024 N loads of four.
+template <uint32_t N>
+__device__ __forceinline__ void group_sums(const FinishArgs &A, PlaceShared &S, uint32_t n_vec)
+{
+    const uint4 *__restrict__ src = reinterpret_cast<const uint4 *>(A.seg_cnt);
+    const uint32_t tid  = threadIdx.x;
+    const uint32_t lane = tid & 63u;
+    const uint32_t gs   = A.grp_shift;
+    uint4 c[N];
+#pragma unroll
+    for (uint32_t q = 0; q < N; ++q) {  // index clamped, not a guarded load: all in flight together
+        const uint32_t v = tid + q * kFinishWG;
+        c[q] = src[v < n_vec ? v : 0u];
+    }
+#pragma unroll
+    for (uint32_t q = 0; q < N; ++q) {
+        const uint32_t v = tid + q * kFinishWG;
+        if (v >= n_vec) c[q] = make_uint4(0u, 0u, 0u, 0u);
+        if ((v & ~63u) < n_vec) {  // wave-uniform: this wave's slice holds counters
+            if (gs == 0u) {  // every counter is a group
+                if (4u * v + 0u < A.n_groups) S.grp[4u * v + 0u] = c[q].x;
+                if (4u * v + 1u < A.n_groups) S.grp[4u * v + 1u] = c[q].y;
+                if (4u * v + 2u < A.n_groups) S.grp[4u * v + 2u] = c[q].z;
+                if (4u * v + 3u < A.n_groups) S.grp[4u * v + 3u] = c[q].w;
+            } else {
+                uint32_t x = (c[q].x + c[q].y) + (c[q].z + c[q].w);
+                if (gs == 4u) {  // four lanes = one group
+                    x += dpp_move<0xB1, 0xF>(0u, x);  // quad lanes 1 0 3 2
+                    x += dpp_move<0x4E, 0xF>(0u, x);  // quad lanes 2 3 0 1
+                    if ((lane & 3u) == 0u && (v >> 2) < A.n_groups) S.grp[v >> 2] = x;
+                } else if (v < A.n_groups) {
+                    S.grp[v] = x;
+                }
+            }
+        }
+    }
+}
+
 // Builds S.grp (exclusive prefix of the segment counters, one entry per group of 1, 4 or 16
 // segments: A.grp_shift = 0, 2, 4) and S.total.
 __device__ __forceinline__ void place_table(const FinishArgs &A, PlaceShared &S)
@@ -418,41 +505,15 @@ __device__ __forceinline__ void place_table(const FinishArgs &A, PlaceShared &S)
     const uint32_t tid  = threadIdx.x;
     const uint32_t lane = tid & 63u;
     const uint32_t wave = tid >> 6;
-    // group sums: a lane takes four counters per load; the counter arrays are padded with
-    // zeros to a multiple of 64
+    // group sums: a lane takes four counters per load (the counter arrays are padded with
+    // zeros to a multiple of 64), and a thread's loads are all requested before the first is
+    // used: up to 8 (32768 counters) or up to 16 (65536)
     {
-        const uint4 *__restrict__ src = reinterpret_cast<const uint4 *>(A.seg_cnt);
         const uint32_t n_vec = (A.n_segs + 3u) >> 2;
-        const uint32_t gs    = A.grp_shift;
-        constexpr uint32_t kAhead = 4;
-        for (uint32_t v0 = wave * 64u + lane; v0 < ((n_vec + 63u) & ~63u); v0 += kAhead * kFinishWG) {
-            uint4 c[kAhead];
-#pragma unroll
-            for (uint32_t q = 0; q < kAhead; ++q) {  // index clamped, not a guarded load: all in flight together
-                const uint32_t v = v0 + q * kFinishWG;
-                c[q] = src[v < n_vec ? v : 0u];
-                if (v >= n_vec) c[q] = make_uint4(0u, 0u, 0u, 0u);
-            }
-#pragma unroll
-            for (uint32_t q = 0; q < kAhead; ++q) {
-                const uint32_t v = v0 + q * kFinishWG;
-                if (gs == 0u) {  // every counter is a group
-                    if (4u * v + 0u < A.n_groups) S.grp[4u * v + 0u] = c[q].x;
-                    if (4u * v + 1u < A.n_groups) S.grp[4u * v + 1u] = c[q].y;
-                    if (4u * v + 2u < A.n_groups) S.grp[4u * v + 2u] = c[q].z;
-                    if (4u * v + 3u < A.n_groups) S.grp[4u * v + 3u] = c[q].w;
-                } else {
-                    uint32_t x = (c[q].x + c[q].y) + (c[q].z + c[q].w);
-                    if (gs == 4u) {  // four lanes = one group
-                        x += dpp_move<0xB1, 0xF>(0u, x);  // quad lanes 1 0 3 2
-                        x += dpp_move<0x4E, 0xF>(0u, x);  // quad lanes 2 3 0 1
-                        if ((lane & 3u) == 0u && (v >> 2) < A.n_groups) S.grp[v >> 2] = x;
-                    } else if (v < A.n_groups) {
-                        S.grp[v] = x;
-                    }
-                }
-            }
-        }
+        if (n_vec <= 8u * kFinishWG)
+            group_sums<8>(A, S, n_vec);
+        else
+            group_sums<16>(A, S, n_vec);
     }
     __syncthreads();
     // exclusive scan of the group sums, a run of consecutive groups per thread
@@ -492,7 +553,7 @@ __device__ __forceinline__ const uint2 *staged_pairs(const FinishArgs &A, uint32
 
 // ---- by tile: ranks, the next slot table, clean segment counters, put-backs ----
 template <bool NORM>
-__device__ void place_tiles(const FinishArgs &A, PlaceShared &S, uint64_t cap, uint32_t wg, uint4 w4,
+__device__ __forceinline__ void place_tiles(const FinishArgs &A, PlaceShared &S, uint64_t cap, uint32_t wg, uint4 w4,
                             uint64_t prev, double &add)
 {
     // how fast the selected count grows: this pass's total over the last pass's (prev), 1 .. 4
@@ -736,7 +797,7 @@ __device__ __forceinline__ uint32_t find_tile(const FinishArgs &A, uint32_t seg,
 // that every thread walks down all levels on its own.  Then the pairs are copied, all loads
 // of a thread in flight together. ----
 template <bool NORM, int CMP>
-__device__ void place_ranks(const FinishArgs &A, PlaceShared &S, uint32_t n_g, uint32_t n_out,
+__device__ __forceinline__ void place_ranks(const FinishArgs &A, PlaceShared &S, uint32_t n_g, uint32_t n_out,
                             uint32_t wg, uint32_t n_wg, float delta, double &sub, uint32_t &sub_nf)
 {
     constexpr uint32_t kMaxPer = 4;  // output ranks per thread and window
@@ -901,7 +962,7 @@ __device__ void place_ranks(const FinishArgs &A, PlaceShared &S, uint32_t n_g, u
 }
 
 template <bool NORM, int CMP>
-__device__ void finish_place(const FinishArgs &A, uint32_t n_g, uint64_t cap)
+__device__ __forceinline__ void finish_place(const FinishArgs &A, uint32_t n_g, uint64_t cap)
 {
     constexpr uint32_t kWaves = kFinishWG / 64;
     __shared__ PlaceShared S;

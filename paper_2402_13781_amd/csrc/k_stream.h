@@ -27,7 +27,9 @@ struct StreamArgs {
     uint32_t        n_g, n_tiles, gran_per_blk, parity;
     uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
     uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
-    uint32_t        one_counter;  // a block is exactly one segment: blk_cnt doubles as seg_cnt
+    uint32_t        seg_only;   // blocks are whole segments: only the segment counters are added to
+                                // (one segment per block: blk_cnt doubles as seg_cnt; several: the
+                                // finishing kernel sums them into blk_cnt)
     // worker view (Alg. 1 (Sparsify)): compare only inside the partition that worker sel_rank
     // owns at this iteration (Alg. 3 (cyclic allocation), from the device's own iteration
     // counter); kAllParts = everywhere
@@ -241,11 +243,11 @@ k_stream(StreamArgs A)
                                   (uint32_t)__popc(nib[u]));
                 if (lane == 0) atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
             } else if (lane == 0) {
-                // One counter per block / segment keeps same-address atomics rare (they
-                // serialise at roughly 150 ns each across the dies).
-                if (A.one_counter) {
-                    // a block is exactly one segment: the same counter serves both
-                    atomicAdd(&A.blk_cnt[tile >> A.seg_shift], total);
+                // Adds to one address serialise at the memory side, and a wavefront does not
+                // retire before its add has returned: up to four tiles per counter (the tiles
+                // of one workgroup) cost next to nothing, sixteen cost 4 % of the pass.
+                if (A.seg_only) {
+                    atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
                 } else {
                     // per-block counters; consecutive granules of one block are added together
                     uint32_t blk = A.gpb_shift < 32u ? gran0 >> A.gpb_shift : gran0 / A.gran_per_blk;
