@@ -167,12 +167,15 @@ int validate_config(const exdyna_config *c, uint64_t *n_b_out, uint64_t *cap_out
 }
 
 // Staging slots every wave tile has: room for four times the expected number of
-// selected gradients in 1024 (density d), a power of two between 16 and 64
-// (16 pairs = one 128-byte line).
+// selected gradients in 1024 (density d), 32 or 64 (16 pairs = one 128-byte line).
+// Not fewer than 32: a tile beyond its fixed slots depends on the slots the finishing
+// kernel gave it from its last count, four per pair, and with 16 fixed slots the tiles
+// that had 3 to 7 pairs and now have 17 or more (a few per thousand while the threshold is
+// still catching up) would be left without room and have to be read again.
 uint32_t staging_slots(double density)
 {
     const double want = 4.0 * density * (double)kTile + 4.0;
-    uint32_t s = 16;
+    uint32_t s = 32;
     while (s < 64 && (double)s < want) s <<= 1;
     return s;
 }

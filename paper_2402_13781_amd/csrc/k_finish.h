@@ -558,14 +558,17 @@ __device__ __forceinline__ void place_tiles(const FinishArgs &A, PlaceShared &S,
 {
     // how fast the selected count grows: this pass's total over the last pass's (prev), 1 .. 4
     uint64_t zero_below = cap;
-    uint32_t slots_per8 = 20;  // extra staging slots per selected gradient, in eighths
+    uint32_t slots_per8 = 32;  // extra staging slots per selected gradient, in eighths
     {
         const double   now  = (double)S.total;
         double growth = prev ? now / (double)prev : 1.0;
+        // Four slots per pair: a tile with 6 to 16 pairs now (its fixed slots hold 16) then
+        // has room for 32 or more, far outside the spread of its next count.  Two and a half
+        // while the total shrinks: the same pool then reaches tiles ranked further out, which
+        // is where the capacity's edge moves to.
+        slots_per8 = growth < 0.9 ? 20u : 32u;
         growth = growth < 1.0 ? 1.0 : growth > 4.0 ? 4.0 : growth;
         zero_below = (uint64_t)((double)cap / (growth * 1.125));
-        slots_per8 = (uint32_t)(16.0 * growth * 1.25);  // in eighths: 2.5 slots per pair when nothing grows
-        slots_per8 = slots_per8 > 32u ? 32u : slots_per8;
     }
     const uint32_t tid  = threadIdx.x;
     const uint32_t lane = tid & 63u;
@@ -601,8 +604,8 @@ __device__ __forceinline__ void place_tiles(const FinishArgs &A, PlaceShared &S,
             }
         }
         // Staging slots for the next iteration follow this iteration's ranks and counts.
-        // Beyond its fixed slots a tile gets two and a half to four slots per gradient it
-        // selected now (more while the total is growing) in the extra part of the pool, at an
+        // Beyond its fixed slots a tile gets four slots per gradient it selected now (two and
+        // a half while the total is shrinking) in the extra part of the pool, at an
         // offset that is the running sum of those sizes (taken from the rank, rounded down to
         // 16 pairs = 128 bytes so that two tiles never share a cache line), for as long as
         // the extra part lasts: it covers at least one and a half output capacities.  A tile
