@@ -15,6 +15,7 @@ constexpr uint32_t kTileGran    = 4;     // granules per wave tile
 constexpr uint32_t kTile        = kGran * kTileGran;  // 1024 gradients per wavefront
 constexpr uint32_t kStreamWG    = 256;   // k_stream: 4 wavefronts = 4096 contiguous gradients
 constexpr uint32_t kWavesPerWG  = kStreamWG / 64;
+constexpr uint32_t kStageBuf    = 256;   // pairs a wavefront of k_stream lines up in LDS before it stores them
 constexpr uint32_t kSegShift    = 4;     // longer vectors: 16 wave tiles per segment counter, unless the density asks for fewer
 constexpr uint32_t kMaxSegShift = 6;     // ... or the vector is so long (> 2 G gradients) that the group table asks for more
 constexpr uint32_t kMaxFineSegs = 65536; // up to this many segments, a segment is the four tiles of one streaming workgroup

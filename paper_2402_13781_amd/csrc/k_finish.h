@@ -936,11 +936,13 @@ __device__ __forceinline__ void place_ranks(const FinishArgs &A, PlaceShared &S,
             for (uint32_t q = 0; q < kMaxPer; ++q) {
                 if (src[q]) {
                     const uint32_t r = (uint32_t)w0 + q * kFinishWG + tid;
-                    A.out_idx[r] = pr[q].x;
-                    A.out_val[r] = __uint_as_float(pr[q].y);
+                    // streamed out: nothing in this kernel reads them again, and what is not left
+                    // dirty in L2 does not have to be written back when the kernel ends
+                    __builtin_nontemporal_store(pr[q].x, &A.out_idx[r]);
+                    __builtin_nontemporal_store(__uint_as_float(pr[q].y), &A.out_val[r]);
                     if (word[q] & kKept) {
                         // staged but left in the residual: zeroed now that it is sent
-                        A.e[pr[q].x] = 0.0f;
+                        __builtin_nontemporal_store(0.0f, &A.e[pr[q].x]);
                         if (NORM) left_selected(__uint_as_float(pr[q].y), sub, sub_nf);
                     }
                 }

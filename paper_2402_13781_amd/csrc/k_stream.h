@@ -76,6 +76,28 @@ __device__ __forceinline__ void left_selected(float v, double &sum, uint32_t &no
         sum += (double)(v * v);
 }
 
+// A tile's selected gradients as (index, value bits) pairs, in index order, to dst[rank in
+// the tile]: every lane writes its own (cu: selected per granule; below: those in the granule
+// in front of this lane's).
+__device__ __forceinline__ void put_pairs(uint2 *dst, const f32x4 (&a)[kTileGran], const uint32_t (&nib)[kTileGran],
+                                          const uint32_t (&cu)[kTileGran], const uint32_t (&below)[kTileGran],
+                                          uint32_t gran0, uint32_t lane)
+{
+    uint32_t pre = 0;
+#pragma unroll
+    for (uint32_t u = 0; u < kTileGran; ++u) {
+        if (nib[u]) {
+            uint32_t       r  = pre + below[u];
+            const uint32_t i0 = ((gran0 + u) << 8) + lane * 4u;
+            if (nib[u] & 1u) dst[r++] = make_uint2(i0, __float_as_uint(a[u].x));
+            if (nib[u] & 2u) dst[r++] = make_uint2(i0 + 1u, __float_as_uint(a[u].y));
+            if (nib[u] & 4u) dst[r++] = make_uint2(i0 + 2u, __float_as_uint(a[u].z));
+            if (nib[u] & 8u) dst[r++] = make_uint2(i0 + 3u, __float_as_uint(a[u].w));
+        }
+        pre += cu[u];
+    }
+}
+
 // GEN: block sizes that are multiples of 32 but not of 256.  Block and partition
 // boundaries then fall inside granules (always between lanes: a lane's four
 // gradients share a 32-aligned group), so the comparison is masked per lane
@@ -199,19 +221,18 @@ k_stream(StreamArgs A)
                 }
             }
             if (slot) {
-                // staged: pairs in index order
-                uint32_t pre  = 0;
-#pragma unroll
-                for (uint32_t u = 0; u < kTileGran; ++u) {
-                    if (nib[u]) {
-                        uint32_t       r  = pre + below[u];
-                        const uint32_t i0 = ((gran0 + u) << 8) + lane * 4u;
-                        if (nib[u] & 1u) slot[r++] = make_uint2(i0, __float_as_uint(a[u].x));
-                        if (nib[u] & 2u) slot[r++] = make_uint2(i0 + 1u, __float_as_uint(a[u].y));
-                        if (nib[u] & 4u) slot[r++] = make_uint2(i0 + 2u, __float_as_uint(a[u].z));
-                        if (nib[u] & 8u) slot[r++] = make_uint2(i0 + 3u, __float_as_uint(a[u].w));
-                    }
-                    pre += cu[u];
+                // Staged: pairs in index order.  The lanes first put their pairs in rank order
+                // into the wavefront's own piece of LDS (no barrier: a wavefront's LDS accesses
+                // stay in program order), then lane j stores pair j: one store instruction per
+                // 64 pairs to consecutive addresses.  Sixteen instructions with a lane or two
+                // active each, one per gradient slot, cost the pass 2 % at one pair per tile.
+                __shared__ uint2 sbuf[kWavesPerWG][kStageBuf];
+                if (total <= kStageBuf) {  // wave-uniform
+                    put_pairs(sbuf[wave], a, nib, cu, below, gran0, lane);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+                    for (uint32_t j = lane; j < total; j += 64u) slot[j] = sbuf[wave][j];
+                } else {
+                    put_pairs(slot, a, nib, cu, below, gran0, lane);
                 }
             } else {
                 word |= kFlag;  // more than the slots hold (or no slots at all): counted only
