@@ -41,9 +41,9 @@ CFG5_BAND_LIMIT = 300                         # untimed search for the end of it
 # from inside this program, so the figure is the one of the committed summary for the same
 # workload and kind of window, and `traffic_source` names it; None where nothing was measured.
 MEASURED_TRAFFIC = {
-    (4, "transient"): (int((543268.5 * 2.0 + 555879.1) * 1024),
+    (4, "transient"): (int((543272.1 * 2.0 + 552501.6) * 1024),
                        "profiles/k_stream_cfg4_hbm_traffic.txt (rocprofv3 --pmc, --warmup 5 --steps 20 window)"),
-    (4, "steady"): (int((543213.4 * 2.0 + 546324.5) * 1024),
+    (4, "steady"): (int((543219.3 * 2.0 + 546323.1) * 1024),
                     "profiles/k_stream_cfg4_hbm_traffic.txt (rocprofv3 --pmc, --warmup 60 --steps 10 window)"),
 }
 
