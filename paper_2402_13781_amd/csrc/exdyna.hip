@@ -93,13 +93,13 @@
 namespace {
 
 struct Layout {
-    size_t state, parts, part_cnt, part_off, blk_cnt, seg_cnt, tile_cnt, err_slots, stage,
+    size_t state, parts, part_cnt, part_off, blk_cnt, blk_out, seg_cnt, tile_cnt, err_slots, stage,
         out_idx, out_val, total;
     size_t n_tiles, n_segs, n_groups, pool_pairs;
-    size_t blk_stride, seg_stride;  // entries between the two parities' counter arrays (padded to 64)
+    size_t blk_stride, seg_stride, out_stride;  // entries between the two parities' arrays (padded to 64)
     size_t tile_pad;                // entries of tile_cnt (n_tiles rounded up to 1024, the rest stays 0)
-    uint32_t one_counter; // blocks coincide with segments: one counter array serves both
     uint32_t segs_per_blk; // blocks are this many whole segments (0: they are not; the streaming pass counts blocks too)
+    uint32_t rep_shift;    // ... then with 2^rep_shift counters to a block, one per streaming workgroup in turn
     size_t slot_tab;
     uint32_t pool_extra; // staging pairs handed out in proportion to the last counts
     uint32_t slots;      // staging slots every wave tile always has
@@ -214,18 +214,23 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap, bool with
         while (!groups_fit(L.n_tiles, L.seg_shift)) ++L.seg_shift;  // 64 tiles per segment always fit
     }
     // Blocks that are whole segments are not counted by the streaming pass: the control
-    // workgroup adds their segments up.  A block of exactly one segment shares its counter.
+    // workgroup adds their segments up.
     {
         const uint64_t seg_elems = (uint64_t)kTile << L.seg_shift;
         L.segs_per_blk = c->block_size % seg_elems == 0 ? (uint32_t)(c->block_size / seg_elems) : 0u;
-        L.one_counter  = L.segs_per_blk == 1;
+        // Other blocks are counted by the streaming pass itself.  Large ones get several
+        // counters, used by consecutive workgroups in turn, so that about four tiles add to one.
+        L.rep_shift = 0;
+        if (!L.segs_per_blk)
+            while (L.rep_shift < 4 && ((uint64_t)4 * kTile << L.rep_shift) < c->block_size) ++L.rep_shift;
     }
     L.n_segs   = (L.n_tiles + (1u << L.seg_shift) - 1) >> L.seg_shift;
     // few entries make the table quick to build; every level below it costs one more lookup
     L.grp_shift = L.n_segs > 4096 ? 4 : L.n_segs > 1024 ? 2 : 0;
     L.n_groups = (L.n_segs + (1u << L.grp_shift) - 1) >> L.grp_shift;
     // the placement reads counters 16 and 64 at a time: arrays are padded with zeros that nothing writes
-    L.blk_stride = align_up(n_b, 64);
+    L.blk_stride = align_up(n_b << L.rep_shift, 64);
+    L.out_stride = align_up(n_b, 64);
     L.seg_stride = align_up(std::max<size_t>(L.n_segs, (size_t)n_b * L.segs_per_blk), 64);  // whole blocks' worth
     L.tile_pad   = align_up(L.n_tiles, 1024);  // whole groups of segments (at most 16 x 64 tiles)
     size_t off = 0;
@@ -235,6 +240,7 @@ Layout make_layout(const exdyna_config *c, uint64_t n_b, uint64_t cap, bool with
     L.part_cnt  = take(P * sizeof(uint64_t));
     L.part_off  = take((P + 1) * sizeof(uint64_t));
     L.blk_cnt   = take(2 * L.blk_stride * sizeof(uint32_t));  // two alternating counter arrays
+    L.blk_out   = take(2 * L.out_stride * sizeof(uint32_t));  // the per-block counts as the getters see them
     L.seg_cnt   = take(2 * L.seg_stride * sizeof(uint32_t));  // likewise
     L.tile_cnt  = take(L.tile_pad * sizeof(uint32_t));
     L.err_slots = take(2 * 2 * kErrSlots * sizeof(double));   // per parity: unselected, then left-behind selected
@@ -325,6 +331,15 @@ template <typename T> T *at(exdyna_ctx *c, size_t off) { return reinterpret_cast
 int32_t *slot_part(exdyna_ctx *c, uint64_t slot) { return at<int32_t>(c, c->lay.parts) + (slot & 1) * 2 * c->cfg.n_parts; }
 int32_t *slot_pos(exdyna_ctx *c, uint64_t slot) { return slot_part(c, slot) + c->cfg.n_parts; }
 uint32_t *blk_cnt_of(exdyna_ctx *c, uint64_t t) { return at<uint32_t>(c, c->lay.blk_cnt) + (t & 1) * c->lay.blk_stride; }
+uint32_t *seg_cnt_of(exdyna_ctx *c, uint64_t t);
+// Where iteration t's per-block counts are: the counters themselves when a block has exactly one
+// (its own, or its one segment's), else the sums the control workgroup stores.
+uint32_t *blk_out_of(exdyna_ctx *c, uint64_t t)
+{
+    if (c->lay.segs_per_blk == 1) return seg_cnt_of(c, t);
+    if (c->lay.segs_per_blk == 0 && c->lay.rep_shift == 0) return blk_cnt_of(c, t);
+    return at<uint32_t>(c, c->lay.blk_out) + (t & 1) * c->lay.out_stride;
+}
 double *err_slots_of(exdyna_ctx *c, uint64_t t) { return at<double>(c, c->lay.err_slots) + (t & 1) * 2 * kErrSlots; }
 
 uint2 *slot_tab_of(exdyna_ctx *c, uint64_t t) { return at<uint2>(c, c->lay.slot_tab) + (t & 1) * c->lay.n_tiles; }
@@ -345,9 +360,10 @@ void launch_stream(exdyna_ctx *c, const void *g, float eta, hipStream_t s)
     A.slot_tab = slot_tab_of(c, c->t);
     A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
     A.blk_cnt = blk_cnt_of(c, c->t);
-    A.seg_cnt = c->lay.one_counter ? blk_cnt_of(c, c->t) : seg_cnt_of(c, c->t);
+    A.seg_cnt = seg_cnt_of(c, c->t);
     A.seg_shift = c->lay.seg_shift;
     A.seg_only = c->lay.segs_per_blk != 0;
+    A.rep_shift = c->lay.rep_shift;
     A.err_slots = err_slots_of(c, c->t);
     A.n_g = (uint32_t)c->cfg.n_g;
     A.n_tiles = (uint32_t)c->lay.n_tiles;
@@ -380,10 +396,18 @@ FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
     A.pack_off = c->lay.pool_extra <= kMaxPackedExtra;
     A.slots_min = c->lay.slots;
     A.tile_cnt = at<uint32_t>(c, c->lay.tile_cnt);
-    A.blk_cnt = blk_cnt_of(c, t);
-    A.seg_cnt = c->lay.one_counter ? blk_cnt_of(c, t) : seg_cnt_of(c, t);
-    A.blk_cnt_next = blk_cnt_of(c, t + 1);
-    A.seg_cnt_next = c->lay.one_counter ? blk_cnt_of(c, t + 1) : seg_cnt_of(c, t + 1);
+    A.seg_cnt = seg_cnt_of(c, t);
+    A.seg_cnt_next = seg_cnt_of(c, t + 1);
+    if (c->lay.segs_per_blk) {  // a block's count: the sum of its segments' counters
+        A.blk_src = A.seg_cnt;
+        A.blk_clear = nullptr;  // the placement clears the segment counters
+        A.per_blk = c->lay.segs_per_blk;
+    } else {                    // ... or of its own counters
+        A.blk_src = blk_cnt_of(c, t);
+        A.blk_clear = blk_cnt_of(c, t + 1);
+        A.per_blk = 1u << c->lay.rep_shift;
+    }
+    A.blk_out = blk_out_of(c, t);
     A.cur_part = slot_part(c, t);
     A.cur_pos = slot_pos(c, t);
     A.nxt_part = slot_part(c, t + 1);
@@ -396,7 +420,6 @@ FinishArgs finish_args(exdyna_ctx *c, uint32_t mode)
     A.err_slots_next = err_slots_of(c, t + 1);
     A.n_tiles = (uint32_t)c->lay.n_tiles;
     A.n_segs = (uint32_t)c->lay.n_segs;
-    A.segs_per_blk = c->lay.one_counter ? 0u : c->lay.segs_per_blk;
     A.n_groups = (uint32_t)c->lay.n_groups;
     A.search_step = 0;  // largest power of two <= n_groups - 1: the first stride of the offset search
     for (uint32_t p2 = 1; p2 < A.n_groups; p2 <<= 1) A.search_step = p2;
@@ -834,7 +857,7 @@ int exdyna_get_block_counts(exdyna_ctx *c, uint32_t *h_counts)
     if (!ctx_ok(c)) return c ? EXDYNA_ESTATE : EXDYNA_ENULL;
     if (!h_counts) return EXDYNA_ENULL;
     if (!have_iteration(c)) return EXDYNA_ESTATE;
-    HIP_TRY(c, hipMemcpyAsync(h_counts, blk_cnt_of(c, last_iteration(c)), c->n_b * sizeof(uint32_t),
+    HIP_TRY(c, hipMemcpyAsync(h_counts, blk_out_of(c, last_iteration(c)), c->n_b * sizeof(uint32_t),
                               hipMemcpyDeviceToHost, c->stream));
     HIP_TRY(c, hipStreamSynchronize(c->stream));
     return EXDYNA_OK;

@@ -15,9 +15,11 @@ struct FinishArgs {
     const uint2    *slot_tab;        // this iteration's {offset in the extra part, slots | bits} per tile
     uint2          *slot_tab_next;   // the next iteration's, written here
     const uint32_t *tile_cnt;
-    uint32_t       *blk_cnt;         // this iteration's per-block counts: complete, or written here from the segment counters
+    const uint32_t *blk_src;         // this iteration's counters that make up the block counts: per_blk
+                                     // consecutive ones to a block (its segments' counters, or its own)
+    uint32_t       *blk_clear;       // the other parity's block counters, cleared here (null: they are segment counters)
+    uint32_t       *blk_out;         // receives the per-block counts (for the getters) when per_blk > 1
     const uint32_t *seg_cnt;         // this iteration's per-segment counters (complete)
-    uint32_t       *blk_cnt_next;    // the other parity's counters, cleared here
     uint32_t       *seg_cnt_next;
     const int32_t  *cur_part;        // topology this iteration selected with
     const int32_t  *cur_pos;
@@ -38,7 +40,7 @@ struct FinishArgs {
     uint32_t        sel_rank;        // worker view: the worker whose partition was compared; else kAllParts
     uint32_t        block_size;
     uint32_t        n_parts;
-    uint32_t        segs_per_blk;    // > 1: a block's count is the sum of this many segment counters, written to blk_cnt here
+    uint32_t        per_blk;         // counters per block (>= 1)
 };
 
 // ---- control: workgroup 0 of k_finish (1024 threads) ----
@@ -80,42 +82,50 @@ enum : uint32_t {
 };
 
 // Selected gradients of blocks i0 + 64 q + lane, q < N (index clamped into [.., end) so that
-// every load can be issued at once).  The streaming pass counts per block only when blocks are
-// not whole segments; otherwise a block's count is the sum of its segments' counters: one load
-// of two or four counters when there are that many (the usual cases), all of a trip's loads
-// in flight before the first sum waits for one.
-template <uint32_t N>
+// every load can be issued at once).  A block's count is the sum of per_blk consecutive
+// counters: the counters of its segments when blocks are whole segments, else its own (one per
+// streaming workgroup in turn).  M = per_blk when it is 1, 2, 4, 8 or 16 (one load per block
+// and four counters, all of a trip's loads in flight before the first sum waits for one), 0 for
+// any other number (counter by counter).
+template <uint32_t M, uint32_t N>
 __device__ __forceinline__ void block_counts(const FinishArgs &A, uint32_t i0, uint32_t end, uint32_t lane,
                                              uint32_t (&out)[N])
 {
-    const uint32_t m = A.segs_per_blk;  // workgroup-uniform
-    if (m == 0u) {
+    if (M == 1u) {
 #pragma unroll
         for (uint32_t q = 0; q < N; ++q) {
             const uint32_t i = i0 + q * 64u + lane;
-            out[q] = A.blk_cnt[i < end ? i : 0u];
+            out[q] = A.blk_src[i < end ? i : 0u];
         }
-    } else if (m == 4u) {
-        uint4 raw[N];
-#pragma unroll
-        for (uint32_t q = 0; q < N; ++q) {
-            const uint32_t i = i0 + q * 64u + lane;
-            raw[q] = reinterpret_cast<const uint4 *>(A.seg_cnt)[i < end ? i : 0u];
-        }
-#pragma unroll
-        for (uint32_t q = 0; q < N; ++q) out[q] = (raw[q].x + raw[q].y) + (raw[q].z + raw[q].w);
-    } else if (m == 2u) {
+    } else if (M == 2u) {
         uint2 raw[N];
 #pragma unroll
         for (uint32_t q = 0; q < N; ++q) {
             const uint32_t i = i0 + q * 64u + lane;
-            raw[q] = reinterpret_cast<const uint2 *>(A.seg_cnt)[i < end ? i : 0u];
+            raw[q] = reinterpret_cast<const uint2 *>(A.blk_src)[i < end ? i : 0u];
         }
 #pragma unroll
         for (uint32_t q = 0; q < N; ++q) out[q] = raw[q].x + raw[q].y;
+    } else if (M >= 4u) {
+        constexpr uint32_t V = M / 4u;  // loads of four counters per block
+        uint4 raw[N][V ? V : 1];
+#pragma unroll
+        for (uint32_t q = 0; q < N; ++q) {
+            const uint32_t i = i0 + q * 64u + lane;
+#pragma unroll
+            for (uint32_t v = 0; v < V; ++v)
+                raw[q][v] = reinterpret_cast<const uint4 *>(A.blk_src)[(size_t)(i < end ? i : 0u) * V + v];
+        }
+#pragma unroll
+        for (uint32_t q = 0; q < N; ++q) {
+            out[q] = 0u;
+#pragma unroll
+            for (uint32_t v = 0; v < V; ++v) out[q] += (raw[q][v].x + raw[q][v].y) + (raw[q][v].z + raw[q][v].w);
+        }
     } else {
-        // any other number of segments per block: the blocks side by side, segment by segment
-        // (the counter arrays are padded with zeros to whole blocks)
+        // any other number: the blocks side by side, counter by counter (the arrays are padded
+        // with zeros to whole blocks)
+        const uint32_t m = A.per_blk;
 #pragma unroll
         for (uint32_t q = 0; q < N; ++q) out[q] = 0u;
         for (uint32_t j = 0; j < m; ++j) {
@@ -123,7 +133,7 @@ __device__ __forceinline__ void block_counts(const FinishArgs &A, uint32_t i0, u
 #pragma unroll
             for (uint32_t q = 0; q < N; ++q) {
                 const uint32_t i = i0 + q * 64u + lane;
-                raw[q] = A.seg_cnt[(size_t)(i < end ? i : 0u) * m + j];
+                raw[q] = A.blk_src[(size_t)(i < end ? i : 0u) * m + j];
             }
 #pragma unroll
             for (uint32_t q = 0; q < N; ++q) out[q] += raw[q];
@@ -131,12 +141,29 @@ __device__ __forceinline__ void block_counts(const FinishArgs &A, uint32_t i0, u
     }
 }
 
+// Zeroes block i's counters of the other parity.
+template <uint32_t M>
+__device__ __forceinline__ void clear_block(const FinishArgs &A, uint32_t i)
+{
+    if (M == 1u) {
+        A.blk_clear[i] = 0u;
+    } else if (M == 2u) {
+        reinterpret_cast<uint2 *>(A.blk_clear)[i] = make_uint2(0u, 0u);
+    } else if (M >= 4u) {
+#pragma unroll
+        for (uint32_t v = 0; v < M / 4u; ++v)
+            reinterpret_cast<uint4 *>(A.blk_clear)[(size_t)i * (M / 4u) + v] = make_uint4(0u, 0u, 0u, 0u);
+    } else {
+        for (uint32_t j = 0; j < A.per_blk; ++j) A.blk_clear[(size_t)i * A.per_blk + j] = 0u;
+    }
+}
+
 // k_{p,t} from the per-block counts (Sec. 4.2: the workload of a partition).
-// Each wave takes a contiguous run of the blocks, 64 at a time; its first
-// slices are requested before anything waits on memory.  Also clears the other
-// parity's block counters and norm partials for the next iteration (or, when the
-// block counts are sums of segment counters, stores them for the getters).
-__device__ __forceinline__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S)
+// Each wave takes a contiguous run of the blocks, 64 at a time; a trip's slices are requested
+// before anything waits on memory.  Also stores the block counts for the getters and clears
+// the other parity's block counters and norm partials for the next iteration.
+template <uint32_t M>
+__device__ __forceinline__ void control_counts_impl(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S)
 {
     constexpr uint32_t kWaves = kFinishWG / 64;
     const uint32_t tid  = threadIdx.x;
@@ -148,9 +175,10 @@ __device__ __forceinline__ void control_counts(const FinishArgs &A, const CtrlPa
     const uint32_t per_wave = (n_b + kWaves - 1) / kWaves;
     const uint32_t beg      = wave * per_wave < n_b ? wave * per_wave : n_b;
     const uint32_t end      = beg + per_wave < n_b ? beg + per_wave : n_b;
-    constexpr uint32_t kAhead = 12;  // 768 blocks per wave and trip: one trip up to 12288 blocks
+    // slices per trip: 768 blocks per wave (12288 per trip of the workgroup), fewer when a block has many counters
+    constexpr uint32_t kAhead = M == 8u ? 6u : M == 16u ? 3u : 12u;
     uint32_t cbuf[kAhead];
-    block_counts(A, beg, end, lane, cbuf);
+    block_counts<M>(A, beg, end, lane, cbuf);
     if (tid < P) {
         S.cnt[tid]   = 0u;
         S.lpos[tid]  = A.cur_pos[tid];
@@ -174,17 +202,15 @@ __device__ __forceinline__ void control_counts(const FinishArgs &A, const CtrlPa
         uint32_t next_start = pcur + 1 < P ? (uint32_t)S.lpos[pcur + 1] : 0xFFFFFFFFu;
         uint32_t acc        = 0;  // this lane's share of partition pcur so far
         for (uint32_t i0 = beg; i0 < end; i0 += kAhead * 64u) {
-            if (i0 != beg) block_counts(A, i0, end, lane, cbuf);
+            if (i0 != beg) block_counts<M>(A, i0, end, lane, cbuf);
 #pragma unroll
             for (uint32_t q = 0; q < kAhead; ++q) {
                 const uint32_t s0 = i0 + q * 64u;  // first block of this slice
                 const uint32_t i  = s0 + lane;
                 uint32_t c = i < end ? cbuf[q] : 0u;
                 if (i < end) {
-                    if (A.segs_per_blk)
-                        A.blk_cnt[i] = c;       // the block's count, for the getters
-                    else
-                        A.blk_cnt_next[i] = 0u;  // clean block counters for the next iteration
+                    if (M != 1u) A.blk_out[i] = c;         // the block's count, for the getters (one counter per block: it is the count)
+                    if (A.blk_clear) clear_block<M>(A, i);  // clean block counters for the next iteration
                 }
                 while (next_start < s0 + 64u && next_start < end) {  // the slice reaches the next partition
                     acc += i < next_start ? c : 0u;
@@ -202,6 +228,18 @@ __device__ __forceinline__ void control_counts(const FinishArgs &A, const CtrlPa
         if (lane == 0 && acc) atomicAdd(&S.cnt[pcur], acc);
     }
     __syncthreads();
+}
+
+__device__ __forceinline__ void control_counts(const FinishArgs &A, const CtrlParams &prm, CtrlShared &S)
+{
+    switch (A.per_blk) {  // workgroup-uniform
+    case 1u: control_counts_impl<1>(A, prm, S); break;
+    case 2u: control_counts_impl<2>(A, prm, S); break;
+    case 4u: control_counts_impl<4>(A, prm, S); break;
+    case 8u: control_counts_impl<8>(A, prm, S); break;
+    case 16u: control_counts_impl<16>(A, prm, S); break;
+    default: control_counts_impl<0>(A, prm, S); break;
+    }
 }
 
 // Everything that follows from the per-partition counts in S.cnt (S.lpos /

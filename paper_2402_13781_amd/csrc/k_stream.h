@@ -20,7 +20,7 @@ struct StreamArgs {
     uint32_t       *tile_cnt;   // n_tiles: selected in the tile | kFlag (only counted) | kKept (staged, not zeroed)
     uint32_t        slots_min;  // fixed staging slots of every tile
     uint32_t        pack_off;   // the tile word also carries the offset of pairs staged in the extra part
-    uint32_t       *blk_cnt;    // this iteration's per-block counters (zero on entry)
+    uint32_t       *blk_cnt;    // this iteration's per-block counters (zero on entry), 2^rep_shift to a block
     uint32_t       *seg_cnt;    // this iteration's per-segment counters (zero on entry)
     double         *err_slots;  // norm statistic: kErrSlots sums of unselected squares, then
                                 // kErrSlots sums over selected entries left in the residual
@@ -28,8 +28,9 @@ struct StreamArgs {
     uint32_t        gpb_shift;  // log2(gran_per_blk) when it is a power of two, else 32
     uint32_t        seg_shift;  // log2(wave tiles per segment counter), 2..6
     uint32_t        seg_only;   // blocks are whole segments: only the segment counters are added to
-                                // (one segment per block: blk_cnt doubles as seg_cnt; several: the
-                                // finishing kernel sums them into blk_cnt)
+                                // (the finishing kernel sums a block's segments)
+    uint32_t        rep_shift;  // otherwise: a block has 2^rep_shift counters, one per streaming workgroup
+                                // in turn, so that no counter is added to by more than about four tiles
     // worker view (Alg. 1 (Sparsify)): compare only inside the partition that worker sel_rank
     // owns at this iteration (Alg. 3 (cyclic allocation), from the device's own iteration
     // counter); kAllParts = everywhere
@@ -256,17 +257,25 @@ k_stream(StreamArgs A)
                     if (nib[u] & 8u) left_selected(a[u].w, left, left_nf);
                 }
             }
+            // (adds to one address serialise at the memory side, and a wavefront does not retire
+            // before its add has returned: up to four tiles per counter -- the tiles of one
+            // workgroup -- cost next to nothing, sixteen cost 4 % of the pass)
+            const uint32_t rep = (tile >> 2) & ((1u << A.rep_shift) - 1u);  // this workgroup's counter of a block
             if (GEN) {
+                const uint32_t first = gran0 << 8;
+                const uint32_t last  = first + kTile - 1u < A.n_g ? first + kTile - 1u : A.n_g - 1u;
+                const uint32_t b_lo = first / A.block_size, b_hi = last / A.block_size;  // wave-uniform
+                if (b_lo == b_hi) {  // the whole tile inside one block: one add
+                    if (lane == 0) atomicAdd(&A.blk_cnt[(b_lo << A.rep_shift) + rep], total);
+                } else {
 #pragma unroll
-                for (uint32_t u = 0; u < kTileGran; ++u)
-                    if (nib[u])
-                        atomicAdd(&A.blk_cnt[(((gran0 + u) << 8) + lane * 4u) / A.block_size],
-                                  (uint32_t)__popc(nib[u]));
+                    for (uint32_t u = 0; u < kTileGran; ++u)
+                        if (nib[u])
+                            atomicAdd(&A.blk_cnt[(((((gran0 + u) << 8) + lane * 4u) / A.block_size) << A.rep_shift) + rep],
+                                      (uint32_t)__popc(nib[u]));
+                }
                 if (lane == 0) atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
             } else if (lane == 0) {
-                // Adds to one address serialise at the memory side, and a wavefront does not
-                // retire before its add has returned: up to four tiles per counter (the tiles
-                // of one workgroup) cost next to nothing, sixteen cost 4 % of the pass.
                 if (A.seg_only) {
                     atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
                 } else {
@@ -277,14 +286,14 @@ k_stream(StreamArgs A)
 #pragma unroll
                     for (uint32_t u = 1; u < kTileGran; ++u) {
                         if (++in_blk == A.gran_per_blk) {  // granule gran0 + u starts the next block
-                            if (run) atomicAdd(&A.blk_cnt[blk], run);
+                            if (run) atomicAdd(&A.blk_cnt[(blk << A.rep_shift) + rep], run);
                             ++blk;
                             in_blk = 0;
                             run = 0;
                         }
                         run += cu[u];
                     }
-                    if (run) atomicAdd(&A.blk_cnt[blk], run);
+                    if (run) atomicAdd(&A.blk_cnt[(blk << A.rep_shift) + rep], run);
                     atomicAdd(&A.seg_cnt[tile >> A.seg_shift], total);
                 }
             }

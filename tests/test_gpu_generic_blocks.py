@@ -30,6 +30,29 @@ def test_generic_block_sizes_bit_exact(n_g, b, P, d):
     x.close()
 
 
+# Blocks of many tiles that are not whole segments are counted by the streaming pass with
+# several counters to a block (2, 4, 8, 16), which the control workgroup adds up; a tile inside
+# one block adds once, a tile across a boundary lane by lane.
+@pytest.mark.parametrize("b,P,d", [
+    (5120, 7, 0.004),       # multiple of 256: counted per granule run, 2 counters per block
+    (16640, 4, 0.01),       # 65 granules, 8 counters
+    (8224, 5, 0.004),       # 257 x 32, 4 counters
+    (16352, 3, 0.001),      # Alg. 2's own size for 138,357,544 gradients in 8445 blocks; 4 counters
+    (16416, 4, 0.02),       # 513 x 32, 8 counters
+    (33056, 2, 0.004),      # 1033 x 32, 16 counters
+    (70000 - 70000 % 32, 2, 0.004),   # more than 64 tiles: 16 counters
+])
+def test_large_blocks_that_are_not_whole_segments(b, P, d):
+    n_g = b * 11 + 5000 + 3
+    w = synthetic.WORKLOADS[5].scaled(n_g, b, P)
+    src = synthetic.GradientSource(w, DEV)
+    thr = synthetic.initial_threshold(src.grad(0), d)
+    log(f"case large generic n_g={n_g} b={b} P={P} d={d}")
+    x, o = make_pair(n_g, b, P, d, thr, want_err_norm=1, blk_move=1)
+    run_trajectory(x, o, (src.grad(t) for t in range(8)), tag=f"b={b}", check_norm=True)
+    x.close()
+
+
 def test_block_size_from_alg2_is_usable():
     """n_b = 100 blocks asked for, block size by Alg. 2 (block size) with the paper's multiple of 32."""
     n_g = 123_457

@@ -42,6 +42,21 @@ def test_small_trajectories_bit_exact(n_g, b, P, d):
     x.close()
 
 
+# Blocks of several whole segments (a segment is a streaming workgroup's 4096 gradients): the
+# streaming pass counts per segment only and the control workgroup adds a block's segments up --
+# two and four with one load, any other number one by one.  The last block is short, and the
+# skew gives Alg. 3 blocks to move.
+@pytest.mark.parametrize("b,P", [(8192, 5), (12288, 4), (16384, 6), (20480, 3), (32768, 2), (16384, 1)])
+def test_blocks_of_whole_segments(b, P):
+    n_g = b * 13 + 4096 * 2 + 333
+    w = synthetic.WORKLOADS[5].scaled(n_g, b, P)
+    log(f"case n_g={n_g} b={b} P={P}")
+    thr = synthetic.initial_threshold(synthetic.GradientSource(w, DEV).grad(0), 0.004)
+    x, o = make_pair(n_g, b, P, 0.004, thr, want_err_norm=1, blk_move=1)
+    run_trajectory(x, o, _grads(w, 8), tag=f"segs-{b}", check_norm=True)
+    x.close()
+
+
 @pytest.mark.parametrize("n_g", [1, 3, 4, 255, 256, 257, 1023, 1024, 1025, 4095, 4097])
 def test_tiny_and_ragged_sizes(n_g):
     rng = np.random.default_rng(n_g)
