@@ -66,8 +66,11 @@ def test_block_size_from_alg2_is_usable():
     x.close()
 
 
-def test_generic_blocks_scaled_16bit_and_worker_view():
-    n_g, b, n, d = 150_000 + 7, 416, 3, 0.01
+# b = 416: boundaries inside wavefront loads; b = 8224 (257 x 32) and 12288 + 256: many tiles to a
+# block with four counters each, partitions that start and end inside a wave tile
+@pytest.mark.parametrize("b", [416, 8224, 12544])
+def test_generic_blocks_scaled_16bit_and_worker_view(b):
+    n_g, n, d = 150_000 + 7, 3, 0.01
     wl = synthetic.WORKLOADS[4].scaled(n_g, b, n)
     src = synthetic.GradientSource(wl, DEV)
     eta = 0.0625
