@@ -58,8 +58,9 @@ typedef struct exdyna_ctx exdyna_ctx; /* opaque, host memory, library-owned */
 typedef struct {
     uint64_t n_g;          /* number of gradients, 1 <= n_g < 2^32 (indices are u32)        */
     uint32_t block_size;   /* b: gradients per block, > 0 and a multiple of 32 (Sec. 4.1,
-                              Alg. 2's rounding).  Multiples of 256 (one wavefront x
-                              float4) take the kernel variant with fewer counter updates   */
+                              Alg. 2's rounding).  Any such size runs at about the same
+                              speed; multiples of 4096 (one streaming workgroup) need no
+                              per-block counters at all                                    */
     uint32_t n_parts;      /* P = number of workers n, 1 <= P <= min(n_b, 1024)             */
     double   density;      /* d in (0, 1]; k = d * n_g is kept in fp64 (Sec. 1)             */
     float    threshold0;   /* delta_0 > 0, finite (Alg. 1, threshold initialisation)        */
