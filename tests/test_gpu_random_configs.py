@@ -1,6 +1,6 @@
 """Seeded random configurations within the documented limits, each run for a few iterations
-against the oracle: sizes, block sizes (any multiple of 32), partition counts up to one block per
-partition, densities from 1e-4 to 0.3, both comparators, all hyper-parameters, small capacities,
+against the oracle: sizes, block sizes (any multiple of 32, from one granule to 70 wave tiles),
+partition counts up to one block per partition, densities from 1e-4 to 0.3, both comparators, all hyper-parameters, small capacities,
 and a mix of plain and learning-rate-fused steps."""
 import numpy as np
 import pytest
@@ -59,6 +59,37 @@ def test_random_configuration(seed):
             x.step_scaled(gb, eta)
             o.step_scaled(gb.view(torch.int16).cpu().numpy().view(np.uint16), 1, eta)
         compare_step(x, o, t, check_norm=True, tag=f"random-{seed}")
+    x.close()
+
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configuration_with_many_tiles_per_block(seed):
+    """Longer vectors with blocks of 4 to 70 wave tiles: blocks of whole segments (1 to 16 of
+    them), and blocks that are not (1 to 16 counters each, generic sizes included); uneven load,
+    small capacities, dense and sparse selections."""
+    rng = np.random.default_rng(9000 + seed)
+    b = int(rng.choice([4096, 8192, 12288, 16384, 20480, 65536, 4096 + 256, 8192 + 512, 16384 + 256,
+                        32768 + 1024, 5120 + 32, 8224, 16352, 16416, 33056, 71648]))
+    n_b = int(rng.integers(3, 40))
+    n_g = int(b * (n_b - 1) + rng.integers(1, b + 1))
+    P = int(min(n_b, rng.choice([1, 2, 3, 5, 8, n_b])))
+    d = float(rng.choice([2e-4, 1e-3, 0.004, 0.02, 0.2]))
+    kw = dict(cmp_mode=int(rng.integers(0, 2)), alpha=float(rng.choice([1.0, 1.2])),
+              gamma=float(rng.choice([0.01, 0.05, 0.3])), blk_move=int(rng.choice([0, 1, 2])),
+              min_blk=1, max_selected=int(rng.choice([0, 0, max(1, n_g // 500), n_g])), want_err_norm=1)
+    hot = int(rng.integers(0, n_g + 1)) if rng.random() < 0.7 else 0
+    g0 = rng.laplace(0, 1.0, n_g).astype(np.float32)
+    thr = float(np.quantile(np.abs(g0), 1.0 - d))
+    log(f"case tiles-per-block seed={seed} n_g={n_g} b={b} P={P} d={d} hot={hot} {kw}")
+    x, o = make_pair(n_g, b, P, d, thr, **kw)
+    for t in range(5):
+        g = g0 if t == 0 else rng.laplace(0, 1.0, n_g).astype(np.float32)
+        if hot:
+            g = g.copy()
+            g[:hot] *= 4.0
+        x.step(torch.from_numpy(g).to(DEV))
+        o.step(g)
+        compare_step(x, o, t, check_norm=True, tag=f"tiles-per-block-{seed}")
     x.close()
 
 
