@@ -75,6 +75,19 @@ def band_entry(rows, k, beta):
     return first, last_out
 
 
+def caught_up(rows, k, beta):
+    """First iteration after the first from which k'/k <= beta: the threshold has caught up with
+    the residual build-up and Alg. 5 stops taking its coarse step up (k' may then swing across
+    the band for a while without landing inside it).  None if it never does."""
+    grown = False
+    for r in rows:
+        ratio = r["k_actual"] / k
+        grown = grown or ratio > beta
+        if grown and ratio <= beta:
+            return r["t"]
+    return None
+
+
 def main(argv=None) -> int:
     from . import synthetic
 
@@ -98,7 +111,8 @@ def main(argv=None) -> int:
     beta = binding.default_config().beta
     first, last_out = band_entry(rows, w.density * w.n_g, beta)
     print(f"# k'/k first within (1/{beta:g}, {beta:g}] at iteration {first}; last iteration outside: "
-          f"{last_out} of {len(rows)}", file=sys.stderr)
+          f"{last_out} of {len(rows)}; back to k'/k <= {beta:g} after the build-up at iteration "
+          f"{caught_up(rows, w.density * w.n_g, beta)}", file=sys.stderr)
     return 0
 
 
